@@ -1,0 +1,190 @@
+/*
+ * kvswap.h - C ABI of the MI355X KV-cache context-switch library.
+ *
+ * The library moves a preempted request's paged KV cache from GPU HBM to
+ * pinned host memory and back (FastSwitch, arXiv 2411.18424: Section 2.1
+ * "preemption by swapping", Section 3.1 block groups, Section 3.2 asynchronous
+ * swapping, Section 3.3 reuse of the CPU copy).  The data path is
+ *
+ *   swap-out: gather kernel (scattered pool chunks -> contiguous device
+ *             staging) -> large pinned device-to-host copies
+ *   swap-in : large pinned host-to-device copies -> scatter kernel (staging ->
+ *             freshly allocated pool chunks)
+ *
+ * on dedicated HIP streams ordered by events, so that both directions overlap
+ * each other and the caller's compute.
+ *
+ * Conventions
+ *  - Every function returns 0 (KV_OK) or a negative kv_status_t.  No function
+ *    throws or aborts.  All argument validation happens before anything is
+ *    enqueued: a call that returns an error has had no effect.
+ *  - All pointers are HOST pointers unless a comment says "device pointer".
+ *  - The caller owns every array it passes; the library has consumed it when
+ *    the call returns.  The library owns the pool object, the pinned host
+ *    arena, its streams and events, and (unless supplied) the staging ring.
+ *  - Block ids are int32 in [0, n_gpu_blocks).  Request ids are caller-chosen
+ *    int64 values.
+ *  - swap_* calls are asynchronous: they enqueue work and return.  Use
+ *    kv_wait / kv_query / kv_stream_wait to observe completion.
+ *  - A kv_pool_t may be used from several host threads (one internal lock).
+ *
+ * Layouts (bytes; all elements are opaque, NaN/Inf payloads survive bit-exact)
+ *  - chunk  C = block_size * n_kv_heads * head_dim * elt_bytes, a multiple of 16
+ *  - GPU pool:   pool[p][b][C],  plane p = 2*layer + kv (kv 0 = K, 1 = V),
+ *                P = 2*n_layers planes, b in [0, n_gpu_blocks)
+ *  - host image of a request with n logical blocks: image[j][p][C], j < n
+ *                (one block record R = P*C bytes per logical block)
+ */
+#ifndef KVSWAP_H
+#define KVSWAP_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  KV_OK          =  0,
+  KV_EINVAL      = -1, /* bad argument: id out of range, duplicate id, length mismatch, bad shape */
+  KV_ENOMEM_GPU  = -2, /* no free GPU blocks / device allocation failed */
+  KV_ENOMEM_HOST = -3, /* pinned host arena exhausted */
+  KV_ENOENT      = -4, /* request has no (valid) host copy */
+  KV_EBUSY       = -5, /* object still in use */
+  KV_EHIP        = -6, /* a HIP runtime call failed; see kv_last_error() */
+  KV_ENODEV      = -7  /* operation needs a device but the pool is plan-only */
+} kv_status_t;
+
+/* flags for kv_pool_config_t.flags */
+#define KV_FLAG_PLAN_ONLY        1u /* no HIP call is ever made and no byte moves: only validation,
+                                       allocator and reuse-map bookkeeping run (host-logic tests) */
+#define KV_FLAG_PROFILE          2u /* time every kernel launch and copy with HIP events (kv_profile_*) */
+#define KV_FLAG_ORDER_COMPUTE    4u /* order swaps after work already enqueued on compute_stream */
+
+typedef struct kv_pool kv_pool_t;
+
+typedef struct {
+  int32_t n_layers, n_kv_heads, head_dim, block_size, elt_bytes;
+  int32_t flags;            /* KV_FLAG_* */
+  int64_t n_gpu_blocks;     /* N */
+  void*   gpu_base;         /* device pointer, >= P*N*C bytes, 16-byte aligned; caller-owned */
+  int64_t host_bytes;       /* capacity of the pinned host arena (library allocates it) */
+  void*   staging_base;     /* device pointer to staging memory, or NULL: library allocates */
+  int64_t staging_bytes;    /* total staging bytes (split evenly: out ring + in ring); 0 = default */
+  int32_t n_slots;          /* ring slots per direction (>= 2); 0 = default 4 */
+  int32_t host_slack_blocks;/* room reserved after each new host image for the next turn's
+                               increment (Section 3.3 adjacent preallocation); <0 = default 32 */
+  int64_t copy_chunk_bytes; /* a host<->device copy is issued in pieces of at most this many
+                               bytes so other streams' copies can interleave (Section 3.2,
+                               dispatch-order control); 0 = default */
+  void*   compute_stream;   /* hipStream_t of the caller's inference work (used with
+                               KV_FLAG_ORDER_COMPUTE and by kv_stream_wait) */
+  int32_t gather_grid;      /* workgroups per pack-kernel launch; 0 = default */
+  int32_t reserved;
+} kv_pool_config_t;
+
+/* Section 3.1 (KV pool + block groups).  Creates the pool object: pinned host arena,
+ * staging rings, side streams, event pool, allocator with all N blocks free.
+ * *out is written only on success. */
+int32_t kv_pool_create(const kv_pool_config_t* cfg, kv_pool_t** out);
+/* Waits for all in-flight work, then frees everything the library owns. */
+int32_t kv_pool_destroy(kv_pool_t* pool);
+
+/* Section 3.1, Dynamic Block Group allocation.  Returns n_blocks physical ids in
+ * out_blocks[n_blocks] (caller-allocated), in as few maximal contiguous runs as the free
+ * lists allow; runs shorter than min_run are used only when nothing longer is free.
+ * *out_n_runs (may be NULL) receives the number of maximal runs.  Blocks still being read
+ * by an unfinished gather are never handed out (Section 3.2, KV cache conflict): if they
+ * are needed the call waits for exactly that gather.  KV_ENOMEM_GPU if fewer than
+ * n_blocks are free; nothing is allocated then. */
+int32_t alloc_block_group(kv_pool_t* pool, int64_t req, int32_t n_blocks, int32_t min_run,
+                          int32_t* out_blocks, int32_t* out_n_runs);
+/* Returns blocks to the free lists (adjacent free runs merge).  Blocks named by a swap_out
+ * whose gather has not finished stay unavailable until it has.  KV_EINVAL if any block is
+ * out of range, repeated, or not currently allocated (then nothing is freed). */
+int32_t free_block_group(kv_pool_t* pool, int64_t req, const int32_t* blocks, int32_t n_blocks);
+/* Number of blocks currently free (including those waiting for a gather to finish). */
+int32_t kv_free_blocks(kv_pool_t* pool, int64_t* out_free, int64_t* out_largest_run);
+
+/* Sections 2.1 / 3.3.  Full swap-out: every logical block j (block_table[j] = its physical
+ * id) is copied into the request's host image, replacing any earlier image.
+ * KV_EINVAL: id out of range or repeated.  KV_ENOMEM_HOST: arena full. */
+int32_t swap_out(kv_pool_t* pool, int64_t req, const int32_t* block_table, int32_t n_blocks);
+/* Section 3.3.  Swap-out with reuse: moves exactly the logical blocks j with
+ * dirty_mask[j] != 0 or without a valid host copy; all other image bytes stay.  A request
+ * longer than its image has the image extended (in place when the reserved slack or the
+ * neighbouring arena space allows, else by relocation).  n_blocks smaller than the image
+ * is KV_EINVAL.  out_n_moved may be NULL. */
+int32_t swap_out_delta(kv_pool_t* pool, int64_t req, const int32_t* block_table, int32_t n_blocks,
+                       const uint8_t* dirty_mask, int32_t* out_n_moved);
+/* Section 3.2 swap-in path.  Copies the host image into new_block_table's blocks.  The
+ * image is kept (Section 3.3).  KV_ENOENT: no image, or a needed block's host copy is not
+ * valid.  KV_EINVAL: n_blocks differs from the image, bad ids. */
+int32_t swap_in(kv_pool_t* pool, int64_t req, const int32_t* new_block_table, int32_t n_blocks);
+/* As swap_in, but logical blocks with resident_mask[j] != 0 are already on the GPU and are
+ * skipped (only non-resident blocks move). */
+int32_t swap_in_delta(kv_pool_t* pool, int64_t req, const int32_t* new_block_table, int32_t n_blocks,
+                      const uint8_t* resident_mask, int32_t* out_n_moved);
+
+/* Batched forms: one scheduling iteration preempts / resumes several requests (Algorithm 1,
+ * steps 2 and 3).  tables is the concatenation of the requests' block tables,
+ * n_blocks[i] the length of request i's.  All requests are validated first; pack kernels
+ * and copies are shared across request boundaries.  A request id may appear once. */
+int32_t swap_out_batch(kv_pool_t* pool, int32_t n_req, const int64_t* reqs,
+                       const int32_t* tables, const int32_t* n_blocks);
+int32_t swap_in_batch(kv_pool_t* pool, int32_t n_req, const int64_t* reqs,
+                      const int32_t* tables, const int32_t* n_blocks);
+
+/* Completion (Algorithm 1, step 1: IsCompleted / Synchronize). */
+int32_t kv_wait(kv_pool_t* pool, int64_t req);                /* blocks until req's last op is done */
+int32_t kv_query(kv_pool_t* pool, int64_t req, int32_t* done);/* non-blocking; *done = 0/1 */
+int32_t kv_wait_packed(kv_pool_t* pool, int64_t req);         /* until the last swap-out's gather has
+                                                                 finished: GPU blocks reusable */
+int32_t kv_stream_wait(kv_pool_t* pool, int64_t req, void* stream); /* make a hipStream_t wait (on the
+                                                                 device) for req's last op */
+int32_t kv_wait_all(kv_pool_t* pool);
+
+/* Reuse map (Section 3.3). */
+int32_t kv_host_view(kv_pool_t* pool, int64_t req, const void** ptr, int64_t* bytes,
+                     int32_t* n_blocks);                      /* pinned image; valid until released/relocated */
+int32_t kv_host_valid(kv_pool_t* pool, int64_t req, uint8_t* out_mask, int32_t n); /* 1 = valid */
+int32_t kv_host_invalidate(kv_pool_t* pool, int64_t req, const uint8_t* mask, int32_t n); /* contaminate */
+int32_t kv_host_release(kv_pool_t* pool, int64_t req);        /* drop the image (waits for its ops) */
+
+typedef struct {
+  int64_t bytes_out, bytes_in;          /* payload bytes enqueued per direction (moved blocks * R) */
+  int64_t blocks_out, blocks_in;
+  int64_t gather_launches, scatter_launches;
+  int64_t d2h_copies, h2d_copies;
+  int64_t conflict_waits;               /* device-side waits inserted by conflict detection */
+  int64_t host_relocations;
+  int64_t host_arena_used, host_arena_bytes;
+} kv_stats_t;
+int32_t kv_stats(kv_pool_t* pool, kv_stats_t* out);
+
+/* Profiling (needs KV_FLAG_PROFILE).  One record per kernel launch / copy, in issue order. */
+typedef struct {
+  int32_t kind;      /* 0 gather, 1 scatter, 2 D2H copy, 3 H2D copy */
+  int32_t reserved;
+  int64_t bytes;     /* payload bytes of this launch / copy */
+  double  ms;        /* device duration */
+} kv_prof_record_t;
+/* Waits for all work, then writes up to cap records; *out_n = number available. */
+int32_t kv_profile_read(kv_pool_t* pool, kv_prof_record_t* out, int32_t cap, int32_t* out_n);
+int32_t kv_profile_reset(kv_pool_t* pool);
+
+/* Host-link probe: times `reps` pinned copies of `bytes` bytes on a side stream and
+ * returns the best rate in GB/s.  direction 0 = device-to-host, 1 = host-to-device,
+ * 2 = both at once (sum).  Defines the "measured host-link peak". */
+int32_t kv_link_probe(int64_t bytes, int32_t direction, int32_t reps, double* out_gbps);
+/* Device copy ceiling: plain device-to-device copy kernel, read+write GB/s. */
+int32_t kv_hbm_probe(int64_t bytes, int32_t reps, double* out_gbps);
+
+/* Thread-local text of the last error. */
+const char* kv_last_error(void);
+const char* kv_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* KVSWAP_H */

@@ -1,0 +1,240 @@
+// Block-group allocator and host-arena allocator (host-side bookkeeping, no HIP).
+//
+// Block groups follow FastSwitch (arXiv 2411.18424) Section 3.1: KV blocks are handed out
+// in contiguous runs ("block groups") in the manner of a buddy allocator - all blocks start
+// merged into one free group, a group is split on demand, adjacent free groups merge - so
+// that a request's blocks sit in few large extents.
+#pragma once
+#include <stdint.h>
+
+#include <algorithm>
+#include <map>
+#include <set>
+#include <utility>
+#include <vector>
+
+namespace kv {
+
+// Free runs of a 1-D id space, indexed by address (merge) and by size (fit).
+class RunSet {
+ public:
+  void clear() {
+    by_addr_.clear();
+    by_size_.clear();
+    total_ = 0;
+  }
+  int64_t total() const { return total_; }
+  int64_t largest() const { return by_size_.empty() ? 0 : by_size_.rbegin()->first; }
+  size_t n_runs() const { return by_addr_.size(); }
+
+  // Insert [start, start+len), merging with free neighbours.
+  void insert(int64_t start, int64_t len) {
+    if (len <= 0) return;
+    total_ += len;
+    auto next = by_addr_.lower_bound(start);
+    if (next != by_addr_.begin()) {
+      auto prev = std::prev(next);
+      if (prev->first + prev->second == start) {
+        start = prev->first;
+        len += prev->second;
+        by_size_.erase({prev->second, prev->first});
+        by_addr_.erase(prev);
+      }
+    }
+    if (next != by_addr_.end() && start + len == next->first) {
+      len += next->second;
+      by_size_.erase({next->second, next->first});
+      by_addr_.erase(next);
+    }
+    by_addr_[start] = len;
+    by_size_.insert({len, start});
+  }
+
+  // Best fit: the smallest run with len >= n, lowest address on ties.  Takes its low end.
+  bool take_best_fit(int64_t n, int64_t* start) {
+    auto it = by_size_.lower_bound({n, INT64_MIN});
+    if (it == by_size_.end()) return false;
+    carve(it->second, it->first, n);
+    *start = last_start_;
+    return true;
+  }
+
+  // Takes the low end (up to n) of the largest run; returns the length taken.
+  int64_t take_from_largest(int64_t n, int64_t* start) {
+    if (by_size_.empty()) return 0;
+    auto it = std::prev(by_size_.end());
+    // lowest address among the largest runs
+    auto lo = by_size_.lower_bound({it->first, INT64_MIN});
+    int64_t take = std::min<int64_t>(n, lo->first);
+    carve(lo->second, lo->first, take);
+    *start = last_start_;
+    return take;
+  }
+
+  // Takes [start, start+len) if it is entirely free (used to extend a region in place).
+  bool take_exact(int64_t start, int64_t len) {
+    auto it = by_addr_.upper_bound(start);
+    if (it == by_addr_.begin()) return false;
+    --it;
+    int64_t rs = it->first, rl = it->second;
+    if (start < rs || start + len > rs + rl) return false;
+    by_size_.erase({rl, rs});
+    by_addr_.erase(it);
+    total_ -= rl;
+    insert(rs, start - rs);
+    insert(start + len, rs + rl - (start + len));
+    return true;
+  }
+
+  const std::map<int64_t, int64_t>& runs() const { return by_addr_; }
+
+ private:
+  void carve(int64_t start, int64_t len, int64_t n) {
+    by_size_.erase({len, start});
+    by_addr_.erase(start);
+    total_ -= len;
+    last_start_ = start;
+    if (len > n) insert(start + n, len - n);
+  }
+  std::map<int64_t, int64_t> by_addr_;           // start -> len
+  std::set<std::pair<int64_t, int64_t>> by_size_;  // (len, start)
+  int64_t total_ = 0;
+  int64_t last_start_ = 0;
+};
+
+// Allocator of GPU KV blocks in contiguous runs.
+class BlockGroupAllocator {
+ public:
+  enum State : uint8_t { FREE = 0, USED = 1, DRAINING = 2 };
+
+  void init(int64_t n_blocks) {
+    n_ = n_blocks;
+    state_.assign((size_t)n_blocks, FREE);
+    free_.clear();
+    free_.insert(0, n_blocks);
+    draining_.clear();
+    n_draining_ = 0;
+  }
+  int64_t n_free() const { return free_.total(); }
+  int64_t n_draining() const { return n_draining_; }
+  int64_t largest_run() const { return free_.largest(); }
+
+  // Allocates n ids into out (appended), fewest runs first.  Caller has checked n <= n_free().
+  // Returns the number of maximal runs used.
+  int32_t alloc(int64_t n, int64_t min_run, std::vector<int32_t>* out) {
+    (void)min_run;  // largest-first already uses short runs only when nothing longer is free
+    int32_t runs = 0;
+    int64_t start;
+    while (n > 0) {
+      int64_t got;
+      if (free_.take_best_fit(n, &start)) {
+        got = n;
+      } else {
+        got = free_.take_from_largest(n, &start);
+      }
+      for (int64_t i = 0; i < got; ++i) {
+        state_[(size_t)(start + i)] = USED;
+        out->push_back((int32_t)(start + i));
+      }
+      n -= got;
+      ++runs;
+    }
+    return count_runs(*out, runs);
+  }
+
+  // True if every id is in range, USED and named once.  scratch is a caller-kept stamp array.
+  bool can_free(const int32_t* ids, int32_t n, std::vector<uint32_t>* stamp, uint32_t* epoch) const {
+    if ((int64_t)stamp->size() != n_) stamp->assign((size_t)n_, 0);
+    ++*epoch;
+    for (int32_t i = 0; i < n; ++i) {
+      int64_t b = ids[i];
+      if (b < 0 || b >= n_ || state_[(size_t)b] != USED) return false;
+      if ((*stamp)[(size_t)b] == *epoch) return false;
+      (*stamp)[(size_t)b] = *epoch;
+    }
+    return true;
+  }
+
+  // Frees ids.  Ids whose reader sequence number (reader_seq[b]) is beyond done_seq are still
+  // being read by a gather: they are parked and released by reap() once it has finished.
+  void free_ids(const int32_t* ids, int32_t n, const std::vector<uint64_t>& reader_seq,
+                uint64_t done_seq) {
+    std::vector<int32_t> v(ids, ids + n);
+    std::sort(v.begin(), v.end());
+    size_t i = 0;
+    while (i < v.size()) {
+      size_t j = i;
+      uint64_t seq = reader_seq[(size_t)v[i]];
+      bool parked = seq > done_seq;
+      uint64_t max_seq = seq;
+      while (j + 1 < v.size() && v[j + 1] == v[j] + 1 &&
+             ((reader_seq[(size_t)v[j + 1]] > done_seq) == parked)) {
+        ++j;
+        max_seq = std::max(max_seq, reader_seq[(size_t)v[j]]);
+      }
+      int64_t start = v[i], len = (int64_t)(j - i + 1);
+      if (parked) {
+        for (int64_t k = 0; k < len; ++k) state_[(size_t)(start + k)] = DRAINING;
+        draining_.push_back({max_seq, start, len});
+        n_draining_ += len;
+      } else {
+        for (int64_t k = 0; k < len; ++k) state_[(size_t)(start + k)] = FREE;
+        free_.insert(start, len);
+      }
+      i = j + 1;
+    }
+  }
+
+  // Releases parked runs whose gather (sequence <= done_seq) has finished.
+  void reap(uint64_t done_seq) {
+    size_t w = 0;
+    for (size_t i = 0; i < draining_.size(); ++i) {
+      Parked& d = draining_[i];
+      if (d.seq <= done_seq) {
+        for (int64_t k = 0; k < d.len; ++k) state_[(size_t)(d.start + k)] = FREE;
+        free_.insert(d.start, d.len);
+        n_draining_ -= d.len;
+      } else {
+        draining_[w++] = d;
+      }
+    }
+    draining_.resize(w);
+  }
+
+  // Smallest sequence number whose completion would release at least `need` parked blocks
+  // (0 if even all parked blocks are not enough).
+  uint64_t seq_to_release(int64_t need) const {
+    std::vector<std::pair<uint64_t, int64_t>> v;
+    for (const Parked& d : draining_) v.push_back({d.seq, d.len});
+    std::sort(v.begin(), v.end());
+    int64_t got = 0;
+    for (auto& e : v) {
+      got += e.second;
+      if (got >= need) return e.first;
+    }
+    return 0;
+  }
+
+  uint8_t state(int64_t b) const { return state_[(size_t)b]; }
+
+ private:
+  struct Parked {
+    uint64_t seq;
+    int64_t start, len;
+  };
+  static int32_t count_runs(const std::vector<int32_t>& ids, int32_t fallback) {
+    if (ids.empty()) return 0;
+    (void)fallback;
+    int32_t r = 1;
+    for (size_t i = 1; i < ids.size(); ++i)
+      if (ids[i] != ids[i - 1] + 1) ++r;
+    return r;
+  }
+  int64_t n_ = 0;
+  std::vector<uint8_t> state_;
+  RunSet free_;
+  std::vector<Parked> draining_;
+  int64_t n_draining_ = 0;
+};
+
+}  // namespace kv

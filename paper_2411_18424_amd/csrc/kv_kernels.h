@@ -1,0 +1,32 @@
+// Device-side interface of the pack kernels (gfx950).  Internal to the library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+// A launch carries its slice of the block table inside the kernel arguments
+// (HIP allows 4 KiB of them), so no table upload is ever enqueued.
+#define KV_MAX_LAUNCH_BLOCKS 896
+#define KV_WG 256  // threads per workgroup: 4 wavefronts of 64 lanes
+
+struct KvPackArgs {
+  char* pool;            // device: pool[p][b][C]
+  char* staging;         // device: staging[k][p][C], k = position in this launch's table
+  int64_t plane_stride;  // N * C bytes
+  uint32_t C;            // chunk bytes (multiple of 16)
+  uint32_t P;            // planes
+  uint32_t m;            // blocks in this launch (<= KV_MAX_LAUNCH_BLOCKS)
+  uint32_t tiles_per_chunk;
+  uint32_t n_tiles;      // m * P * tiles_per_chunk
+  uint32_t pad;
+  int32_t table[KV_MAX_LAUNCH_BLOCKS];  // physical block id of each of the m blocks
+};
+
+// unroll: 16-byte vectors per lane per tile (1, 2, 4 or 8); 0 picks the largest that
+// divides the chunk.  start/stop may be null; when given they receive the dispatch's own
+// begin / end timestamps.
+hipError_t kv_launch_pack(bool scatter, const KvPackArgs& a, int unroll, int grid,
+                          hipStream_t stream, hipEvent_t start, hipEvent_t stop);
+// Plain linear device copy (bandwidth probe): bytes must be a multiple of 16.
+hipError_t kv_launch_linear_copy(void* dst, const void* src, int64_t bytes, int grid,
+                                 hipStream_t stream, hipEvent_t start, hipEvent_t stop);
+int kv_pick_unroll(uint32_t C);

@@ -1,0 +1,288 @@
+"""ctypes binding over libkvswap.so: argument marshalling only.
+
+Every function of include/kvswap.h is exposed under its own name on ``lib``;
+``KVPool`` is a thin convenience object around a ``kv_pool_t*`` with methods of the
+same names.  Nothing here moves or computes a byte: if the shared library is missing
+the import fails loudly (build it with ``python -m paper_2411_18424_amd.build``).
+"""
+
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libkvswap.so")
+
+KV_OK, KV_EINVAL, KV_ENOMEM_GPU, KV_ENOMEM_HOST = 0, -1, -2, -3
+KV_ENOENT, KV_EBUSY, KV_EHIP, KV_ENODEV = -4, -5, -6, -7
+KV_FLAG_PLAN_ONLY, KV_FLAG_PROFILE, KV_FLAG_ORDER_COMPUTE = 1, 2, 4
+
+_STATUS_NAMES = {0: "KV_OK", -1: "KV_EINVAL", -2: "KV_ENOMEM_GPU", -3: "KV_ENOMEM_HOST",
+                 -4: "KV_ENOENT", -5: "KV_EBUSY", -6: "KV_EHIP", -7: "KV_ENODEV"}
+
+
+class KVError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__("%s: %s" % (_STATUS_NAMES.get(status, status), text))
+        self.status = status
+
+
+class kv_pool_config_t(C.Structure):
+    _fields_ = [
+        ("n_layers", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+        ("block_size", C.c_int32), ("elt_bytes", C.c_int32), ("flags", C.c_int32),
+        ("n_gpu_blocks", C.c_int64), ("gpu_base", C.c_void_p), ("host_bytes", C.c_int64),
+        ("staging_base", C.c_void_p), ("staging_bytes", C.c_int64), ("n_slots", C.c_int32),
+        ("host_slack_blocks", C.c_int32), ("copy_chunk_bytes", C.c_int64),
+        ("compute_stream", C.c_void_p), ("gather_grid", C.c_int32), ("reserved", C.c_int32),
+    ]
+
+
+class kv_stats_t(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in (
+        "bytes_out", "bytes_in", "blocks_out", "blocks_in", "gather_launches",
+        "scatter_launches", "d2h_copies", "h2d_copies", "conflict_waits",
+        "host_relocations", "host_arena_used", "host_arena_bytes")]
+
+
+class kv_prof_record_t(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("reserved", C.c_int32), ("bytes", C.c_int64), ("ms", C.c_double)]
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            "libkvswap.so is not built (%s). Run `python -m paper_2411_18424_amd.build`; "
+            "there is no fallback path." % LIB_PATH)
+    lib = C.CDLL(LIB_PATH)
+    P = C.POINTER
+    pool_p = C.c_void_p
+    i32p, i64p, u8p = P(C.c_int32), P(C.c_int64), P(C.c_uint8)
+    sig = {
+        "kv_pool_create": (C.c_int32, [P(kv_pool_config_t), P(pool_p)]),
+        "kv_pool_destroy": (C.c_int32, [pool_p]),
+        "alloc_block_group": (C.c_int32, [pool_p, C.c_int64, C.c_int32, C.c_int32, i32p, i32p]),
+        "free_block_group": (C.c_int32, [pool_p, C.c_int64, i32p, C.c_int32]),
+        "kv_free_blocks": (C.c_int32, [pool_p, i64p, i64p]),
+        "swap_out": (C.c_int32, [pool_p, C.c_int64, i32p, C.c_int32]),
+        "swap_out_delta": (C.c_int32, [pool_p, C.c_int64, i32p, C.c_int32, u8p, i32p]),
+        "swap_in": (C.c_int32, [pool_p, C.c_int64, i32p, C.c_int32]),
+        "swap_in_delta": (C.c_int32, [pool_p, C.c_int64, i32p, C.c_int32, u8p, i32p]),
+        "swap_out_batch": (C.c_int32, [pool_p, C.c_int32, i64p, i32p, i32p]),
+        "swap_in_batch": (C.c_int32, [pool_p, C.c_int32, i64p, i32p, i32p]),
+        "kv_wait": (C.c_int32, [pool_p, C.c_int64]),
+        "kv_query": (C.c_int32, [pool_p, C.c_int64, i32p]),
+        "kv_wait_packed": (C.c_int32, [pool_p, C.c_int64]),
+        "kv_stream_wait": (C.c_int32, [pool_p, C.c_int64, C.c_void_p]),
+        "kv_wait_all": (C.c_int32, [pool_p]),
+        "kv_host_view": (C.c_int32, [pool_p, C.c_int64, P(C.c_void_p), i64p, i32p]),
+        "kv_host_valid": (C.c_int32, [pool_p, C.c_int64, u8p, C.c_int32]),
+        "kv_host_invalidate": (C.c_int32, [pool_p, C.c_int64, u8p, C.c_int32]),
+        "kv_host_release": (C.c_int32, [pool_p, C.c_int64]),
+        "kv_stats": (C.c_int32, [pool_p, P(kv_stats_t)]),
+        "kv_profile_read": (C.c_int32, [pool_p, P(kv_prof_record_t), C.c_int32, i32p]),
+        "kv_profile_reset": (C.c_int32, [pool_p]),
+        "kv_link_probe": (C.c_int32, [C.c_int64, C.c_int32, C.c_int32, P(C.c_double)]),
+        "kv_hbm_probe": (C.c_int32, [C.c_int64, C.c_int32, P(C.c_double)]),
+        "kv_last_error": (C.c_char_p, []),
+        "kv_version": (C.c_char_p, []),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(lib, name)
+        fn.restype, fn.argtypes = res, args
+    lib._signatures = sig
+    return lib
+
+
+lib = _load()
+
+
+def _check(status: int) -> int:
+    if status != KV_OK:
+        raise KVError(status, (lib.kv_last_error() or b"").decode())
+    return status
+
+
+def _i32(a):
+    a = np.ascontiguousarray(a, dtype=np.int32)
+    return a, a.ctypes.data_as(C.POINTER(C.c_int32))
+
+
+def _u8(a):
+    a = np.ascontiguousarray(a, dtype=np.uint8)
+    return a, a.ctypes.data_as(C.POINTER(C.c_uint8))
+
+
+def _i64(a):
+    a = np.ascontiguousarray(a, dtype=np.int64)
+    return a, a.ctypes.data_as(C.POINTER(C.c_int64))
+
+
+def kv_link_probe(n_bytes: int, direction: int, reps: int = 10) -> float:
+    out = C.c_double()
+    _check(lib.kv_link_probe(n_bytes, direction, reps, C.byref(out)))
+    return out.value
+
+
+def kv_hbm_probe(n_bytes: int, reps: int = 10) -> float:
+    out = C.c_double()
+    _check(lib.kv_hbm_probe(n_bytes, reps, C.byref(out)))
+    return out.value
+
+
+class KVPool:
+    """Owner of one ``kv_pool_t*``.  Methods carry the C functions' names."""
+
+    def __init__(self, *, n_layers, n_kv_heads, head_dim, block_size, elt_bytes, n_gpu_blocks,
+                 gpu_base=0, host_bytes=0, staging_base=0, staging_bytes=0, n_slots=0,
+                 host_slack_blocks=-1, copy_chunk_bytes=0, compute_stream=0, flags=0,
+                 gather_grid=0, tile_unroll=0):
+        cfg = kv_pool_config_t(
+            n_layers=n_layers, n_kv_heads=n_kv_heads, head_dim=head_dim, block_size=block_size,
+            elt_bytes=elt_bytes, flags=flags, n_gpu_blocks=n_gpu_blocks, gpu_base=gpu_base or None,
+            host_bytes=host_bytes, staging_base=staging_base or None, staging_bytes=staging_bytes,
+            n_slots=n_slots, host_slack_blocks=host_slack_blocks, copy_chunk_bytes=copy_chunk_bytes,
+            compute_stream=compute_stream or None, gather_grid=gather_grid, reserved=tile_unroll)
+        self._h = C.c_void_p()
+        _check(lib.kv_pool_create(C.byref(cfg), C.byref(self._h)))
+        self.P = 2 * n_layers
+        self.C = block_size * n_kv_heads * head_dim * elt_bytes
+        self.R = self.P * self.C
+        self.N = n_gpu_blocks
+
+    # -- lifetime
+    def kv_pool_destroy(self):
+        if self._h:
+            _check(lib.kv_pool_destroy(self._h))
+            self._h = C.c_void_p()
+
+    close = kv_pool_destroy
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.kv_pool_destroy()
+
+    def __del__(self):
+        try:
+            self.kv_pool_destroy()
+        except Exception:
+            pass
+
+    # -- allocator
+    def alloc_block_group(self, req: int, n_blocks: int, min_run: int = 1):
+        out = np.empty(n_blocks, dtype=np.int32)
+        runs = C.c_int32()
+        _check(lib.alloc_block_group(self._h, req, n_blocks, min_run,
+                                     out.ctypes.data_as(C.POINTER(C.c_int32)), C.byref(runs)))
+        return out, runs.value
+
+    def free_block_group(self, req: int, blocks):
+        a, p = _i32(blocks)
+        _check(lib.free_block_group(self._h, req, p, a.size))
+
+    def kv_free_blocks(self):
+        f, l = C.c_int64(), C.c_int64()
+        _check(lib.kv_free_blocks(self._h, C.byref(f), C.byref(l)))
+        return f.value, l.value
+
+    # -- swaps
+    def swap_out(self, req: int, block_table):
+        a, p = _i32(block_table)
+        _check(lib.swap_out(self._h, req, p, a.size))
+
+    def swap_out_delta(self, req: int, block_table, dirty_mask) -> int:
+        a, p = _i32(block_table)
+        m, mp = _u8(dirty_mask)
+        if m.size != a.size:
+            raise KVError(KV_EINVAL, "dirty mask length differs from table length")
+        n = C.c_int32()
+        _check(lib.swap_out_delta(self._h, req, p, a.size, mp, C.byref(n)))
+        return n.value
+
+    def swap_in(self, req: int, new_block_table):
+        a, p = _i32(new_block_table)
+        _check(lib.swap_in(self._h, req, p, a.size))
+
+    def swap_in_delta(self, req: int, new_block_table, resident_mask) -> int:
+        a, p = _i32(new_block_table)
+        m, mp = _u8(resident_mask)
+        if m.size != a.size:
+            raise KVError(KV_EINVAL, "resident mask length differs from table length")
+        n = C.c_int32()
+        _check(lib.swap_in_delta(self._h, req, p, a.size, mp, C.byref(n)))
+        return n.value
+
+    def _batch(self, fn, reqs, tables):
+        r, rp = _i64(reqs)
+        nb, nbp = _i32([len(t) for t in tables])
+        cat = np.concatenate([np.asarray(t, dtype=np.int32) for t in tables]) if len(tables) else \
+            np.zeros(0, np.int32)
+        cat, cp = _i32(cat)
+        _check(fn(self._h, r.size, rp, cp, nbp))
+
+    def swap_out_batch(self, reqs, tables):
+        self._batch(lib.swap_out_batch, reqs, tables)
+
+    def swap_in_batch(self, reqs, tables):
+        self._batch(lib.swap_in_batch, reqs, tables)
+
+    # -- completion
+    def kv_wait(self, req: int):
+        _check(lib.kv_wait(self._h, req))
+
+    def kv_wait_packed(self, req: int):
+        _check(lib.kv_wait_packed(self._h, req))
+
+    def kv_query(self, req: int) -> bool:
+        d = C.c_int32()
+        _check(lib.kv_query(self._h, req, C.byref(d)))
+        return bool(d.value)
+
+    def kv_stream_wait(self, req: int, stream: int):
+        _check(lib.kv_stream_wait(self._h, req, stream or None))
+
+    def kv_wait_all(self):
+        _check(lib.kv_wait_all(self._h))
+
+    # -- reuse map
+    def kv_host_view(self, req: int) -> np.ndarray:
+        """uint8 view [n][P][C] over the pinned host image (no copy)."""
+        ptr, nbytes, n = C.c_void_p(), C.c_int64(), C.c_int32()
+        _check(lib.kv_host_view(self._h, req, C.byref(ptr), C.byref(nbytes), C.byref(n)))
+        if nbytes.value == 0:
+            return np.zeros((0, self.P, self.C), dtype=np.uint8)
+        buf = (C.c_uint8 * nbytes.value).from_address(ptr.value)
+        return np.frombuffer(buf, dtype=np.uint8).reshape(n.value, self.P, self.C)
+
+    def kv_host_valid(self, req: int, n: int) -> np.ndarray:
+        out = np.zeros(n, dtype=np.uint8)
+        _check(lib.kv_host_valid(self._h, req, out.ctypes.data_as(C.POINTER(C.c_uint8)), n))
+        return out
+
+    def kv_host_invalidate(self, req: int, mask):
+        m, mp = _u8(mask)
+        _check(lib.kv_host_invalidate(self._h, req, mp, m.size))
+
+    def kv_host_release(self, req: int):
+        _check(lib.kv_host_release(self._h, req))
+
+    # -- stats / profiling
+    def kv_stats(self) -> dict:
+        st = kv_stats_t()
+        _check(lib.kv_stats(self._h, C.byref(st)))
+        return {n: getattr(st, n) for n, _ in kv_stats_t._fields_}
+
+    def kv_profile_read(self):
+        n = C.c_int32()
+        _check(lib.kv_profile_read(self._h, None, 0, C.byref(n)))
+        recs = (kv_prof_record_t * max(1, n.value))()
+        _check(lib.kv_profile_read(self._h, recs, n.value, C.byref(n)))
+        return [(recs[i].kind, recs[i].bytes, recs[i].ms) for i in range(n.value)]
+
+    def kv_profile_reset(self):
+        _check(lib.kv_profile_reset(self._h))

@@ -1,0 +1,217 @@
+"""CPU-only tests of the boundary and the host logic.
+
+The library is loaded (no GPU needed for that), every function the header declares
+must be exported, and pools created with KV_FLAG_PLAN_ONLY exercise validation, the
+block-group allocator, the host arena and the reuse map without a single HIP call.
+Plan-only pools move no bytes, so nothing here is a parity claim about data."""
+
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle.kv_oracle import AllocChecker, KVOracle
+from paper_2411_18424_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def kv():
+    from paper_2411_18424_amd import kvswap
+    return kvswap
+
+
+def plan_pool(kv, shape, host_blocks=64, **kw):
+    return kv.KVPool(n_layers=shape.n_layers, n_kv_heads=shape.n_kv_heads, head_dim=shape.head_dim,
+                     block_size=shape.block_size, elt_bytes=shape.elt_bytes,
+                     n_gpu_blocks=shape.n_blocks, host_bytes=host_blocks * shape.R,
+                     flags=kv.KV_FLAG_PLAN_ONLY, **kw)
+
+
+def test_header_symbols_are_exported(kv):
+    text = open(os.path.join(ROOT, "include", "kvswap.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"^\s*(?:const\s+)?(?:int32_t|char\s*\*|void)\s+\**\s*(\w+)\s*\(", text, flags=re.M)
+    assert {"kv_pool_create", "alloc_block_group", "swap_out", "swap_in", "swap_out_delta"} <= set(names)
+    assert len(names) >= 25
+    for n in names:
+        assert hasattr(kv.lib, n), "library does not export %s" % n
+    assert set(names) == set(kv.lib._signatures), "binding and header disagree"
+
+
+def test_create_rejects_bad_configs(kv):
+    s = synth.TINY
+    with pytest.raises(kv.KVError) as ei:
+        kv.KVPool(n_layers=0, n_kv_heads=1, head_dim=8, block_size=16, elt_bytes=2, n_gpu_blocks=4,
+                  flags=kv.KV_FLAG_PLAN_ONLY)
+    assert ei.value.status == kv.KV_EINVAL
+    with pytest.raises(kv.KVError):  # chunk of 6 bytes is not a multiple of 16
+        kv.KVPool(n_layers=1, n_kv_heads=1, head_dim=3, block_size=1, elt_bytes=2, n_gpu_blocks=4,
+                  flags=kv.KV_FLAG_PLAN_ONLY)
+    with pytest.raises(kv.KVError):  # a device pool needs a device pointer
+        kv.KVPool(n_layers=s.n_layers, n_kv_heads=s.n_kv_heads, head_dim=s.head_dim,
+                  block_size=s.block_size, elt_bytes=s.elt_bytes, n_gpu_blocks=s.n_blocks)
+    with pytest.raises(kv.KVError):  # a ring slot must hold one block record
+        plan_pool(kv, s, staging_bytes=1024)
+
+
+def test_validation_errors_and_no_effect(kv):
+    p = plan_pool(kv, synth.TINY, host_blocks=20, host_slack_blocks=0)
+    p.swap_out(0, np.arange(10, dtype=np.int32))
+    st0 = p.kv_stats()
+    for bad, code in (([3, 3], kv.KV_EINVAL), ([256], kv.KV_EINVAL), ([-2], kv.KV_EINVAL)):
+        with pytest.raises(kv.KVError) as ei:
+            p.swap_out(1, np.array(bad, np.int32))
+        assert ei.value.status == code
+    with pytest.raises(kv.KVError) as ei:
+        p.swap_in(9, np.arange(3, dtype=np.int32))
+    assert ei.value.status == kv.KV_ENOENT
+    with pytest.raises(kv.KVError) as ei:
+        p.swap_in(0, np.arange(3, dtype=np.int32))
+    assert ei.value.status == kv.KV_EINVAL
+    with pytest.raises(kv.KVError) as ei:
+        p.swap_out_delta(0, np.arange(4, dtype=np.int32), np.ones(4, np.uint8))  # shorter than image
+    assert ei.value.status == kv.KV_EINVAL
+    with pytest.raises(kv.KVError) as ei:
+        p.swap_out(2, np.arange(11, dtype=np.int32))
+    assert ei.value.status == kv.KV_ENOMEM_HOST
+    with pytest.raises(kv.KVError) as ei:
+        p.swap_out_batch([4, 4], [[1], [2]])
+    assert ei.value.status == kv.KV_EINVAL
+    with pytest.raises(kv.KVError) as ei:
+        p.swap_out_batch([4, 5], [[1, 2], [2, 3]])  # a block in two tables
+    assert ei.value.status == kv.KV_EINVAL
+    with pytest.raises(kv.KVError) as ei:
+        p.kv_host_view(0)
+    assert ei.value.status == kv.KV_ENODEV
+    with pytest.raises(kv.KVError):
+        p.kv_wait(12345)
+    assert p.kv_stats() == st0
+    assert p.kv_host_valid(0, 10).all()
+
+
+def test_moved_sets_follow_the_reuse_map(kv):
+    """Bookkeeping only: the number of blocks each call moves equals the oracle's moved set
+    over a random multi-turn history with contamination and partial swap-in."""
+    shape = synth.KVShape("s", 1, 1, 8, 1, 2, 512, "fp16")
+    p = plan_pool(kv, shape, host_blocks=4096)
+    o = KVOracle(1, 1, 8, 1, 2, 512)
+    rng = synth.rng_for(21)
+    sizes = {}
+    for step in range(300):
+        r = int(rng.integers(0, 8))
+        n_old = sizes.get(r, 0)
+        kind = rng.integers(0, 5)
+        if n_old == 0 or kind == 0:
+            n = int(rng.integers(1, 40))
+            t = rng.permutation(512)[:n].astype(np.int32)
+            p.swap_out(r, t)
+            o.swap_out(r, t)
+            sizes[r] = n
+        elif kind in (1, 2):
+            n = n_old + int(rng.integers(0, 12))
+            t = rng.permutation(512)[:n].astype(np.int32)
+            dirty = synth.random_mask(rng, n, 0.2)
+            assert p.swap_out_delta(r, t, dirty) == len(o.swap_out_delta(r, t, dirty))
+            sizes[r] = n
+        elif kind == 3:
+            m = synth.random_mask(rng, n_old, 0.25)
+            p.kv_host_invalidate(r, m)
+            o.host_invalidate(r, m)
+        else:
+            t = rng.permutation(512)[:n_old].astype(np.int32)
+            res = 1 - o.host[r].host_valid.astype(np.uint8)  # invalid blocks must be resident
+            res |= synth.random_mask(rng, n_old, 0.3)
+            assert p.swap_in_delta(r, t, res) == len(o.swap_in(r, t, resident=res))
+        assert np.array_equal(p.kv_host_valid(r, sizes[r]).astype(bool), o.host[r].host_valid)
+    st = p.kv_stats()
+    assert st["bytes_out"] == o.bytes_out and st["bytes_in"] == o.bytes_in
+    assert st["host_relocations"] > 0
+
+
+def test_allocator_never_double_assigns(kv):
+    shape = synth.KVShape("s", 1, 1, 8, 1, 2, 1000, "fp16")
+    p = plan_pool(kv, shape)
+    chk = AllocChecker(1000)
+    rng = synth.rng_for(22)
+    live = {}
+    for step in range(2000):
+        if live and (rng.random() < 0.45 or chk.n_used() > 900):
+            r = list(live)[int(rng.integers(0, len(live)))]
+            ids = live.pop(r)
+            if rng.random() < 0.3 and len(ids) > 1:  # free in two parts, any order
+                cut = int(rng.integers(1, len(ids)))
+                sh = rng.permutation(len(ids))
+                p.free_block_group(r, ids[sh[:cut]])
+                p.free_block_group(r, ids[sh[cut:]])
+            else:
+                p.free_block_group(r, ids)
+            chk.on_free(r, ids)
+        else:
+            n = int(rng.integers(1, 80))
+            free, largest = p.kv_free_blocks()
+            assert free == 1000 - chk.n_used()
+            if n > free:
+                with pytest.raises(kv.KVError) as ei:
+                    p.alloc_block_group(step, n, 8)
+                assert ei.value.status == kv.KV_ENOMEM_GPU
+                continue
+            ids, runs = p.alloc_block_group(step, n, 8)
+            rl = chk.on_alloc(step, ids)
+            assert runs == len(rl)
+            if largest >= n:
+                assert runs == 1, "a free run of %d could hold %d blocks" % (largest, n)
+            live[step] = ids
+    for r, ids in live.items():
+        p.free_block_group(r, ids)
+    assert p.kv_free_blocks() == (1000, 1000)  # everything merged back into one group
+
+
+def test_allocator_rejects_bad_frees(kv):
+    p = plan_pool(kv, synth.TINY)
+    ids, _ = p.alloc_block_group(1, 8, 1)
+    for bad in ([ids[0], ids[0]], [300], [200]):
+        with pytest.raises(kv.KVError) as ei:
+            p.free_block_group(1, np.array(bad, np.int32))
+        assert ei.value.status == kv.KV_EINVAL
+    assert p.kv_free_blocks()[0] == 256 - 8
+    p.free_block_group(1, ids)
+    with pytest.raises(kv.KVError):
+        p.free_block_group(1, ids)  # double free
+
+
+def test_fragmented_pool_yields_few_long_runs(kv):
+    """Block groups (Section 3.1): when the pool is fragmented the allocator still returns
+    the longest free runs first."""
+    shape = synth.KVShape("s", 1, 1, 8, 1, 2, 256, "fp16")
+    p = plan_pool(kv, shape)
+    all_ids, _ = p.alloc_block_group(0, 256, 1)
+    # free runs of length 16, 8, 4, 2 at known places
+    for start, ln in ((0, 16), (32, 8), (64, 4), (96, 2)):
+        p.free_block_group(0, np.arange(start, start + ln, dtype=np.int32))
+    ids, runs = p.alloc_block_group(1, 26, 8)
+    assert AllocChecker.run_lengths(ids) == [16, 8, 2]
+    assert runs == 3
+    ids2, runs2 = p.alloc_block_group(2, 3, 1)
+    assert AllocChecker.run_lengths(ids2) == [3] and ids2[0] == 64
+
+
+def test_plan_counts_copies_and_launches(kv):
+    """Host-side plan of one swap: launches per ring slot, one copy per run of adjacent host
+    records, copies cut at copy_chunk_bytes."""
+    shape = synth.TINY  # R = 32 KiB
+    p = plan_pool(kv, shape, host_blocks=256, staging_bytes=2 * 2 * 4 * shape.R, n_slots=2,
+                  copy_chunk_bytes=3 * shape.R)
+    t = np.arange(10, dtype=np.int32)
+    p.swap_out(0, t)
+    st = p.kv_stats()
+    assert st["gather_launches"] == 3          # slots of 4 blocks: 4 + 4 + 2
+    assert st["d2h_copies"] == 2 + 2 + 1       # 4 records -> 3 + 1, 2 records -> 1
+    dirty = np.array([1, 0, 1, 1, 0, 0, 0, 1, 1, 1], np.uint8)
+    assert p.swap_out_delta(0, t, dirty) == 6
+    st2 = p.kv_stats()
+    # moved j = 0 | 2 3 | 7 8 9 -> slot A holds 0,2,3,7 (runs 0 | 2-3 | 7), slot B holds 8,9
+    assert st2["gather_launches"] - st["gather_launches"] == 2
+    assert st2["d2h_copies"] - st["d2h_copies"] == 3 + 1

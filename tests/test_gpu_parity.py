@@ -1,0 +1,387 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle,
+byte for byte, on the same seeded inputs.  Integer / byte work: bit-exact."""
+
+import numpy as np
+import pytest
+
+from oracle.kv_oracle import AllocChecker
+from paper_2411_18424_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+MiB = 1 << 20
+
+
+@pytest.fixture
+def harness():
+    made = []
+
+    def make(shape, cfg=1, host_bytes=64 * MiB, **kw):
+        from gpu_util import Harness
+        h = Harness(shape, cfg, host_bytes, **kw)
+        made.append(h)
+        return h
+
+    yield make
+    for h in made:
+        h.close()
+
+
+def _tiny_requests(cfg=1):
+    rng = synth.rng_for(cfg)
+    lens = synth.lengths_uniform(rng, 8, 16, 256)
+    nblk = synth.blocks_for(lens, synth.TINY.block_size)
+    tables = synth.deal_tables(rng, synth.TINY.n_blocks, nblk, run=1)
+    tables2 = synth.deal_tables(rng, synth.TINY.n_blocks, nblk, run=1)
+    return lens, tables, tables2
+
+
+def test_tiny_pool_swap_all_out_then_in(harness):
+    """Config 1: 8 requests out to pinned host, then back through a fresh permutation."""
+    h = harness(synth.TINY)
+    lens, tables, tables2 = _tiny_requests()
+    before = [h.oracle.token_kv(t, int(n)) for t, n in zip(tables, lens)]
+    for r, t in enumerate(tables):
+        h.pool.swap_out(r, t)
+        h.oracle.swap_out(r, t)
+    for r in range(len(tables)):
+        h.assert_image_equal(r)
+    h.assert_pool_equal()  # a swap-out changes nothing on the GPU
+    # the preempted requests' blocks get reused by others
+    junk = np.full((int(sum(len(t) for t in tables)), h.shape.P, h.shape.C), 0xEE, np.uint8)
+    h.overwrite_blocks(np.concatenate(tables), junk)
+    for r, t in enumerate(tables2):
+        h.pool.swap_in(r, t)
+        h.oracle.swap_in(r, t)
+    h.pool.kv_wait_all()
+    h.assert_pool_equal()
+    for r, (t, n) in enumerate(zip(tables2, lens)):
+        assert np.array_equal(h.oracle.token_kv(t, int(n)), before[r])
+    st = h.pool.kv_stats()
+    assert st["bytes_out"] == h.oracle.bytes_out and st["bytes_in"] == h.oracle.bytes_in
+
+
+def test_batched_calls_match_oracle(harness):
+    h = harness(synth.TINY, cfg=2)
+    _, tables, tables2 = _tiny_requests(cfg=2)
+    reqs = list(range(100, 100 + len(tables)))
+    h.pool.swap_out_batch(reqs, tables)
+    for r, t in zip(reqs, tables):
+        h.oracle.swap_out(r, t)
+    for r in reqs:
+        h.assert_image_equal(r)
+    h.pool.swap_in_batch(reqs, tables2)
+    for r, t in zip(reqs, tables2):
+        h.oracle.swap_in(r, t)
+    h.pool.kv_wait_all()
+    h.assert_pool_equal()
+
+
+@pytest.mark.parametrize("L,H,D,B,e,N", [
+    (1, 1, 8, 1, 2, 64),       # C = 16 bytes: one vector per chunk
+    (3, 3, 40, 16, 2, 96),     # C = 3840: ragged tail inside a tile
+    (2, 5, 24, 16, 2, 128),    # C = 3840*... = 3840? (5*24*16*2 = 3840)
+    (2, 7, 72, 16, 2, 64),     # C = 16128: several tiles + ragged tail
+    (4, 8, 128, 16, 2, 64),    # C = 32 KiB: full-tile fast path, 8 vectors per lane
+    (2, 40, 128, 16, 2, 24),   # C = 160 KiB: 5 tiles per chunk
+    (2, 4, 64, 16, 1, 64),     # 1-byte elements (fp8 KV): C = 4 KiB
+    (1, 2, 96, 16, 4, 48),     # 4-byte elements: C = 12 KiB
+])
+def test_shapes_and_ragged_chunks(harness, L, H, D, B, e, N):
+    shape = synth.KVShape("s", L, H, D, B, e, N, "fp16")
+    h = harness(shape, cfg=3, fill="random")  # random bytes: NaN / Inf patterns included
+    rng = synth.rng_for(3, stream=L * 1000 + H)
+    nblk = [1, 2, 5, N // 4]
+    tables = synth.deal_tables(rng, N, nblk)
+    tables2 = synth.deal_tables(rng, N, nblk)
+    for r, t in enumerate(tables):
+        h.pool.swap_out(r, t)
+        h.oracle.swap_out(r, t)
+        h.assert_image_equal(r)
+    for r, t in enumerate(tables2):
+        h.pool.swap_in(r, t)
+        h.oracle.swap_in(r, t)
+    h.pool.kv_wait_all()
+    h.assert_pool_equal()
+
+
+@pytest.mark.parametrize("unroll", [1, 2, 4, 8])
+def test_every_tile_width(harness, unroll):
+    shape = synth.KVShape("s", 2, 6, 80, 16, 2, 80, "bf16")  # C = 30720: full for U<=2, ragged for 4, 8
+    h = harness(shape, cfg=4, fill="random", tile_unroll=unroll)
+    rng = synth.rng_for(4)
+    t = rng.permutation(80)[:33].astype(np.int32)
+    t2 = rng.permutation(80)[:33].astype(np.int32)
+    h.pool.swap_out(0, t)
+    h.oracle.swap_out(0, t)
+    h.assert_image_equal(0)
+    h.pool.swap_in(0, t2)
+    h.oracle.swap_in(0, t2)
+    h.pool.kv_wait_all()
+    h.assert_pool_equal()
+
+
+def test_ring_wraps_when_request_exceeds_staging(harness):
+    shape = synth.TINY
+    # 2 directions x 2 slots x 3 block records: a 16-block request needs 6 slot uses
+    h = harness(shape, cfg=5, staging_bytes=2 * 2 * 3 * shape.R, n_slots=2, copy_chunk_bytes=40000)
+    rng = synth.rng_for(5)
+    tables = synth.deal_tables(rng, shape.n_blocks, [16, 7, 16, 1])
+    tables2 = synth.deal_tables(rng, shape.n_blocks, [16, 7, 16, 1])
+    for r, t in enumerate(tables):
+        h.pool.swap_out(r, t)
+        h.oracle.swap_out(r, t)
+    for r in range(4):
+        h.assert_image_equal(r)
+    for r, t in enumerate(tables2):
+        h.pool.swap_in(r, t)
+        h.oracle.swap_in(r, t)
+    h.pool.kv_wait_all()
+    h.assert_pool_equal()
+    st = h.pool.kv_stats()
+    assert st["gather_launches"] == 6 + 3 + 6 + 1
+    assert st["d2h_copies"] > st["gather_launches"]  # copies are also cut at 40000 bytes
+
+
+def test_more_blocks_than_one_launch_carries(harness):
+    """A launch carries at most 896 table entries: 2500 blocks need 3 launches per slot."""
+    shape = synth.KVShape("s", 1, 1, 32, 16, 2, 4096, "fp16")  # C = 1 KiB, R = 2 KiB
+    h = harness(shape, cfg=6, fill="random")
+    rng = synth.rng_for(6)
+    t = rng.permutation(4096)[:2500].astype(np.int32)
+    t2 = rng.permutation(4096)[:2500].astype(np.int32)
+    h.pool.swap_out(0, t)
+    h.oracle.swap_out(0, t)
+    h.assert_image_equal(0)
+    h.pool.swap_in(0, t2)
+    h.oracle.swap_in(0, t2)
+    h.pool.kv_wait_all()
+    h.assert_pool_equal()
+    assert h.pool.kv_stats()["gather_launches"] >= 3
+
+
+def test_multi_turn_delta_and_contamination(harness):
+    """Section 3.3 flow: keep the host copy, move only dirty / invalid blocks, grow the image."""
+    shape = synth.TINY
+    h = harness(shape, cfg=7, host_slack_blocks=4)
+    rng = synth.rng_for(7)
+    B = shape.block_size
+    tokens = 5 * B - 3
+    perm = rng.permutation(shape.n_blocks).astype(np.int32)
+    cursor = 5
+    table = perm[:5].copy()
+    h.pool.swap_out(0, table)
+    h.oracle.swap_out(0, table)
+    h.assert_image_equal(0)
+    for turn in range(6):
+        # resume into fresh blocks
+        new_table = perm[cursor:cursor + len(table)].copy()
+        cursor += len(table)
+        h.pool.swap_in(0, new_table)
+        h.oracle.swap_in(0, new_table)
+        h.pool.kv_wait(0)
+        h.assert_pool_equal()
+        # the turn appends tokens: tail block changes, new blocks appear
+        new_tokens = int(rng.integers(1, 4 * B))
+        n_old = len(new_table)
+        dirty = synth.turn_dirty_mask(n_old, tokens, new_tokens, B)
+        extra = len(dirty) - n_old
+        grown = np.concatenate([new_table, perm[cursor:cursor + extra]]).astype(np.int32)
+        cursor += extra
+        touched = np.flatnonzero(dirty)
+        h.overwrite_blocks(grown[touched], synth.fresh_tokens(rng, shape, len(touched)))
+        tokens += new_tokens
+        if turn % 2 == 1:  # part of the host copy was reclaimed meanwhile
+            inval = synth.random_mask(rng, n_old, 0.3)
+            h.pool.kv_host_invalidate(0, inval)
+            h.oracle.host_invalidate(0, inval)
+        moved = h.pool.swap_out_delta(0, grown, dirty)
+        want = h.oracle.swap_out_delta(0, grown, dirty)
+        assert moved == len(want)
+        h.assert_image_equal(0)
+        table = grown
+    st = h.pool.kv_stats()
+    assert st["bytes_out"] == h.oracle.bytes_out
+    assert st["bytes_in"] == h.oracle.bytes_in
+    assert st["host_relocations"] >= 1 or st["host_arena_used"] > 0
+
+
+def test_partial_swap_in_moves_only_non_resident_blocks(harness):
+    h = harness(synth.TINY, cfg=8)
+    rng = synth.rng_for(8)
+    t, t2 = synth.deal_tables(rng, 256, [12])[0], synth.deal_tables(rng, 256, [12])[0]
+    h.pool.swap_out(0, t)
+    h.oracle.swap_out(0, t)
+    res = synth.random_mask(rng, 12, 0.5)
+    res[0], res[1] = 1, 0
+    moved = h.pool.swap_in_delta(0, t2, res)
+    want = h.oracle.swap_in(0, t2, resident=res)
+    assert moved == len(want)
+    h.pool.kv_wait(0)
+    h.assert_pool_equal()
+
+
+def test_swap_in_over_blocks_still_being_gathered(harness):
+    """Conflict (Section 3.2): request B resumes into the blocks request A is leaving."""
+    shape = synth.KVShape("s", 4, 8, 128, 16, 2, 96, "bf16")
+    h = harness(shape, cfg=9, host_bytes=256 * MiB)
+    rng = synth.rng_for(9)
+    ta, tb = synth.deal_tables(rng, 96, [40, 40])
+    h.pool.swap_out(1, tb)
+    h.oracle.swap_out(1, tb)
+    h.pool.kv_wait(1)
+    for rep in range(3):
+        h.pool.swap_out(0, ta)            # A's blocks are being read ...
+        h.pool.swap_in(1, ta[::-1].copy())  # ... while B is written into them
+        h.oracle.swap_out(0, ta)
+        h.oracle.swap_in(1, ta[::-1].copy())
+        h.assert_image_equal(0)
+        h.pool.kv_wait(1)
+        h.assert_pool_equal()
+        # and the reverse hazard: gather blocks whose scatter is still in flight
+        h.pool.swap_in(0, tb)
+        h.pool.swap_out(1, tb)
+        h.oracle.swap_in(0, tb)
+        h.oracle.swap_out(1, tb)
+        h.assert_image_equal(1)
+        h.pool.kv_wait_all()
+        h.assert_pool_equal()
+        ta, tb = tb, ta
+
+
+def test_allocator_driven_flow(harness):
+    """Tables come from alloc_block_group; blocks are freed right after swap_out is enqueued
+    and may be handed out again only once their gather has finished."""
+    shape = synth.KVShape("s", 4, 8, 128, 16, 2, 128, "bf16")
+    h = harness(shape, cfg=10, host_bytes=512 * MiB)
+    chk = AllocChecker(shape.n_blocks)
+    rng = synth.rng_for(10)
+    live = {}
+    for r in range(6):
+        ids, runs = h.pool.alloc_block_group(r, 20, 8)
+        rl = chk.on_alloc(r, ids)
+        assert runs == len(rl)
+        live[r] = ids
+        h.overwrite_blocks(ids, synth.fresh_tokens(rng, shape, len(ids)))
+    # preempt 0..2, resume them later into whatever the allocator returns
+    for r in range(3):
+        h.pool.swap_out(r, live[r])
+        h.oracle.swap_out(r, live[r])
+        h.pool.free_block_group(r, live[r])
+        chk.on_free(r, live[r])
+    for r in range(3):
+        ids, _ = h.pool.alloc_block_group(r, 20, 8)
+        chk.on_alloc(r, ids)
+        h.pool.swap_in(r, ids)
+        h.oracle.swap_in(r, ids)
+        live[r] = ids
+    h.pool.kv_wait_all()
+    for r in range(3):
+        h.assert_image_equal(r)
+    h.assert_pool_equal()
+    free, _ = h.pool.kv_free_blocks()
+    assert free + chk.n_used() == shape.n_blocks
+
+
+def test_empty_request_and_queries(harness):
+    h = harness(synth.TINY, cfg=11)
+    h.pool.swap_out(0, np.zeros(0, np.int32))
+    h.oracle.swap_out(0, [])
+    h.pool.kv_wait(0)
+    assert h.pool.kv_query(0)
+    assert h.pool.kv_host_view(0).shape[0] == 0
+    h.pool.swap_in(0, np.zeros(0, np.int32))
+    h.pool.kv_wait(0)
+    h.assert_pool_equal()
+
+
+def test_rejected_calls_have_no_effect(harness):
+    h = harness(synth.TINY, cfg=12, host_bytes=20 * synth.TINY.R, host_slack_blocks=0)
+    kv = h.kv
+    t = np.arange(10, 20, dtype=np.int32)
+    h.pool.swap_out(0, t)
+    h.oracle.swap_out(0, t)
+    h.assert_image_equal(0)
+    for bad in ([1, 2, 2], [0, 256], [-1, 3]):
+        with pytest.raises(kv.KVError) as ei:
+            h.pool.swap_out(1, np.array(bad, np.int32))
+        assert ei.value.status == kv.KV_EINVAL
+    with pytest.raises(kv.KVError) as ei:
+        h.pool.swap_in(5, t)
+    assert ei.value.status == kv.KV_ENOENT
+    with pytest.raises(kv.KVError) as ei:
+        h.pool.swap_in(0, t[:5])
+    assert ei.value.status == kv.KV_EINVAL
+    with pytest.raises(kv.KVError) as ei:
+        h.pool.swap_out(2, np.arange(0, 11, dtype=np.int32))  # arena holds 20 records, 10 in use
+    assert ei.value.status == kv.KV_ENOMEM_HOST
+    h.pool.kv_host_invalidate(0, [1] + [0] * 9)
+    h.oracle.host_invalidate(0, [1] + [0] * 9)
+    with pytest.raises(kv.KVError) as ei:
+        h.pool.swap_in(0, t)
+    assert ei.value.status == kv.KV_ENOENT
+    h.pool.kv_wait_all()
+    h.assert_pool_equal()
+    h.assert_image_equal(0)
+    st = h.pool.kv_stats()
+    assert st["bytes_out"] == 10 * h.shape.R and st["bytes_in"] == 0
+
+
+def test_ordering_with_the_compute_stream(harness):
+    """KV written on the caller's stream just before swap_out must be what gets swapped, and
+    a stream made to wait by kv_stream_wait sees the swapped-in bytes."""
+    import torch
+    shape = synth.KVShape("s", 4, 8, 128, 16, 2, 64, "bf16")
+    stream = torch.cuda.Stream()
+    from gpu_util import Harness
+    h = Harness(shape, 13, 256 * MiB, fill="random",
+                flags=4, compute_stream=stream.cuda_stream)  # KV_FLAG_ORDER_COMPUTE
+    try:
+        rng = synth.rng_for(13)
+        t, t2 = synth.deal_tables(rng, 64, [24, 24])
+        view = h.gpu.view(shape.P, shape.n_blocks, shape.C)
+        idx = torch.from_numpy(t.astype(np.int64)).to(h.dev)
+        payload = synth.fresh_tokens(rng, shape, 24)
+        dev_payload = torch.from_numpy(np.ascontiguousarray(payload.transpose(1, 0, 2))).to(h.dev)
+        torch.cuda.synchronize()
+        with torch.cuda.stream(stream):
+            for _ in range(20):  # keep the stream busy, last write wins
+                view[:, idx, :] = 0
+            view[:, idx, :] = dev_payload
+        h.pool.swap_out(0, t)  # no host synchronisation in between
+        h.oracle.G[:, t.astype(np.int64), :] = payload.transpose(1, 0, 2)
+        h.oracle.swap_out(0, t)
+        h.assert_image_equal(0)
+        h.pool.swap_in(0, t2)
+        h.oracle.swap_in(0, t2)
+        h.pool.kv_stream_wait(0, stream.cuda_stream)
+        with torch.cuda.stream(stream):
+            idx2 = torch.from_numpy(t2.astype(np.int64)).to(h.dev)
+            got = view[:, idx2, :].clone()
+        stream.synchronize()
+        assert np.array_equal(got.cpu().numpy(), h.oracle.G[:, t2.astype(np.int64), :])
+    finally:
+        h.close()
+
+
+def test_profile_records(harness):
+    h = harness(synth.TINY, cfg=14, flags=2)  # KV_FLAG_PROFILE
+    t = np.arange(16, dtype=np.int32)
+    h.pool.swap_out(0, t)
+    h.pool.swap_in(0, t[::-1].copy())
+    recs = h.pool.kv_profile_read()
+    kinds = sorted(k for k, _, _ in recs)
+    assert kinds == [0, 1, 2, 3]
+    for k, nbytes, ms in recs:
+        assert nbytes == 16 * h.shape.R and ms > 0
+    h.pool.kv_profile_reset()
+    assert h.pool.kv_profile_read() == []
+
+
+def test_probes_report_plausible_rates():
+    from paper_2411_18424_amd import kvswap
+    hbm = kvswap.kv_hbm_probe(256 * MiB, 3)
+    d2h = kvswap.kv_link_probe(64 * MiB, 0, 2)
+    h2d = kvswap.kv_link_probe(64 * MiB, 1, 2)
+    assert 100 < hbm < 8000
+    assert 1 < d2h < 200 and 1 < h2d < 200
