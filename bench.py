@@ -1,0 +1,273 @@
+#!/usr/bin/env python3
+"""KV-swap benchmark on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input: the 16
+victims of the Llama-3-8B-shaped workload (config 2) are swapped out of a 16 GiB paged
+KV pool to pinned host memory (gather kernels + device-to-host copies) and swapped back
+in through fresh block tables (host-to-device copies + scatter kernels).  The pool is
+resident in HBM before the timed region.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--no-cpu-baseline]
+"""
+
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
+GiB = 1 << 30
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def percentile(xs, q):
+    import numpy as np
+    return float(np.percentile(np.asarray(xs, dtype=np.float64), q))
+
+
+def cpu_baseline(work, budget_s=12.0):
+    """The CPU oracle, as it stands, on the same victims: swap all out, then in through the
+    resume tables, repeated until about budget_s seconds of work.  One thread."""
+    import numpy as np
+    from oracle.kv_oracle import KVOracle
+    from paper_2411_18424_amd import synth
+
+    s = work.shape
+    o = KVOracle(s.n_layers, s.n_kv_heads, s.head_dim, s.block_size, s.elt_bytes, s.n_blocks)
+    content = synth.PoolContent(s, work.cfg)
+    for v in work.victims:  # only the victims' blocks are materialised (the rest stays untouched zero pages)
+        blocks = work.tables[v].astype(np.int64)
+        for p in range(s.P):
+            o.G[p, blocks, :] = content.plane(p, blocks)
+    cur = {v: work.tables[v] for v in work.victims}
+    nxt = {v: t for v, t in zip(work.victims, work.resume_tables)}
+    steps, moved = 0, 0
+    t0 = time.perf_counter()
+    while True:
+        for v in work.victims:
+            moved += len(o.swap_out(v, cur[v])) * s.R
+        for v in work.victims:
+            moved += len(o.swap_in(v, nxt[v])) * s.R
+        cur, nxt = nxt, cur
+        steps += 1
+        dt = time.perf_counter() - t0
+        if dt >= budget_s or steps >= 50:
+            break
+    nb = sum(len(work.tables[v]) for v in work.victims)
+    return {"value": moved / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": "same 16 victims (%d blocks, %.2f GiB each way), %d full out+in steps, %.1f s"
+                      % (nb, nb * s.R / GiB, steps, dt)}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--latency-reps", type=int, default=3)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        log("bench.py: this build measures one GPU only (the swap path has no cross-GPU step); "
+            "--gpus %d is not supported" % args.gpus)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2411_18424_amd import kvswap as kv
+    from paper_2411_18424_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    work = synth.llama3_8b_preempt_workload()
+    s = work.shape
+    victims = work.victims
+    nb = sum(len(work.tables[v]) for v in victims)
+    payload = nb * s.R  # bytes each way per step
+    log("workload: %s, pool %d blocks (%.1f GiB), %d requests, %d victims = %d blocks = %.2f GiB each way"
+        % (s.name, s.n_blocks, s.n_blocks * s.R / GiB, len(work.tables), len(victims), nb, payload / GiB))
+
+    # ---- measured ceilings (before anything else is resident)
+    link_d2h = kv.kv_link_probe(GiB, 0, 10)
+    link_h2d = kv.kv_link_probe(GiB, 1, 10)
+    link_duplex = kv.kv_link_probe(GiB, 2, 5)
+    hbm_copy = kv.kv_hbm_probe(2 * GiB, 10)
+    log("measured: link d2h %.2f h2d %.2f duplex %.2f GB/s; device copy kernel %.0f GB/s"
+        % (link_d2h, link_h2d, link_duplex, hbm_copy))
+
+    # ---- pool resident in HBM
+    gpu = torch.empty(s.R * s.n_blocks, dtype=torch.uint8, device=dev)
+    content = synth.PoolContent(s, work.cfg)
+    content.fill_device(gpu)
+    pool = kv.KVPool(n_layers=s.n_layers, n_kv_heads=s.n_kv_heads, head_dim=s.head_dim,
+                     block_size=s.block_size, elt_bytes=s.elt_bytes, n_gpu_blocks=s.n_blocks,
+                     gpu_base=gpu.data_ptr(), host_bytes=payload + 64 * len(victims) * s.R,
+                     flags=kv.KV_FLAG_PROFILE)
+    cur = [work.tables[v] for v in victims]
+    nxt = list(work.resume_tables)
+
+    def step():
+        nonlocal cur, nxt
+        pool.swap_out_batch(victims, cur)
+        pool.kv_wait_all()
+        pool.swap_in_batch(victims, nxt)
+        pool.kv_wait_all()
+        cur, nxt = nxt, cur
+
+    for _ in range(args.warmup):
+        step()
+    pool.kv_profile_reset()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    recs = pool.kv_profile_read()
+
+    def agg(kind):
+        rs = [r for r in recs if r[0] == kind]
+        nbytes = sum(r[1] for r in rs)
+        ms = sum(r[2] for r in rs)
+        return len(rs), nbytes, ms
+
+    n_g, b_g, ms_g = agg(0)
+    n_s, b_s, ms_s = agg(1)
+    n_o, b_o, ms_o = agg(2)
+    n_i, b_i, ms_i = agg(3)
+    gather_gbps = 2 * b_g / ms_g / 1e6
+    scatter_gbps = 2 * b_s / ms_s / 1e6
+    d2h_gbps = b_o / ms_o / 1e6
+    h2d_gbps = b_i / ms_i / 1e6
+
+    # ---- sampled check against the content definition (outside the timed region)
+    pool.swap_out_batch(victims, cur)
+    pool.kv_wait_all()
+    rng = synth.rng_for(work.cfg, stream=99)
+    # a logical block keeps the bytes it was created with, wherever it has been moved since
+    origin = [work.tables[v] for v in victims]
+    ok = True
+    for i in rng.integers(0, len(victims), size=8):
+        img = pool.kv_host_view(victims[i])
+        j = int(rng.integers(0, img.shape[0]))
+        ok &= bool(np.array_equal(img[j], content.block(int(origin[i][j]))))
+    pool.swap_in_batch(victims, cur)
+    pool.kv_wait_all()
+
+    # ---- per-preemption switch latency: one victim out, one in, call -> completion
+    out_ms, in_ms, sw_ms = [], [], []
+    for _ in range(args.latency_reps):
+        for i, v in enumerate(victims):
+            t_a = time.perf_counter()
+            pool.swap_out(v, cur[i])
+            pool.kv_wait(v)
+            t_b = time.perf_counter()
+            pool.swap_in(v, nxt[i])
+            pool.kv_wait(v)
+            t_c = time.perf_counter()
+            out_ms.append((t_b - t_a) * 1e3)
+            in_ms.append((t_c - t_b) * 1e3)
+            sw_ms.append((t_c - t_a) * 1e3)
+        cur, nxt = nxt, cur
+    # overlapped switch: victim i leaves while victim i-1 resumes (both directions at once)
+    ov_ms = []
+    pool.swap_out(victims[0], cur[0])
+    pool.kv_wait(victims[0])
+    for i in range(1, len(victims)):
+        t_a = time.perf_counter()
+        pool.swap_out(victims[i], cur[i])
+        pool.swap_in(victims[i - 1], nxt[i - 1])
+        pool.kv_wait(victims[i])
+        pool.kv_wait(victims[i - 1])
+        ov_ms.append((time.perf_counter() - t_a) * 1e3)
+    pool.swap_in(victims[-1], nxt[-1])
+    pool.kv_wait_all()
+    stats = pool.kv_stats()
+    pool.kv_pool_destroy()
+    del gpu
+    torch.cuda.empty_cache()
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "gather_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            with open(tpath) as f:
+                traffic = json.load(f).get("hbm_bytes_per_launch")
+        except Exception:
+            traffic = None
+
+    result = {
+        "metric": "KV swap GB/s (out+in), 1 MI355X",
+        "value": round(2 * payload * args.steps / dt / 1e9, 3),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(dt / args.steps * 1e3, 3),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u8",
+        "data": "synthetic",
+        "config": {
+            "workload": "config 2: Llama-3-8B-shaped KV (32 layers, 8 KV heads, head_dim 128, block 16, bf16), "
+                        "8192-block pool, 64 lognormal requests in block groups of 8, 16 victims swapped out "
+                        "(batched) then in through fresh tables",
+            "payload_bytes_each_way": payload,
+            "victim_blocks": nb,
+        },
+        "roofline": {
+            "bound": "hbm",
+            "kernel": "kv_pack_kernel (gather)",
+            "achieved": round(gather_gbps, 1),
+            "peak": HBM_PEAK_GBPS,
+            "unit": "GB/s",
+            "frac": round(gather_gbps / HBM_PEAK_GBPS, 4),
+            "traffic": traffic,
+            "launches": n_g,
+            "avg_launch_ms": round(ms_g / max(1, n_g), 4),
+            "algorithmic_bytes_per_launch": int(2 * b_g / max(1, n_g)),
+            "scatter_achieved": round(scatter_gbps, 1),
+            "scatter_frac": round(scatter_gbps / HBM_PEAK_GBPS, 4),
+            "device_copy_kernel_gbps": round(hbm_copy, 1),
+        },
+        "link": {
+            "measured_peak_d2h_gbps": round(link_d2h, 2),
+            "measured_peak_h2d_gbps": round(link_h2d, 2),
+            "measured_peak_duplex_gbps": round(link_duplex, 2),
+            "d2h_copies_gbps": round(d2h_gbps, 2),
+            "h2d_copies_gbps": round(h2d_gbps, 2),
+            "d2h_frac_of_measured": round(d2h_gbps / link_d2h, 4),
+            "h2d_frac_of_measured": round(h2d_gbps / link_h2d, 4),
+        },
+        "switch_latency_ms": {
+            "what": "one victim: swap_out call -> done, then swap_in call -> done (sequential), host clock",
+            "n": len(sw_ms),
+            "median": round(percentile(sw_ms, 50), 3), "p99": round(percentile(sw_ms, 99), 3),
+            "max": round(max(sw_ms), 3),
+            "out_median": round(percentile(out_ms, 50), 3), "in_median": round(percentile(in_ms, 50), 3),
+            "overlapped_median": round(percentile(ov_ms, 50), 3),
+            "overlapped_p99": round(percentile(ov_ms, 99), 3),
+            "median_request_MiB": round(float(np.median([len(t) for t in cur])) * s.R / (1 << 20), 1),
+        },
+        "verified_samples_ok": ok,
+        "stats": {k: stats[k] for k in ("gather_launches", "scatter_launches", "d2h_copies", "h2d_copies")},
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(work)
+    print(json.dumps(result), flush=True)
+    return 0 if ok else 1
+
+
+if __name__ == "__main__":
+    sys.exit(main())

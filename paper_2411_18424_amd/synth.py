@@ -132,6 +132,25 @@ class PoolContent:
         for p in range(self.shape.P):
             G[p] = self.plane(p)
 
+    def fill_device(self, gpu_flat) -> None:
+        """Same bytes as fill(), written into a flat uint8 torch tensor on the GPU.
+
+        Only the small base buffer, window indices and stamps cross the host link; the
+        pool itself is materialised by an index_select on the device.
+        """
+        import torch
+        s = self.shape
+        dev = gpu_flat.device
+        view = gpu_flat.view(s.P, s.n_blocks, s.C)
+        base = torch.from_numpy(self.base).to(dev)
+        blocks = np.arange(s.n_blocks)
+        for p in range(s.P):
+            idx = torch.from_numpy(self.window(np.full(blocks.shape, p), blocks)).to(dev)
+            torch.index_select(base, 0, idx, out=view[p])
+            st = self.stamp(np.full(blocks.shape, p), blocks).view(np.uint8).reshape(-1, 16)
+            view[p, :, :16] = torch.from_numpy(st).to(dev)
+        torch.cuda.synchronize()
+
 
 def fresh_tokens(rng: np.random.Generator, shape: KVShape, n_blocks: int) -> np.ndarray:
     """Random replacement payload for n_blocks whole blocks: uint8 [n][P][C]."""
@@ -203,3 +222,31 @@ def turn_dirty_mask(n_old_blocks: int, old_tokens: int, new_tokens: int, block_s
         m[n_old_blocks - 1] = 1
     m[n_old_blocks:] = 1
     return m
+
+
+# ------------------------------------------------------------ named workloads
+@dataclass
+class PreemptWorkload:
+    """A pool full of requests, a set of victims to preempt, and fresh tables to resume into."""
+    shape: KVShape
+    cfg: int
+    tokens: np.ndarray          # per request
+    tables: list                # per request, current block table
+    victims: list               # request ids to preempt
+    resume_tables: list         # per victim, disjoint from every current table
+
+
+def llama3_8b_preempt_workload(n_req: int = 64, n_victims: int = 16, run: int = 8,
+                               shape: KVShape = LLAMA3_8B, cfg: int = 2) -> PreemptWorkload:
+    """Config 2: lognormal request lengths (median 1k, max 8k tokens) in block groups of
+    `run` contiguous blocks; 16 seeded victims; resume tables dealt from the free groups."""
+    rng = rng_for(cfg)
+    while True:
+        tokens = lengths_lognormal(rng, n_req, 1024, 0.8, 16, 8192, shape.block_size, shape.n_blocks)
+        nblk = blocks_for(tokens, shape.block_size)
+        victims = sorted(int(v) for v in rng.permutation(n_req)[:n_victims])
+        try:
+            dealt = deal_tables(rng, shape.n_blocks, list(nblk) + [nblk[v] for v in victims], run=run)
+        except ValueError:
+            continue  # victims' resume tables did not fit the free space: redraw
+        return PreemptWorkload(shape, cfg, tokens, dealt[:n_req], victims, dealt[n_req:])
