@@ -69,18 +69,24 @@ typedef struct {
   int64_t n_gpu_blocks;     /* N */
   void*   gpu_base;         /* device pointer, >= P*N*C bytes, 16-byte aligned; caller-owned */
   int64_t host_bytes;       /* capacity of the pinned host arena (library allocates it) */
-  void*   staging_base;     /* device pointer to staging memory, or NULL: library allocates */
-  int64_t staging_bytes;    /* total staging bytes (split evenly: out ring + in ring); 0 = default */
-  int32_t n_slots;          /* ring slots per direction (>= 2); 0 = default 4 */
-  int32_t host_slack_blocks;/* room reserved after each new host image for the next turn's
-                               increment (Section 3.3 adjacent preallocation); <0 = default 32 */
+  void*   staging_base;     /* device pointer to staging_out_bytes + staging_in_bytes of staging
+                               memory, or NULL: library allocates (then both sizes may be 0) */
+  int64_t staging_out_bytes;/* swap-out staging ring; 0 = default min(4 GiB, pool/4).  A swap-out
+                               call that fits is packed completely before its copies start */
+  int64_t staging_in_bytes; /* swap-in staging ring; 0 = default min(1 GiB, pool/8) */
+  int64_t max_piece_bytes;  /* most bytes one piece (pack launches + their copies) carries;
+                               0 = default.  Always <= half a ring and >= one block record */
   int64_t copy_chunk_bytes; /* a host<->device copy is issued in pieces of at most this many
                                bytes so other streams' copies can interleave (Section 3.2,
-                               dispatch-order control); 0 = default */
+                               dispatch-order control); 0 = default 64 MiB */
   void*   compute_stream;   /* hipStream_t of the caller's inference work (used with
-                               KV_FLAG_ORDER_COMPUTE and by kv_stream_wait) */
-  int32_t gather_grid;      /* workgroups per pack-kernel launch; 0 = default */
-  int32_t reserved;
+                               KV_FLAG_ORDER_COMPUTE) */
+  int32_t host_slack_blocks;/* room reserved after each new host image for the next turn's
+                               increment (Section 3.3 adjacent preallocation); <0 = default 32 */
+  int32_t gather_grid;      /* workgroups per launch of the persistent pack variant; 0 = default */
+  int32_t tile_unroll;      /* 16-byte vectors per lane per tile (1,2,4,8); 0 = from chunk size */
+  int32_t pack_variant;     /* 0 = one tile per workgroup, 3-D grid (default, fastest measured);
+                               1 = persistent grid-stride workgroups with the block table in LDS */
 } kv_pool_config_t;
 
 /* Section 3.1 (KV pool + block groups).  Creates the pool object: pinned host arena,

@@ -21,12 +21,17 @@ struct KvPackArgs {
   int32_t table[KV_MAX_LAUNCH_BLOCKS];  // physical block id of each of the m blocks
 };
 
-// unroll: 16-byte vectors per lane per tile (1, 2, 4 or 8); 0 picks the largest that
-// divides the chunk.  start/stop may be null; when given they receive the dispatch's own
-// begin / end timestamps.
-hipError_t kv_launch_pack(bool scatter, const KvPackArgs& a, int unroll, int grid,
+#define KV_PACK_TILE 0        // one tile per workgroup, 3-D grid (default)
+#define KV_PACK_PERSISTENT 1  // grid-stride loop, block table staged in LDS
+
+// unroll: 16-byte vectors per lane per tile (1, 2, 4 or 8); 0 picks from the chunk size.
+// variant: KV_PACK_*.  grid: workgroups of the persistent variant (<= 0: 2048).
+// start/stop may be null; when given they receive the dispatch's own begin / end timestamps.
+hipError_t kv_launch_pack(bool scatter, const KvPackArgs& a, int unroll, int variant, int grid,
                           hipStream_t stream, hipEvent_t start, hipEvent_t stop);
+// Most blocks one launch may carry for this shape (table capacity and dispatch size).
+int64_t kv_max_launch_blocks(uint32_t C, uint32_t P, int unroll);
 // Plain linear device copy (bandwidth probe): bytes must be a multiple of 16.
-hipError_t kv_launch_linear_copy(void* dst, const void* src, int64_t bytes, int grid,
-                                 hipStream_t stream, hipEvent_t start, hipEvent_t stop);
+hipError_t kv_launch_linear_copy(void* dst, const void* src, int64_t bytes, hipStream_t stream,
+                                 hipEvent_t start, hipEvent_t stop);
 int kv_pick_unroll(uint32_t C);

@@ -13,7 +13,10 @@
 // Streams (all default priority, non-blocking):
 //   s_pack : gather kernels           s_d2h : device-to-host copies
 //   s_h2d  : host-to-device copies    s_scat: scatter kernels
-// Ring slot hand-off: ready[slot] (producer finished) / freed[slot] (consumer finished).
+// Swap-out packs first and drains afterwards: all gathers of a call that fit the staging ring
+// run back to back (the request's GPU blocks are reusable after about a millisecond), then
+// the copies drain the ring; only a call larger than the ring interleaves the two.  Swap-in
+// is pipelined piece by piece: the scatter of piece i runs under the copy of piece i+1.
 
 #include <hip/hip_runtime.h>
 #include <stdarg.h>
@@ -58,6 +61,7 @@ struct Op {
   hipEvent_t packed = nullptr;  // swap-out only: recorded after the last gather
   hipEvent_t done = nullptr;    // recorded after the last copy (out) / scatter (in)
   bool packed_done = false, all_done = false;
+  std::vector<hipEvent_t> aux;  // hand-off events of this op, recycled when it is done
 };
 using OpRef = std::shared_ptr<Op>;
 
@@ -75,13 +79,22 @@ struct Req {
   OpRef last_out;  // last swap-out
 };
 
-struct Ring {
+// Staging is a byte ring: a piece of a swap takes exactly the bytes it needs, so many small
+// requests can be in flight at once and a large one wraps around.  Regions are handed out
+// in ring order and retired in the same order.
+struct Region {
+  int64_t off = 0, len = 0;
+  hipEvent_t freed = nullptr;  // recorded when the region's consumer has finished
+  uint64_t op_seq = 0;
+  bool recorded = false;
+};
+
+struct ByteRing {
   char* base = nullptr;
-  int64_t slot_bytes = 0;
-  int64_t slot_blocks = 0;
-  int n_slots = 0;
-  uint64_t next = 0;
-  std::vector<hipEvent_t> ready, freed;
+  int64_t cap = 0;
+  int64_t head = 0;
+  int64_t piece_blocks = 1;  // most blocks one piece carries
+  std::deque<Region> live;
 };
 
 struct Move {
@@ -107,11 +120,12 @@ struct kv_pool {
   int64_t arena_blocks = 0;
   bool own_staging = false;
   char* staging = nullptr;
-  Ring ring_out, ring_in;
+  ByteRing ring_out, ring_in;
   hipStream_t s_pack = nullptr, s_d2h = nullptr, s_h2d = nullptr, s_scat = nullptr;
   hipStream_t compute = nullptr;
   hipEvent_t ev_compute = nullptr;
-  int unroll = 0, grid = 0;
+  int unroll = 0, grid = 0, variant = 0;
+  int64_t launch_blocks = KV_MAX_LAUNCH_BLOCKS;  // most blocks one pack launch carries
   int64_t copy_chunk = 0;
   int64_t slack = 32;
 
@@ -175,6 +189,8 @@ void reap(kv_pool* p) {
     p->scat_done_seq = p->in_seq;
     p->ops_out.clear();
     p->ops_in.clear();
+    p->ring_out.live.clear();
+    p->ring_in.live.clear();
     p->alloc.reap(p->pack_done_seq);
     return;
   }
@@ -191,6 +207,8 @@ void reap(kv_pool* p) {
     put_event(p, o.packed);
     put_event(p, o.done);
     o.packed = o.done = nullptr;
+    for (hipEvent_t e : o.aux) put_event(p, e);
+    o.aux.clear();
     p->ops_out.pop_front();
   }
   while (!p->ops_in.empty()) {
@@ -200,7 +218,17 @@ void reap(kv_pool* p) {
     p->scat_done_seq = o.seq;
     put_event(p, o.done);
     o.done = nullptr;
+    for (hipEvent_t e : o.aux) put_event(p, e);
+    o.aux.clear();
     p->ops_in.pop_front();
+  }
+  for (ByteRing* r : {&p->ring_out, &p->ring_in}) {
+    while (!r->live.empty()) {
+      Region& f = r->live.front();
+      if (!f.recorded || hipEventQuery(f.freed) != hipSuccess) break;
+      put_event(p, f.freed);
+      r->live.pop_front();
+    }
   }
   p->alloc.reap(p->pack_done_seq);
 }
@@ -288,7 +316,7 @@ int32_t launch_pack(kv_pool* p, bool scatter, char* staging, const Move* mv, int
     if (rc) return rc;
     p->prof.push_back({scatter ? 1 : 0, m * p->R, e0, e1});
   }
-  HIP_TRY(kv_launch_pack(scatter, a, p->unroll, p->grid, s, e0, e1));
+  HIP_TRY(kv_launch_pack(scatter, a, p->unroll, p->variant, p->grid, s, e0, e1));
   return KV_OK;
 }
 
@@ -334,7 +362,47 @@ int32_t order_after_compute(kv_pool* p, hipStream_t s) {
   return KV_OK;
 }
 
-// Swap-out of a move list: gather into ring slots, copy each slot to the host.
+// Claims `len` bytes at the ring head for op `op_seq`.  Every live region the claim
+// overlaps (and every older one) must have been released by its consumer first: the
+// producer stream is made to wait for it on the device.  `flush` is called before waiting
+// on a region of the same op whose consumer work has not been issued yet.
+template <class Flush>
+int32_t ring_claim(kv_pool* p, ByteRing* r, int64_t len, uint64_t op_seq, hipStream_t producer,
+                   Flush&& flush, Region** out) {
+  int32_t rc;
+  auto evict = [&](int64_t lo, int64_t hi) -> int32_t {
+    int last = -1;
+    for (int i = 0; i < (int)r->live.size(); ++i)
+      if (r->live[(size_t)i].off < hi && lo < r->live[(size_t)i].off + r->live[(size_t)i].len) last = i;
+    for (int i = 0; i <= last; ++i) {
+      if (!r->live.front().recorded) {
+        if (r->live.front().op_seq != op_seq) return fail(KV_EBUSY, "staging region of another call is still open");
+        if ((rc = flush())) return rc;
+      }
+      Region f = r->live.front();
+      r->live.pop_front();
+      if ((rc = stream_wait(p, producer, f.freed))) return rc;
+      put_event(p, f.freed);
+    }
+    return KV_OK;
+  };
+  if (r->head + len > r->cap) {  // the tail is too short: skip it and start over at 0
+    if ((rc = evict(r->head, r->cap))) return rc;
+    r->head = 0;
+  }
+  if ((rc = evict(r->head, r->head + len))) return rc;
+  Region g;
+  g.off = r->head;
+  g.len = len;
+  g.op_seq = op_seq;
+  if ((rc = get_event(p, &g.freed))) return rc;
+  r->head += len;
+  r->live.push_back(g);
+  *out = &r->live.back();
+  return KV_OK;
+}
+
+// Swap-out of a move list: gather pieces into the staging ring, then drain them to the host.
 // pre: events the first gather must wait for.
 int32_t enqueue_out(kv_pool* p, const std::vector<Move>& mv, const std::vector<hipEvent_t>& pre,
                     const OpRef& op) {
@@ -342,25 +410,44 @@ int32_t enqueue_out(kv_pool* p, const std::vector<Move>& mv, const std::vector<h
   if ((rc = order_after_compute(p, p->s_pack))) return rc;
   for (hipEvent_t e : pre)
     if ((rc = stream_wait(p, p->s_pack, e))) return rc;
-  Ring& r = p->ring_out;
+  ByteRing& r = p->ring_out;
   const int64_t m = (int64_t)mv.size();
-  for (int64_t i = 0; i < m; i += r.slot_blocks) {
-    const int64_t mp = std::min(r.slot_blocks, m - i);
-    const int slot = (int)(r.next % (uint64_t)r.n_slots);
-    const bool reused = r.next >= (uint64_t)r.n_slots;
-    ++r.next;
-    char* sb = r.base + (int64_t)slot * r.slot_bytes;
-    if (reused && (rc = stream_wait(p, p->s_pack, r.freed[slot]))) return rc;
-    for (int64_t k = 0; k < mp; k += KV_MAX_LAUNCH_BLOCKS) {
-      int64_t ml = std::min<int64_t>(KV_MAX_LAUNCH_BLOCKS, mp - k);
-      if ((rc = launch_pack(p, false, sb + k * p->R, &mv[(size_t)(i + k)], ml))) return rc;
+  struct Pending {
+    int64_t first, count, off;
+  };
+  std::vector<Pending> pending;  // gathered, copies not issued yet
+  auto flush = [&]() -> int32_t {
+    if (pending.empty()) return KV_OK;
+    int32_t rc2;
+    hipEvent_t ready;
+    if ((rc2 = get_event(p, &ready))) return rc2;
+    if (ready) op->aux.push_back(ready);
+    if ((rc2 = record(p, ready, p->s_pack))) return rc2;
+    if ((rc2 = stream_wait(p, p->s_d2h, ready))) return rc2;
+    for (const Pending& q : pending) {
+      if ((rc2 = issue_copies(p, true, r.base + q.off, &mv[(size_t)q.first], q.count))) return rc2;
+      for (Region& g : r.live)
+        if (g.off == q.off && g.op_seq == op->seq && !g.recorded) {
+          if ((rc2 = record(p, g.freed, p->s_d2h))) return rc2;
+          g.recorded = true;
+        }
     }
-    if ((rc = record(p, r.ready[slot], p->s_pack))) return rc;
-    if ((rc = stream_wait(p, p->s_d2h, r.ready[slot]))) return rc;
-    if ((rc = issue_copies(p, true, sb, &mv[(size_t)i], mp))) return rc;
-    if ((rc = record(p, r.freed[slot], p->s_d2h))) return rc;
+    pending.clear();
+    return KV_OK;
+  };
+  for (int64_t i = 0; i < m; i += r.piece_blocks) {
+    const int64_t mp = std::min(r.piece_blocks, m - i);
+    Region* g;
+    if ((rc = ring_claim(p, &r, mp * p->R, op->seq, p->s_pack, flush, &g))) return rc;
+    const int64_t off = g->off;
+    for (int64_t k = 0; k < mp; k += p->launch_blocks) {
+      int64_t ml = std::min<int64_t>(p->launch_blocks, mp - k);
+      if ((rc = launch_pack(p, false, r.base + off + k * p->R, &mv[(size_t)(i + k)], ml))) return rc;
+    }
+    pending.push_back({i, mp, off});
   }
   if ((rc = record(p, op->packed, p->s_pack))) return rc;
+  if ((rc = flush())) return rc;
   if (m == 0 && (rc = stream_wait(p, p->s_d2h, op->packed))) return rc;
   if ((rc = record(p, op->done, p->s_d2h))) return rc;
   p->st.bytes_out += m * p->R;
@@ -368,7 +455,7 @@ int32_t enqueue_out(kv_pool* p, const std::vector<Move>& mv, const std::vector<h
   return KV_OK;
 }
 
-// Swap-in of a move list: copy host records into ring slots, scatter each slot.
+// Swap-in of a move list: copy host records into ring pieces, scatter each piece.
 // pre_copy: events the first host-to-device copy waits for (the image's last writer);
 // pre_scat: events the first scatter waits for (gathers still reading the target blocks).
 int32_t enqueue_in(kv_pool* p, const std::vector<Move>& mv, const std::vector<hipEvent_t>& pre_copy,
@@ -379,23 +466,26 @@ int32_t enqueue_in(kv_pool* p, const std::vector<Move>& mv, const std::vector<hi
   if ((rc = order_after_compute(p, p->s_scat))) return rc;
   for (hipEvent_t e : pre_scat)
     if ((rc = stream_wait(p, p->s_scat, e))) return rc;
-  Ring& r = p->ring_in;
+  ByteRing& r = p->ring_in;
   const int64_t m = (int64_t)mv.size();
-  for (int64_t i = 0; i < m; i += r.slot_blocks) {
-    const int64_t mp = std::min(r.slot_blocks, m - i);
-    const int slot = (int)(r.next % (uint64_t)r.n_slots);
-    const bool reused = r.next >= (uint64_t)r.n_slots;
-    ++r.next;
-    char* sb = r.base + (int64_t)slot * r.slot_bytes;
-    if (reused && (rc = stream_wait(p, p->s_h2d, r.freed[slot]))) return rc;
+  auto no_flush = []() -> int32_t { return KV_OK; };  // every region is closed before the next claim
+  for (int64_t i = 0; i < m; i += r.piece_blocks) {
+    const int64_t mp = std::min(r.piece_blocks, m - i);
+    Region* g;
+    if ((rc = ring_claim(p, &r, mp * p->R, op->seq, p->s_h2d, no_flush, &g))) return rc;
+    char* sb = r.base + g->off;
     if ((rc = issue_copies(p, false, sb, &mv[(size_t)i], mp))) return rc;
-    if ((rc = record(p, r.ready[slot], p->s_h2d))) return rc;
-    if ((rc = stream_wait(p, p->s_scat, r.ready[slot]))) return rc;
-    for (int64_t k = 0; k < mp; k += KV_MAX_LAUNCH_BLOCKS) {
-      int64_t ml = std::min<int64_t>(KV_MAX_LAUNCH_BLOCKS, mp - k);
+    hipEvent_t ready;
+    if ((rc = get_event(p, &ready))) return rc;
+    if (ready) op->aux.push_back(ready);
+    if ((rc = record(p, ready, p->s_h2d))) return rc;
+    if ((rc = stream_wait(p, p->s_scat, ready))) return rc;
+    for (int64_t k = 0; k < mp; k += p->launch_blocks) {
+      int64_t ml = std::min<int64_t>(p->launch_blocks, mp - k);
       if ((rc = launch_pack(p, true, sb + k * p->R, &mv[(size_t)(i + k)], ml))) return rc;
     }
-    if ((rc = record(p, r.freed[slot], p->s_scat))) return rc;
+    if ((rc = record(p, g->freed, p->s_scat))) return rc;
+    g->recorded = true;
   }
   if (m == 0) {
     // nothing moved: completion still follows the image's last writer
@@ -610,37 +700,18 @@ int32_t do_swap_in(kv_pool* p, std::vector<InItem>& items, int32_t* out_n_moved)
   return enqueue_in(p, mv, pre_copy, pre_scat, op);
 }
 
-int32_t make_ring(kv_pool* p, Ring* r, char* base, int64_t slot_bytes, int n_slots) {
-  r->base = base;
-  r->slot_bytes = slot_bytes;
-  r->slot_blocks = slot_bytes / p->R;
-  r->n_slots = n_slots;
-  r->next = 0;
-  r->ready.assign((size_t)n_slots, nullptr);
-  r->freed.assign((size_t)n_slots, nullptr);
-  if (p->plan) return KV_OK;
-  for (int i = 0; i < n_slots; ++i) {
-    HIP_TRY(hipEventCreateWithFlags(&r->ready[(size_t)i], hipEventDisableTiming));
-    HIP_TRY(hipEventCreateWithFlags(&r->freed[(size_t)i], hipEventDisableTiming));
-  }
-  return KV_OK;
-}
-
 void destroy_pool(kv_pool* p) {
   if (!p->plan) {
     (void)hipDeviceSynchronize();
-    for (Ring* r : {&p->ring_out, &p->ring_in}) {
-      for (hipEvent_t e : r->ready)
-        if (e) (void)hipEventDestroy(e);
-      for (hipEvent_t e : r->freed)
-        if (e) (void)hipEventDestroy(e);
-    }
-    for (auto& o : p->ops_out) {
-      if (o->packed) (void)hipEventDestroy(o->packed);
-      if (o->done) (void)hipEventDestroy(o->done);
-    }
-    for (auto& o : p->ops_in)
-      if (o->done) (void)hipEventDestroy(o->done);
+    for (ByteRing* r : {&p->ring_out, &p->ring_in})
+      for (Region& g : r->live)
+        if (g.freed) (void)hipEventDestroy(g.freed);
+    for (auto* dq : {&p->ops_out, &p->ops_in})
+      for (auto& o : *dq) {
+        if (o->packed) (void)hipEventDestroy(o->packed);
+        if (o->done) (void)hipEventDestroy(o->done);
+        for (hipEvent_t e : o->aux) (void)hipEventDestroy(e);
+      }
     for (hipEvent_t e : p->event_pool) (void)hipEventDestroy(e);
     for (hipEvent_t e : p->timing_pool) (void)hipEventDestroy(e);
     for (auto& r : p->prof) {
@@ -677,7 +748,8 @@ int32_t kv_pool_create(const kv_pool_config_t* cfg, kv_pool_t** out) {
     return fail(KV_EINVAL, "gpu_base must be a 16-byte aligned device pointer");
   if (cfg->staging_base && ((uintptr_t)cfg->staging_base & 15))
     return fail(KV_EINVAL, "staging_base must be 16-byte aligned");
-  if (cfg->host_bytes < 0 || cfg->staging_bytes < 0 || cfg->n_slots < 0 || cfg->copy_chunk_bytes < 0)
+  if (cfg->host_bytes < 0 || cfg->staging_out_bytes < 0 || cfg->staging_in_bytes < 0 ||
+      cfg->max_piece_bytes < 0 || cfg->copy_chunk_bytes < 0)
     return fail(KV_EINVAL, "negative size");
 
   kv_pool* p = new kv_pool();
@@ -694,24 +766,33 @@ int32_t kv_pool_create(const kv_pool_config_t* cfg, kv_pool_t** out) {
   p->slack = cfg->host_slack_blocks < 0 ? 32 : cfg->host_slack_blocks;
   p->copy_chunk = cfg->copy_chunk_bytes > 0 ? cfg->copy_chunk_bytes : (64ll << 20);
   p->grid = cfg->gather_grid;
-  p->unroll = cfg->reserved;  // 0 = pick from the chunk size
-  const int n_slots = cfg->n_slots > 0 ? cfg->n_slots : 4;
-  if (n_slots < 2) {
+  p->unroll = cfg->tile_unroll;  // 0 = pick from the chunk size
+  p->variant = cfg->pack_variant;
+  p->launch_blocks = kv_max_launch_blocks((uint32_t)C, (uint32_t)p->P, p->unroll);
+  // staging rings: defaults scale with the pool, capped at 4 GiB (out) and 1 GiB (in)
+  const int64_t pool_bytes = p->R * p->N;
+  auto round_R = [&](int64_t b) { return b / p->R * p->R; };
+  int64_t out_cap = cfg->staging_out_bytes > 0
+                        ? cfg->staging_out_bytes
+                        : std::min<int64_t>(4ll << 30, std::max<int64_t>(2 * p->R, pool_bytes / 4));
+  int64_t in_cap = cfg->staging_in_bytes > 0
+                       ? cfg->staging_in_bytes
+                       : std::min<int64_t>(1ll << 30, std::max<int64_t>(2 * p->R, pool_bytes / 8));
+  out_cap = round_R(out_cap);
+  in_cap = round_R(in_cap);
+  if (out_cap < 2 * p->R || in_cap < 2 * p->R) {
     delete p;
-    return fail(KV_EINVAL, "n_slots must be >= 2");
+    return fail(KV_EINVAL, "staging too small: each ring must hold two block records (%lld bytes)", (long long)(2 * p->R));
   }
-  int64_t slot_bytes;
-  if (cfg->staging_bytes > 0) {
-    slot_bytes = cfg->staging_bytes / (2 * n_slots);
-  } else {
-    int64_t pool_bytes = p->R * p->N;
-    slot_bytes = std::min<int64_t>(256ll << 20, std::max<int64_t>(p->R, pool_bytes / 4));
-  }
-  slot_bytes = slot_bytes / p->R * p->R;
-  if (slot_bytes < p->R) {
-    delete p;
-    return fail(KV_EINVAL, "staging too small: a ring slot must hold one block record (%lld bytes)", (long long)p->R);
-  }
+  auto piece_blocks = [&](int64_t cap, int64_t dflt_bytes) {
+    int64_t b = cfg->max_piece_bytes > 0 ? cfg->max_piece_bytes : dflt_bytes;
+    b = std::min(b, cap / 2);  // two pieces fit, so a large call can pipeline
+    return std::max<int64_t>(1, b / p->R);
+  };
+  p->ring_out.cap = out_cap;
+  p->ring_out.piece_blocks = piece_blocks(out_cap, p->launch_blocks * p->R);
+  p->ring_in.cap = in_cap;
+  p->ring_in.piece_blocks = piece_blocks(in_cap, 256ll << 20);
   p->arena_blocks = cfg->host_bytes / p->R;
   p->arena.insert(0, p->arena_blocks);
   p->alloc.init(p->N);
@@ -751,15 +832,13 @@ int32_t kv_pool_create(const kv_pool_config_t* cfg, kv_pool_t** out) {
     if (cfg->staging_base) {
       p->staging = (char*)cfg->staging_base;
     } else {
-      hipError_t e = hipMalloc((void**)&p->staging, (size_t)(slot_bytes * n_slots * 2));
-      if (e != hipSuccess) return bail(fail(KV_ENOMEM_GPU, "hipMalloc(staging %lld): %s", (long long)(slot_bytes * n_slots * 2), hipGetErrorString(e)));
+      hipError_t e = hipMalloc((void**)&p->staging, (size_t)(out_cap + in_cap));
+      if (e != hipSuccess) return bail(fail(KV_ENOMEM_GPU, "hipMalloc(staging %lld): %s", (long long)(out_cap + in_cap), hipGetErrorString(e)));
       p->own_staging = true;
     }
   }
-  int32_t rc;
-  if ((rc = make_ring(p, &p->ring_out, p->staging, slot_bytes, n_slots))) return bail(rc);
-  if ((rc = make_ring(p, &p->ring_in, p->staging ? p->staging + slot_bytes * n_slots : nullptr, slot_bytes, n_slots)))
-    return bail(rc);
+  p->ring_out.base = p->staging;
+  p->ring_in.base = p->staging ? p->staging + out_cap : nullptr;
   p->st.host_arena_bytes = p->arena_blocks * p->R;
   *out = p;
   return KV_OK;
@@ -1117,11 +1196,8 @@ int32_t kv_hbm_probe(int64_t bytes, int32_t reps, double* out_gbps) {
   PROBE_TRY(hipMemsetAsync(a, 1, (size_t)bytes, s));
   PROBE_TRY(hipEventCreate(&e0));
   PROBE_TRY(hipEventCreate(&e1));
-  int dev = 0, cus = 256;
-  PROBE_TRY(hipGetDevice(&dev));
-  PROBE_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
   for (int r = 0; r < reps + 1; ++r) {
-    PROBE_TRY(kv_launch_linear_copy(b, a, bytes, cus * 8, s, e0, e1));
+    PROBE_TRY(kv_launch_linear_copy(b, a, bytes, s, e0, e1));
     PROBE_TRY(hipStreamSynchronize(s));
     float ms = 0.f;
     PROBE_TRY(hipEventElapsedTime(&ms, e0, e1));

@@ -35,9 +35,11 @@ class kv_pool_config_t(C.Structure):
         ("n_layers", C.c_int32), ("n_kv_heads", C.c_int32), ("head_dim", C.c_int32),
         ("block_size", C.c_int32), ("elt_bytes", C.c_int32), ("flags", C.c_int32),
         ("n_gpu_blocks", C.c_int64), ("gpu_base", C.c_void_p), ("host_bytes", C.c_int64),
-        ("staging_base", C.c_void_p), ("staging_bytes", C.c_int64), ("n_slots", C.c_int32),
-        ("host_slack_blocks", C.c_int32), ("copy_chunk_bytes", C.c_int64),
-        ("compute_stream", C.c_void_p), ("gather_grid", C.c_int32), ("reserved", C.c_int32),
+        ("staging_base", C.c_void_p), ("staging_out_bytes", C.c_int64),
+        ("staging_in_bytes", C.c_int64), ("max_piece_bytes", C.c_int64),
+        ("copy_chunk_bytes", C.c_int64), ("compute_stream", C.c_void_p),
+        ("host_slack_blocks", C.c_int32), ("gather_grid", C.c_int32),
+        ("tile_unroll", C.c_int32), ("pack_variant", C.c_int32),
     ]
 
 
@@ -137,15 +139,18 @@ class KVPool:
     """Owner of one ``kv_pool_t*``.  Methods carry the C functions' names."""
 
     def __init__(self, *, n_layers, n_kv_heads, head_dim, block_size, elt_bytes, n_gpu_blocks,
-                 gpu_base=0, host_bytes=0, staging_base=0, staging_bytes=0, n_slots=0,
+                 gpu_base=0, host_bytes=0, staging_base=0, staging_out_bytes=0, staging_in_bytes=0,
+                 max_piece_bytes=0,
                  host_slack_blocks=-1, copy_chunk_bytes=0, compute_stream=0, flags=0,
-                 gather_grid=0, tile_unroll=0):
+                 gather_grid=0, tile_unroll=0, pack_variant=0):
         cfg = kv_pool_config_t(
             n_layers=n_layers, n_kv_heads=n_kv_heads, head_dim=head_dim, block_size=block_size,
             elt_bytes=elt_bytes, flags=flags, n_gpu_blocks=n_gpu_blocks, gpu_base=gpu_base or None,
-            host_bytes=host_bytes, staging_base=staging_base or None, staging_bytes=staging_bytes,
-            n_slots=n_slots, host_slack_blocks=host_slack_blocks, copy_chunk_bytes=copy_chunk_bytes,
-            compute_stream=compute_stream or None, gather_grid=gather_grid, reserved=tile_unroll)
+            host_bytes=host_bytes, staging_base=staging_base or None,
+            staging_out_bytes=staging_out_bytes, staging_in_bytes=staging_in_bytes,
+            max_piece_bytes=max_piece_bytes, copy_chunk_bytes=copy_chunk_bytes,
+            compute_stream=compute_stream or None, host_slack_blocks=host_slack_blocks,
+            gather_grid=gather_grid, tile_unroll=tile_unroll, pack_variant=pack_variant)
         self._h = C.c_void_p()
         _check(lib.kv_pool_create(C.byref(cfg), C.byref(self._h)))
         self.P = 2 * n_layers

@@ -54,7 +54,7 @@ def test_create_rejects_bad_configs(kv):
         kv.KVPool(n_layers=s.n_layers, n_kv_heads=s.n_kv_heads, head_dim=s.head_dim,
                   block_size=s.block_size, elt_bytes=s.elt_bytes, n_gpu_blocks=s.n_blocks)
     with pytest.raises(kv.KVError):  # a ring slot must hold one block record
-        plan_pool(kv, s, staging_bytes=1024)
+        plan_pool(kv, s, staging_out_bytes=1024)
 
 
 def test_validation_errors_and_no_effect(kv):
@@ -202,16 +202,16 @@ def test_plan_counts_copies_and_launches(kv):
     """Host-side plan of one swap: launches per ring slot, one copy per run of adjacent host
     records, copies cut at copy_chunk_bytes."""
     shape = synth.TINY  # R = 32 KiB
-    p = plan_pool(kv, shape, host_blocks=256, staging_bytes=2 * 2 * 4 * shape.R, n_slots=2,
-                  copy_chunk_bytes=3 * shape.R)
+    p = plan_pool(kv, shape, host_blocks=256, staging_out_bytes=8 * shape.R,
+                  staging_in_bytes=8 * shape.R, copy_chunk_bytes=3 * shape.R)
     t = np.arange(10, dtype=np.int32)
     p.swap_out(0, t)
     st = p.kv_stats()
-    assert st["gather_launches"] == 3          # slots of 4 blocks: 4 + 4 + 2
+    assert st["gather_launches"] == 3          # pieces of 4 blocks (half the ring): 4 + 4 + 2
     assert st["d2h_copies"] == 2 + 2 + 1       # 4 records -> 3 + 1, 2 records -> 1
     dirty = np.array([1, 0, 1, 1, 0, 0, 0, 1, 1, 1], np.uint8)
     assert p.swap_out_delta(0, t, dirty) == 6
     st2 = p.kv_stats()
-    # moved j = 0 | 2 3 | 7 8 9 -> slot A holds 0,2,3,7 (runs 0 | 2-3 | 7), slot B holds 8,9
+    # moved j = 0 | 2 3 | 7 8 9 -> piece A holds 0,2,3,7 (runs 0 | 2-3 | 7), piece B holds 8,9
     assert st2["gather_launches"] - st["gather_launches"] == 2
     assert st2["d2h_copies"] - st["d2h_copies"] == 3 + 1

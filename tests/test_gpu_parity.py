@@ -105,10 +105,11 @@ def test_shapes_and_ragged_chunks(harness, L, H, D, B, e, N):
     h.assert_pool_equal()
 
 
+@pytest.mark.parametrize("variant", [0, 1])
 @pytest.mark.parametrize("unroll", [1, 2, 4, 8])
-def test_every_tile_width(harness, unroll):
+def test_every_tile_width_and_kernel_variant(harness, unroll, variant):
     shape = synth.KVShape("s", 2, 6, 80, 16, 2, 80, "bf16")  # C = 30720: full for U<=2, ragged for 4, 8
-    h = harness(shape, cfg=4, fill="random", tile_unroll=unroll)
+    h = harness(shape, cfg=4, fill="random", tile_unroll=unroll, pack_variant=variant)
     rng = synth.rng_for(4)
     t = rng.permutation(80)[:33].astype(np.int32)
     t2 = rng.permutation(80)[:33].astype(np.int32)
@@ -123,8 +124,10 @@ def test_every_tile_width(harness, unroll):
 
 def test_ring_wraps_when_request_exceeds_staging(harness):
     shape = synth.TINY
-    # 2 directions x 2 slots x 3 block records: a 16-block request needs 6 slot uses
-    h = harness(shape, cfg=5, staging_bytes=2 * 2 * 3 * shape.R, n_slots=2, copy_chunk_bytes=40000)
+    # rings of 7 block records, pieces of 3: a 16-block request wraps the ring twice and
+    # has to interleave gathers with copies
+    h = harness(shape, cfg=5, staging_out_bytes=7 * shape.R, staging_in_bytes=7 * shape.R,
+                max_piece_bytes=3 * shape.R, copy_chunk_bytes=40000)
     rng = synth.rng_for(5)
     tables = synth.deal_tables(rng, shape.n_blocks, [16, 7, 16, 1])
     tables2 = synth.deal_tables(rng, shape.n_blocks, [16, 7, 16, 1])
@@ -143,10 +146,11 @@ def test_ring_wraps_when_request_exceeds_staging(harness):
     assert st["d2h_copies"] > st["gather_launches"]  # copies are also cut at 40000 bytes
 
 
-def test_more_blocks_than_one_launch_carries(harness):
-    """A launch carries at most 896 table entries: 2500 blocks need 3 launches per slot."""
+@pytest.mark.parametrize("variant", [0, 1])
+def test_more_blocks_than_one_launch_carries(harness, variant):
+    """A launch carries at most 896 table entries: 2500 blocks need 3 launches."""
     shape = synth.KVShape("s", 1, 1, 32, 16, 2, 4096, "fp16")  # C = 1 KiB, R = 2 KiB
-    h = harness(shape, cfg=6, fill="random")
+    h = harness(shape, cfg=6, fill="random", pack_variant=variant)
     rng = synth.rng_for(6)
     t = rng.permutation(4096)[:2500].astype(np.int32)
     t2 = rng.permutation(4096)[:2500].astype(np.int32)
