@@ -32,7 +32,9 @@ def log(*a):
 
 def percentile(xs, q):
     import numpy as np
-    return float(np.percentile(np.asarray(xs, dtype=np.float64), q))
+    if len(xs) == 0:
+        return None
+    return round(float(np.percentile(np.asarray(xs, dtype=np.float64), q)), 3)
 
 
 def cpu_baseline(work, budget_s=12.0):
@@ -126,14 +128,14 @@ def main() -> int:
 
     for _ in range(args.warmup):
         step()
-    pool.kv_profile_reset()
+    n_warm = len(pool.kv_profile_read())  # also waits for the warm-up to finish
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    recs = pool.kv_profile_read()
+    recs = pool.kv_profile_read()[n_warm:]  # launches and copies of the timed region only
 
     def agg(kind):
         rs = [r for r in recs if r[0] == kind]
@@ -181,30 +183,34 @@ def main() -> int:
         cur, nxt = nxt, cur
     # overlapped switch: victim i leaves while victim i-1 resumes (both directions at once)
     ov_ms = []
-    pool.swap_out(victims[0], cur[0])
-    pool.kv_wait(victims[0])
-    for i in range(1, len(victims)):
+    if args.latency_reps > 0:
+        pool.swap_out(victims[0], cur[0])
+        pool.kv_wait(victims[0])
+    for i in range(1, len(victims) if args.latency_reps > 0 else 0):
         t_a = time.perf_counter()
         pool.swap_out(victims[i], cur[i])
         pool.swap_in(victims[i - 1], nxt[i - 1])
         pool.kv_wait(victims[i])
         pool.kv_wait(victims[i - 1])
         ov_ms.append((time.perf_counter() - t_a) * 1e3)
-    pool.swap_in(victims[-1], nxt[-1])
+    if args.latency_reps > 0:
+        pool.swap_in(victims[-1], nxt[-1])
     pool.kv_wait_all()
+    all_recs = pool.kv_profile_read()  # every launch and copy of this process
     stats = pool.kv_stats()
     pool.kv_pool_destroy()
     del gpu
     torch.cuda.empty_cache()
 
+    # HBM bytes per gather launch from the committed rocprofv3 counter summary (FETCH_SIZE +
+    # WRITE_SIZE runs of this same command); null when the summary is not there
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "gather_traffic.json")
+    tpath = os.path.join(ROOT, "profiles", "gather_llama3_8b_cfg2_pmc.txt")
     if os.path.exists(tpath):
-        try:
-            with open(tpath) as f:
-                traffic = json.load(f).get("hbm_bytes_per_launch")
-        except Exception:
-            traffic = None
+        with open(tpath) as f:
+            for line in f:
+                if line.startswith("hbm_bytes_per_launch:"):
+                    traffic = int(line.split(":")[1].split()[0])
 
     result = {
         "metric": "KV swap GB/s (out+in), 1 MI355X",
@@ -240,6 +246,11 @@ def main() -> int:
             "scatter_achieved": round(scatter_gbps, 1),
             "scatter_frac": round(scatter_gbps / HBM_PEAK_GBPS, 4),
             "device_copy_kernel_gbps": round(hbm_copy, 1),
+            # every gather launch of this process (warm-up, timed region, sampled check and the
+            # per-request latency phases): the population a kernel trace of this command sees
+            "gather_calls_whole_process": len([r for r in all_recs if r[0] == 0]),
+            "gather_avg_ms_whole_process": round(
+                sum(r[2] for r in all_recs if r[0] == 0) / max(1, len([r for r in all_recs if r[0] == 0])), 4),
         },
         "link": {
             "measured_peak_d2h_gbps": round(link_d2h, 2),
@@ -253,11 +264,11 @@ def main() -> int:
         "switch_latency_ms": {
             "what": "one victim: swap_out call -> done, then swap_in call -> done (sequential), host clock",
             "n": len(sw_ms),
-            "median": round(percentile(sw_ms, 50), 3), "p99": round(percentile(sw_ms, 99), 3),
-            "max": round(max(sw_ms), 3),
-            "out_median": round(percentile(out_ms, 50), 3), "in_median": round(percentile(in_ms, 50), 3),
-            "overlapped_median": round(percentile(ov_ms, 50), 3),
-            "overlapped_p99": round(percentile(ov_ms, 99), 3),
+            "median": percentile(sw_ms, 50), "p99": percentile(sw_ms, 99),
+            "max": percentile(sw_ms, 100),
+            "out_median": percentile(out_ms, 50), "in_median": percentile(in_ms, 50),
+            "overlapped_median": percentile(ov_ms, 50),
+            "overlapped_p99": percentile(ov_ms, 99),
             "median_request_MiB": round(float(np.median([len(t) for t in cur])) * s.R / (1 << 20), 1),
         },
         "verified_samples_ok": ok,
