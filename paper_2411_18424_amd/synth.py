@@ -76,7 +76,7 @@ def normal_elements(rng: np.random.Generator, n_elts: int, dtype: str) -> np.nda
 class PoolContent:
     """Deterministic content of every chunk of a pool.
 
-    A base buffer of W random chunks is drawn once; chunk (plane p, block b)
+    A base buffer of W random chunks (16 MiB) is drawn once; chunk (plane p, block b)
     is base window ``(p*2654435761 + b*40503 + seed) % W`` with its first 16
     bytes replaced by a stamp (magic, seed, plane, block) so that a chunk that
     lands in the wrong place is identified, not merely detected.
@@ -84,7 +84,7 @@ class PoolContent:
 
     MAGIC = 0x4B565357  # "KVSW"
 
-    def __init__(self, shape: KVShape, cfg: int, base_bytes: int = 64 << 20):
+    def __init__(self, shape: KVShape, cfg: int, base_bytes: int = 16 << 20):
         self.shape = shape
         self.seed = SEED_BASE + cfg
         C = shape.C
@@ -127,6 +127,15 @@ class PoolContent:
         out[:, :16] = self.stamp(ps, np.full(ps.shape, b)).view(np.uint8).reshape(-1, 16)
         return out
 
+    def payload(self, ids) -> np.ndarray:
+        """Bytes [len(ids)][P][C] for arbitrary integer ids (fresh KV of appended tokens):
+        the same windows-plus-stamp construction, cheap enough for GiB-sized payloads."""
+        ids = np.asarray(ids, dtype=np.int64)
+        out = np.empty((ids.size, self.shape.P, self.shape.C), dtype=np.uint8)
+        for p in range(self.shape.P):
+            out[:, p, :] = self.plane(p, ids)
+        return out
+
     def fill(self, G: np.ndarray) -> None:
         """Fill a whole pool array G[P][N][C] (uint8) in place."""
         for p in range(self.shape.P):
@@ -149,6 +158,23 @@ class PoolContent:
             torch.index_select(base, 0, idx, out=view[p])
             st = self.stamp(np.full(blocks.shape, p), blocks).view(np.uint8).reshape(-1, 16)
             view[p, :, :16] = torch.from_numpy(st).to(dev)
+        torch.cuda.synchronize()
+
+    def fill_device_blocks(self, gpu_flat, blocks) -> None:
+        """As fill_device(), but only the given physical blocks (pools too large to fill)."""
+        import torch
+        s = self.shape
+        dev = gpu_flat.device
+        view = gpu_flat.view(s.P, s.n_blocks, s.C)
+        base = torch.from_numpy(self.base).to(dev)
+        blocks = np.asarray(blocks, dtype=np.int64)
+        bidx = torch.from_numpy(blocks).to(dev)
+        for p in range(s.P):
+            idx = torch.from_numpy(self.window(np.full(blocks.shape, p), blocks)).to(dev)
+            chunk = torch.index_select(base, 0, idx)
+            st = self.stamp(np.full(blocks.shape, p), blocks).view(np.uint8).reshape(-1, 16)
+            chunk[:, :16] = torch.from_numpy(st).to(dev)
+            view[p, bidx, :] = chunk
         torch.cuda.synchronize()
 
 

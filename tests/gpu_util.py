@@ -68,3 +68,89 @@ class Harness:
 
     def close(self) -> None:
         self.pool.kv_pool_destroy()
+
+
+class SparseHarness:
+    """Full-size pools: the GPU pool has the real N (addresses beyond 4 GiB, up to 0.8 of HBM),
+    the oracle holds only the live blocks in a compact pool and sees every block table through
+    an id map.  What a swap moves does not depend on N, only where it sits does, and that is
+    the GPU side's business; expected bytes always come from the oracle."""
+
+    def __init__(self, shape: synth.KVShape, cfg: int, host_bytes: int, live_blocks, **pool_kw):
+        import torch
+        from paper_2411_18424_amd import kvswap
+
+        self.torch = torch
+        self.kv = kvswap
+        self.shape = shape
+        self.dev = torch.device("cuda:0")
+        live = np.unique(np.asarray(live_blocks, dtype=np.int64))
+        self.live = live
+        self.remap = np.full(shape.n_blocks, -1, dtype=np.int64)
+        self.remap[live] = np.arange(live.size)
+        self.oracle = KVOracle(shape.n_layers, shape.n_kv_heads, shape.head_dim, shape.block_size,
+                               shape.elt_bytes, live.size)
+        self.content = synth.PoolContent(shape, cfg)
+        self.gpu = torch.empty(shape.R * shape.n_blocks, dtype=torch.uint8, device=self.dev)
+        self.view = self.gpu.view(shape.P, shape.n_blocks, shape.C)
+        self.pool = kvswap.KVPool(
+            n_layers=shape.n_layers, n_kv_heads=shape.n_kv_heads, head_dim=shape.head_dim,
+            block_size=shape.block_size, elt_bytes=shape.elt_bytes, n_gpu_blocks=shape.n_blocks,
+            gpu_base=self.gpu.data_ptr(), host_bytes=host_bytes, **pool_kw)
+
+    def t(self, table) -> np.ndarray:
+        """A physical block table as the compact oracle sees it."""
+        ids = self.remap[np.asarray(table, dtype=np.int64)]
+        assert (ids >= 0).all(), "table uses a block that was not declared live"
+        return ids
+
+    def load(self, blocks) -> None:
+        """Give these physical blocks their seeded content on both sides."""
+        blocks = np.asarray(blocks, dtype=np.int64)
+        self.content.fill_device_blocks(self.gpu, blocks)
+        for p in range(self.shape.P):
+            self.oracle.G[p, self.remap[blocks], :] = self.content.plane(p, blocks)
+
+    def stamp_canaries(self, blocks, value: int) -> None:
+        blocks = np.asarray(blocks, dtype=np.int64)
+        idx = self.torch.from_numpy(blocks).to(self.dev)
+        self.view[:, idx, :] = value
+        self.oracle.G[:, self.remap[blocks], :] = value
+        self.torch.cuda.synchronize()
+
+    def gpu_blocks(self, blocks) -> np.ndarray:
+        """Bytes [P][len][C] of physical blocks, downloaded."""
+        idx = self.torch.from_numpy(np.asarray(blocks, dtype=np.int64)).to(self.dev)
+        self.torch.cuda.synchronize()
+        return self.view[:, idx, :].cpu().numpy()
+
+    def assert_blocks_equal(self, blocks, what="") -> None:
+        blocks = np.asarray(blocks, dtype=np.int64)
+        for lo in range(0, blocks.size, 256):  # bounded host memory
+            part = blocks[lo:lo + 256]
+            got = self.gpu_blocks(part)
+            want = self.oracle.G[:, self.remap[part], :]
+            if not np.array_equal(got, want):
+                bad = np.argwhere((got != want).any(axis=2))
+                raise AssertionError("%s pool differs at (plane, index in list): %s ..." % (what, bad[:8].tolist()))
+
+    def assert_image_equal(self, req: int, sample=None) -> None:
+        self.pool.kv_wait(req)
+        got = self.pool.kv_host_view(req)
+        want = self.oracle.host[req]
+        assert got.shape == want.Hq.shape, (got.shape, want.Hq.shape)
+        js = np.arange(got.shape[0]) if sample is None else np.asarray(sample)
+        js = js[want.host_valid[js]]
+        for lo in range(0, js.size, 128):
+            part = js[lo:lo + 128]
+            if not np.array_equal(got[part], want.Hq[part]):
+                bad = np.argwhere((got[part] != want.Hq[part]).any(axis=2))
+                raise AssertionError("host image of req %d differs at (index, plane): %s ..." % (req, bad[:8].tolist()))
+        # first 16 bytes of every chunk (the stamp or whatever the block holds): whole image
+        valid = want.host_valid
+        assert np.array_equal(got[:, :, :16][valid], want.Hq[:, :, :16][valid]), "chunk heads differ"
+
+    def close(self) -> None:
+        self.pool.kv_pool_destroy()
+        del self.view, self.gpu
+        self.torch.cuda.empty_cache()
