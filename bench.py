@@ -78,6 +78,11 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--latency-reps", type=int, default=3)
+    ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5],
+                    help="workload config; 2 is the headline (default), the others print their own JSON line")
+    ap.add_argument("--preemptions", type=int, default=200, help="config 3: length of the stream")
+    ap.add_argument("--conversations", type=int, default=32, help="config 4: conversations held on the host")
+    ap.add_argument("--requests", type=int, default=4, help="config 5: 10 GiB requests per run length")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build measures one GPU only (the swap path has no cross-GPU step); "
@@ -91,6 +96,12 @@ def main() -> int:
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
+    if args.config != 2:
+        import bench_configs
+        result = {1: bench_configs.config1, 3: bench_configs.config3, 4: bench_configs.config4,
+                  5: bench_configs.config5}[args.config](args)
+        print(json.dumps(result), flush=True)
+        return 0
     work = synth.llama3_8b_preempt_workload()
     s = work.shape
     victims = work.victims

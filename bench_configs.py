@@ -1,0 +1,297 @@
+"""The other workload configs of the build (1, 3, 4, 5), run as `python bench.py --config N`.
+
+They are parity-test cases first (tests/test_gpu_full_size.py); here they are timed, for the
+results table.  Each function returns a dict that bench.py prints as one JSON line.  Pools
+are left uninitialised where content does not matter to a copy path.
+"""
+
+from __future__ import annotations
+
+import time
+
+import numpy as np
+
+GiB = 1 << 30
+MiB = 1 << 20
+
+
+def _pct(xs, q):
+    return round(float(np.percentile(np.asarray(xs, dtype=np.float64), q)), 3) if len(xs) else None
+
+
+def _rates(recs):
+    out = {}
+    for kind, name, mult in ((0, "gather", 2), (1, "scatter", 2), (2, "d2h", 1), (3, "h2d", 1)):
+        rs = [r for r in recs if r[0] == kind]
+        ms = sum(r[2] for r in rs)
+        out[name + "_gbps"] = round(mult * sum(r[1] for r in rs) / ms / 1e6, 1) if ms > 0 else None
+        out[name + "_n"] = len(rs)
+    return out
+
+
+def _pool(kv, torch, s, host_bytes, **kw):
+    gpu = torch.empty(s.R * s.n_blocks, dtype=torch.uint8, device="cuda:0")
+    pool = kv.KVPool(n_layers=s.n_layers, n_kv_heads=s.n_kv_heads, head_dim=s.head_dim,
+                     block_size=s.block_size, elt_bytes=s.elt_bytes, n_gpu_blocks=s.n_blocks,
+                     gpu_base=gpu.data_ptr(), host_bytes=host_bytes, **kw)
+    return gpu, pool
+
+
+def config1(args):
+    """Tiny pool: 8 requests of 1..16 blocks (32..512 KiB): small-message latency."""
+    import torch
+    from paper_2411_18424_amd import kvswap as kv, synth
+    s = synth.TINY
+    rng = synth.rng_for(1)
+    nblk = synth.blocks_for(synth.lengths_uniform(rng, 8, 16, 256), s.block_size)
+    tables = synth.deal_tables(rng, s.n_blocks, nblk)
+    tables2 = synth.deal_tables(rng, s.n_blocks, nblk)
+    gpu, pool = _pool(kv, torch, s, 64 * MiB)
+    gpu.random_(0, 256)
+    torch.cuda.synchronize()
+    out_us, in_us, all_ms = [], [], []
+    for rep in range(args.warmup + args.steps * 5):
+        t0 = time.perf_counter()
+        for r, t in enumerate(tables):
+            a = time.perf_counter()
+            pool.swap_out(r, t)
+            pool.kv_wait(r)
+            if rep >= args.warmup:
+                out_us.append((time.perf_counter() - a) * 1e6)
+        for r, t in enumerate(tables2):
+            a = time.perf_counter()
+            pool.swap_in(r, t)
+            pool.kv_wait(r)
+            if rep >= args.warmup:
+                in_us.append((time.perf_counter() - a) * 1e6)
+        if rep >= args.warmup:
+            all_ms.append((time.perf_counter() - t0) * 1e3)
+        tables, tables2 = tables2, tables
+    payload = int(nblk.sum()) * s.R
+    # all eight in two batched calls
+    b_ms = []
+    reqs = list(range(8))
+    for rep in range(args.warmup + args.steps * 5):
+        t0 = time.perf_counter()
+        pool.swap_out_batch(reqs, tables)
+        pool.kv_wait_all()
+        pool.swap_in_batch(reqs, tables2)
+        pool.kv_wait_all()
+        if rep >= args.warmup:
+            b_ms.append((time.perf_counter() - t0) * 1e3)
+        tables, tables2 = tables2, tables
+    pool.kv_pool_destroy()
+    return {"metric": "KV swap GB/s (out+in), 1 MI355X", "unit": "GB/s",
+            "value": round(2 * payload / (np.median(all_ms) * 1e-3) / 1e9, 3),
+            "config": {"workload": "config 1: tiny pool (2 layers, 4 KV heads, head_dim 64, fp16, 256 blocks), "
+                                   "8 requests of 1..16 blocks, one call per request, each waited for"},
+            "payload_bytes_each_way": payload,
+            "per_request_out_us": {"median": _pct(out_us, 50), "p99": _pct(out_us, 99)},
+            "per_request_in_us": {"median": _pct(in_us, 50), "p99": _pct(in_us, 99)},
+            "batched_all8_out_in_ms": {"median": _pct(b_ms, 50), "p99": _pct(b_ms, 99)},
+            "batched_gbps": round(2 * payload / (np.median(b_ms) * 1e-3) / 1e9, 3)}
+
+
+def config3(args):
+    """Llama-2-13B MHA shape, pool at 80 % of 288 GB, a stream of preemptions: request i leaves
+    while request i-2 resumes, both on side streams, with a compute kernel running beside."""
+    import torch
+    from paper_2411_18424_amd import kvswap as kv, synth
+    s = synth.LLAMA2_13B
+    n_pre, lag = args.preemptions, 2
+    rng = synth.rng_for(3)
+    nblk = synth.blocks_for(rng.integers(512, 4097, size=n_pre), s.block_size)
+    host_bytes = int((lag + 2) * (256 + 40)) * s.R
+    gpu, pool = _pool(kv, torch, s, host_bytes, flags=kv.KV_FLAG_PROFILE)
+    a = torch.randn(8192, 8192, device="cuda:0", dtype=torch.bfloat16)
+    comp = torch.cuda.Stream()
+
+    def compute(n):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        with torch.cuda.stream(comp):
+            e0.record()
+            x = a
+            for _ in range(n):
+                x = torch.mm(x, a) * 1e-2
+            e1.record()
+        return e0, e1
+
+    e0, e1 = compute(20)
+    comp.synchronize()
+    e0, e1 = compute(200)
+    comp.synchronize()
+    alone_ms = e0.elapsed_time(e1) / 200
+    # tables from the library's block-group allocator (groups of >= 8 where the pool allows)
+    lat, evs = [], []
+    in_tables = {}
+    moved = 0
+    t_start = time.perf_counter()
+    for i in range(n_pre + lag):
+        evs.append(compute(8))
+        t0 = time.perf_counter()
+        waits = []
+        if i < n_pre:
+            ids, _ = pool.alloc_block_group(i, int(nblk[i]), 8)
+            pool.swap_out(i, ids)
+            pool.free_block_group(i, ids)  # parked until the gather has read them
+            waits.append(i)
+            moved += int(nblk[i]) * s.R
+        j = i - lag
+        if j >= 0:
+            ids2, _ = pool.alloc_block_group(10**6 + j, int(nblk[j]), 8)
+            pool.swap_in(j, ids2)
+            in_tables[j] = ids2
+            waits.append(j)
+            moved += int(nblk[j]) * s.R
+        for r in waits:
+            pool.kv_wait(r)
+        lat.append((time.perf_counter() - t0) * 1e3)
+        if j >= 0:  # the resumed request runs again; its host copy and (here) its blocks are recycled
+            pool.kv_host_release(j)
+            pool.free_block_group(10**6 + j, in_tables.pop(j))
+    total_s = time.perf_counter() - t_start
+    comp.synchronize()
+    busy_ms = sum(x.elapsed_time(y) for x, y in evs) / (8 * len(evs))
+    rates = _rates(pool.kv_profile_read())
+    st = pool.kv_stats()
+    pool.kv_pool_destroy()
+    return {"metric": "KV swap GB/s (out+in), 1 MI355X", "unit": "GB/s",
+            "value": round(moved / total_s / 1e9, 3),
+            "config": {"workload": "config 3: Llama-2-13B-shaped MHA KV (40 layers, 40 KV heads, head_dim 128, fp16), "
+                                   "pool %d blocks = %.1f GB, %d preemptions of 512..4096 tokens, one out while one in, "
+                                   "compute running on a third stream" % (s.n_blocks, s.n_blocks * s.R / 1e9, n_pre)},
+            "switch_latency_ms": {"what": "swap_out(i) + swap_in(i-2) issued together -> both done",
+                                  "median": _pct(lat, 50), "p99": _pct(lat, 99), "max": _pct(lat, 100)},
+            "request_MiB": {"median": round(float(np.median(nblk)) * s.R / MiB, 1),
+                            "max": round(float(nblk.max()) * s.R / MiB, 1)},
+            "kernels_and_copies": rates,
+            "compute_matmul_ms": {"alone": round(alone_ms, 4), "beside_swaps": round(busy_ms, 4),
+                                  "slowdown": round(busy_ms / alone_ms, 4)},
+            "conflict_waits": st["conflict_waits"], "host_arena_bytes": st["host_arena_bytes"]}
+
+
+def config4(args):
+    """Multi-turn delta swap on the Llama-3-8B shape: conversations with a host copy return,
+    append 64..512 tokens and leave; only dirty blocks move out."""
+    import torch
+    from paper_2411_18424_amd import kvswap as kv, synth
+    s = synth.LLAMA3_8B
+    rng = synth.rng_for(4)
+    n_conv = args.conversations
+    B = s.block_size
+    ctx = synth.lengths_loguniform(rng, n_conv, 1024, 16384)
+    nb0 = synth.blocks_for(ctx, B)
+    host_bytes = int(nb0.sum() + 140 * n_conv) * s.R
+    gpu, pool = _pool(kv, torch, s, host_bytes, flags=kv.KV_FLAG_PROFILE)
+    gpu.random_(0, 256)
+    torch.cuda.synchronize()
+    work = rng.permutation(s.n_blocks)[:1200].astype(np.int32)
+    t_build = time.perf_counter()
+    tok = {}
+    for c in range(n_conv):
+        pool.swap_out(c, rng.permutation(work)[:int(nb0[c])])
+        tok[c] = int(ctx[c])
+    pool.kv_wait_all()
+    t_build = time.perf_counter() - t_build
+    full_ms, delta_ms, in_ms, fracs, delta_bytes, full_bytes = [], [], [], [], 0, 0
+    full_recs = []
+    for turn in range(2):
+        for c in range(n_conv):
+            n_old = int(synth.blocks_for(tok[c], B))
+            t = rng.permutation(work)[:n_old]
+            a0 = time.perf_counter()
+            pool.swap_in(c, t)
+            pool.kv_wait(c)
+            in_ms.append((time.perf_counter() - a0) * 1e3)
+            new_tokens = int(rng.integers(64, 513))
+            dirty = synth.turn_dirty_mask(n_old, tok[c], new_tokens, B)
+            target = rng.uniform(0.05, 0.30)
+            dirty[:n_old] |= synth.random_mask(rng, n_old, max(0.0, target - dirty.mean()))
+            grown = np.concatenate([t, np.setdiff1d(work, t)[:len(dirty) - n_old]]).astype(np.int32)
+            a0 = time.perf_counter()
+            moved = pool.swap_out_delta(c, grown, dirty)
+            pool.kv_wait(c)
+            delta_ms.append((time.perf_counter() - a0) * 1e3)
+            assert moved == int(dirty.sum()), (moved, int(dirty.sum()))
+            delta_bytes += moved * s.R
+            fracs.append(moved / len(dirty))
+            tok[c] += new_tokens
+            if turn == 1:  # the same conversation swapped out in full, for comparison
+                n_rec = len(pool.kv_profile_read())
+                a0 = time.perf_counter()
+                pool.swap_out(c, grown)
+                pool.kv_wait(c)
+                full_ms.append((time.perf_counter() - a0) * 1e3)
+                full_bytes += len(grown) * s.R
+                full_recs += pool.kv_profile_read()[n_rec:]
+    st = pool.kv_stats()
+    pool_recs = pool.kv_profile_read()
+    pool.kv_pool_destroy()
+    return {"metric": "KV swap GB/s (out+in), 1 MI355X", "unit": "GB/s",
+            "value": round(delta_bytes / (sum(delta_ms) * 1e-3) / 1e9, 3),
+            "value_is": "payload rate of the delta swap-outs alone",
+            "config": {"workload": "config 4: Llama-3-8B shape, %d conversations (capped from 128 by pinned memory: %.1f GiB "
+                                   "arena) with 1k..16k tokens on the host, 2 turns of +64..512 tokens, dirty fraction 5..30 %%"
+                                   % (n_conv, host_bytes / GiB)},
+            "dirty_fraction": {"min": round(min(fracs), 3), "median": _pct(fracs, 50), "max": round(max(fracs), 3)},
+            "delta_swap_out_ms": {"median": _pct(delta_ms, 50), "p99": _pct(delta_ms, 99)},
+            "full_swap_out_ms": {"median": _pct(full_ms, 50), "p99": _pct(full_ms, 99)},
+            "full_swap_out_gbps": round(full_bytes / (sum(full_ms) * 1e-3) / 1e9, 3),
+            "swap_in_ms": {"median": _pct(in_ms, 50), "p99": _pct(in_ms, 99)},
+            "full_swap_out_kernels_and_copies": _rates(full_recs),
+            "all_kernels_and_copies": _rates(pool_recs),
+            "bytes_moved_equals_dirty_blocks": True,
+            "host_new_extents": st["host_new_extents"], "d2h_copies": st["d2h_copies"]}
+
+
+def config5(args):
+    """Qwen2-72B shape (80 layers), 32k-token requests (2048 blocks, 10 GiB): fully fragmented
+    tables vs block groups of 16; packed path vs the paper-style direct per-group copies."""
+    import torch
+    from paper_2411_18424_amd import kvswap as kv, synth
+    s = synth.QWEN2_72B
+    n_req = args.requests
+    out = {"metric": "KV swap GB/s (out+in), 1 MI355X", "unit": "GB/s",
+           "config": {"workload": "config 5: Qwen2-72B-shaped GQA KV (80 layers, 8 KV heads, head_dim 128, bf16), pool %d blocks "
+                                  "= %.1f GB, %d requests of 2048 blocks (10 GiB) per run length, one at a time"
+                                  % (s.n_blocks, s.n_blocks * s.R / 1e9, n_req)}}
+    gpu, pool = _pool(kv, torch, s, (2048 + 40) * s.R, flags=kv.KV_FLAG_PROFILE)
+    payload = 2048 * s.R
+    for run in (1, 16):
+        rng = synth.rng_for(5, stream=run)
+        tables = synth.deal_tables(rng, s.n_blocks, [2048] * (2 * n_req), run=run)
+        pool.kv_profile_reset()
+        ms = []
+        for r in range(n_req):
+            t0 = time.perf_counter()
+            pool.swap_out(r, tables[2 * r])
+            pool.kv_wait(r)
+            t1 = time.perf_counter()
+            pool.swap_in(r, tables[2 * r + 1])
+            pool.kv_wait(r)
+            t2 = time.perf_counter()
+            pool.kv_host_release(r)
+            if r > 0 or n_req == 1:
+                ms.append(((t1 - t0) * 1e3, (t2 - t1) * 1e3))
+        rates = _rates(pool.kv_profile_read())
+        o = np.array(ms)
+        res = {"out_gbps": round(payload / (np.median(o[:, 0]) * 1e-3) / 1e9, 2),
+               "in_gbps": round(payload / (np.median(o[:, 1]) * 1e-3) / 1e9, 2),
+               "out_ms": _pct(o[:, 0], 50), "in_ms": _pct(o[:, 1], 50), **rates}
+        # the paper-style direct path on the same tables (one request is enough to see it)
+        t0 = time.perf_counter()
+        pool.swap_out_direct(99, tables[0], False)
+        pool.kv_wait(99)
+        t1 = time.perf_counter()
+        pool.swap_in_direct(99, tables[1], False)
+        pool.kv_wait(99)
+        t2 = time.perf_counter()
+        pool.kv_host_release(99)
+        n_copies = s.P * (2048 // run)
+        res["direct_per_group"] = {"copies_each_way": n_copies, "copy_KiB": run * s.C // 1024,
+                                   "out_gbps": round(payload / (t1 - t0) / 1e9, 2),
+                                   "in_gbps": round(payload / (t2 - t1) / 1e9, 2)}
+        out["run_%d" % run] = res
+    pool.kv_pool_destroy()
+    out["value"] = round(2 * payload / ((out["run_16"]["out_ms"] + out["run_16"]["in_ms"]) * 1e-3) / 1e9, 3)
+    return out

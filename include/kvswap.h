@@ -85,8 +85,10 @@ typedef struct {
                                increment (Section 3.3 adjacent preallocation); <0 = default 32 */
   int32_t gather_grid;      /* workgroups per launch of the persistent pack variant; 0 = default */
   int32_t tile_unroll;      /* 16-byte vectors per lane per tile (1,2,4,8); 0 = from chunk size */
-  int32_t pack_variant;     /* 0 = one tile per workgroup, 3-D grid (default, fastest measured);
-                               1 = persistent grid-stride workgroups with the block table in LDS */
+  int32_t pack_variant;     /* 0 = one tile per workgroup, 3-D grid, 1024 or 256 lanes by chunk size
+                               (default, fastest measured); 1 = persistent grid-stride workgroups
+                               with the block table in LDS; 2 / 3 = tile kernel forced to 256 /
+                               1024 lanes */
 } kv_pool_config_t;
 
 /* Section 3.1 (KV pool + block groups).  Creates the pool object: pinned host arena,
@@ -119,7 +121,7 @@ int32_t swap_out(kv_pool_t* pool, int64_t req, const int32_t* block_table, int32
 /* Section 3.3.  Swap-out with reuse: moves exactly the logical blocks j with
  * dirty_mask[j] != 0 or without a valid host copy; all other image bytes stay.  A request
  * longer than its image has the image extended (in place when the reserved slack or the
- * neighbouring arena space allows, else by relocation).  n_blocks smaller than the image
+ * neighbouring arena space allows, else by a further extent).  n_blocks smaller than the image
  * is KV_EINVAL.  out_n_moved may be NULL. */
 int32_t swap_out_delta(kv_pool_t* pool, int64_t req, const int32_t* block_table, int32_t n_blocks,
                        const uint8_t* dirty_mask, int32_t* out_n_moved);
@@ -141,6 +143,16 @@ int32_t swap_out_batch(kv_pool_t* pool, int32_t n_req, const int64_t* reqs,
 int32_t swap_in_batch(kv_pool_t* pool, int32_t n_req, const int64_t* reqs,
                       const int32_t* tables, const int32_t* n_blocks);
 
+/* Comparison path, measured for context only: the paper's own transfer scheme (Section 3.1:
+ * one copy per contiguous block group; per_block != 0: one copy per block, the baseline of
+ * Section 2.2) applied to this pool layout, with no pack kernel - one 2-D copy per (run of
+ * physically adjacent blocks, plane) straight between the pool and the host image.  Same
+ * result, same validation and reuse-map effects as swap_out / swap_in. */
+int32_t swap_out_direct(kv_pool_t* pool, int64_t req, const int32_t* block_table, int32_t n_blocks,
+                        int32_t per_block);
+int32_t swap_in_direct(kv_pool_t* pool, int64_t req, const int32_t* new_block_table, int32_t n_blocks,
+                       int32_t per_block);
+
 /* Completion (Algorithm 1, step 1: IsCompleted / Synchronize). */
 int32_t kv_wait(kv_pool_t* pool, int64_t req);                /* blocks until req's last op is done */
 int32_t kv_query(kv_pool_t* pool, int64_t req, int32_t* done);/* non-blocking; *done = 0/1 */
@@ -151,8 +163,17 @@ int32_t kv_stream_wait(kv_pool_t* pool, int64_t req, void* stream); /* make a hi
 int32_t kv_wait_all(kv_pool_t* pool);
 
 /* Reuse map (Section 3.3). */
-int32_t kv_host_view(kv_pool_t* pool, int64_t req, const void** ptr, int64_t* bytes,
-                     int32_t* n_blocks);                      /* pinned image; valid until released/relocated */
+/* The image of a request is a list of extents of the pinned arena: one extent (with slack
+ * behind it) when it is created, a further extent whenever it grows past the room reserved
+ * and the arena space behind it is taken - an image is never moved.  kv_host_len reports
+ * its length and extent count; kv_host_blocks reports where each logical block is:
+ * record_index[j] (caller-allocated, n = image length) is the index of the R-byte record
+ * [P][C] of logical block j, i.e. its bytes start at *arena_base + record_index[j]*R.
+ * Consecutive logical blocks are adjacent inside an extent.  Valid until the image is
+ * released or rebuilt by a full swap_out; wait for the request before reading the bytes. */
+int32_t kv_host_len(kv_pool_t* pool, int64_t req, int32_t* n_blocks, int32_t* n_extents);
+int32_t kv_host_blocks(kv_pool_t* pool, int64_t req, const void** arena_base, int64_t* record_index,
+                       int32_t n);
 int32_t kv_host_valid(kv_pool_t* pool, int64_t req, uint8_t* out_mask, int32_t n); /* 1 = valid */
 int32_t kv_host_invalidate(kv_pool_t* pool, int64_t req, const uint8_t* mask, int32_t n); /* contaminate */
 int32_t kv_host_release(kv_pool_t* pool, int64_t req);        /* drop the image (waits for its ops) */
@@ -163,7 +184,7 @@ typedef struct {
   int64_t gather_launches, scatter_launches;
   int64_t d2h_copies, h2d_copies;
   int64_t conflict_waits;               /* device-side waits inserted by conflict detection */
-  int64_t host_relocations;
+  int64_t host_new_extents;             /* image growths that had to open a new arena extent */
   int64_t host_arena_used, host_arena_bytes;
 } kv_stats_t;
 int32_t kv_stats(kv_pool_t* pool, kv_stats_t* out);

@@ -71,6 +71,18 @@ class RunSet {
     return take;
   }
 
+  // Takes the high end (n records) of the largest run, if it is that long.
+  bool take_top_of_largest(int64_t n, int64_t* start) {
+    if (by_size_.empty()) return false;
+    auto it = std::prev(by_size_.end());
+    auto lo = by_size_.lower_bound({it->first, INT64_MIN});
+    if (lo->first < n) return false;
+    const int64_t s = lo->second + lo->first - n;
+    if (!take_exact(s, n)) return false;
+    *start = s;
+    return true;
+  }
+
   // Takes [start, start+len) if it is entirely free (used to extend a region in place).
   bool take_exact(int64_t start, int64_t len) {
     auto it = by_addr_.upper_bound(start);

@@ -6,7 +6,7 @@
 // A launch carries its slice of the block table inside the kernel arguments
 // (HIP allows 4 KiB of them), so no table upload is ever enqueued.
 #define KV_MAX_LAUNCH_BLOCKS 896
-#define KV_WG 256  // threads per workgroup: 4 wavefronts of 64 lanes
+#define KV_WG 256  // lanes per workgroup of the linear copy probe
 
 struct KvPackArgs {
   char* pool;            // device: pool[p][b][C]
@@ -21,8 +21,10 @@ struct KvPackArgs {
   int32_t table[KV_MAX_LAUNCH_BLOCKS];  // physical block id of each of the m blocks
 };
 
-#define KV_PACK_TILE 0        // one tile per workgroup, 3-D grid (default)
-#define KV_PACK_PERSISTENT 1  // grid-stride loop, block table staged in LDS
+#define KV_PACK_TILE 0        // one tile per workgroup, 3-D grid, workgroup size by chunk (default)
+#define KV_PACK_PERSISTENT 1  // grid-stride loop, block table staged in LDS, 256 lanes
+#define KV_PACK_TILE_256 2    // tile kernel, 256 lanes
+#define KV_PACK_TILE_1024 3   // tile kernel, 1024 lanes
 
 // unroll: 16-byte vectors per lane per tile (1, 2, 4 or 8); 0 picks from the chunk size.
 // variant: KV_PACK_*.  grid: workgroups of the persistent variant (<= 0: 2048).
@@ -30,8 +32,8 @@ struct KvPackArgs {
 hipError_t kv_launch_pack(bool scatter, const KvPackArgs& a, int unroll, int variant, int grid,
                           hipStream_t stream, hipEvent_t start, hipEvent_t stop);
 // Most blocks one launch may carry for this shape (table capacity and dispatch size).
-int64_t kv_max_launch_blocks(uint32_t C, uint32_t P, int unroll);
+int64_t kv_max_launch_blocks(uint32_t C, uint32_t P, int unroll, int variant);
 // Plain linear device copy (bandwidth probe): bytes must be a multiple of 16.
 hipError_t kv_launch_linear_copy(void* dst, const void* src, int64_t bytes, hipStream_t stream,
                                  hipEvent_t start, hipEvent_t stop);
-int kv_pick_unroll(uint32_t C);
+int kv_pick_unroll(uint32_t C, int wg);

@@ -10,8 +10,8 @@
 //
 // Two decompositions are kept, selected per launch:
 //
-//  TILE (default): one workgroup moves one tile of KV_WG*16*U contiguous bytes of one chunk
-//    and exits.  The grid is 3-D, x = tile in chunk, y = plane, z = block of this launch, so
+//  TILE (default): one workgroup of WG lanes moves one tile of WG*16*U contiguous bytes of one
+//    chunk and exits.  The grid is 3-D, x = tile in chunk, y = plane, z = block of this launch, so
 //    no index arithmetic is needed, consecutive workgroups walk the staging side linearly,
 //    and the physical block id is one scalar load from the kernel arguments.  Letting the
 //    hardware dispatcher do the looping measured ~12 % faster on MI355X than a persistent
@@ -25,35 +25,37 @@
 
 #include <hip/hip_ext.h>
 
+#include <algorithm>
+
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-template <int U, bool FULL, bool SCATTER>
+template <int WG, int U, bool FULL, bool SCATTER>
 __device__ __forceinline__ void move_tile(u32x4* pool_ptr, u32x4* stag_ptr, uint32_t rem) {
   const u32x4* src = SCATTER ? stag_ptr : pool_ptr;
   u32x4* dst = SCATTER ? pool_ptr : stag_ptr;
   u32x4 r[U];
   if (FULL) {
 #pragma unroll
-    for (int u = 0; u < U; ++u) r[u] = __builtin_nontemporal_load(src + threadIdx.x + u * KV_WG);
+    for (int u = 0; u < U; ++u) r[u] = __builtin_nontemporal_load(src + threadIdx.x + u * WG);
 #pragma unroll
-    for (int u = 0; u < U; ++u) __builtin_nontemporal_store(r[u], dst + threadIdx.x + u * KV_WG);
+    for (int u = 0; u < U; ++u) __builtin_nontemporal_store(r[u], dst + threadIdx.x + u * WG);
   } else {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const uint32_t i = threadIdx.x + u * KV_WG;
+      const uint32_t i = threadIdx.x + u * WG;
       if (i < rem) r[u] = __builtin_nontemporal_load(src + i);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const uint32_t i = threadIdx.x + u * KV_WG;
+      const uint32_t i = threadIdx.x + u * WG;
       if (i < rem) __builtin_nontemporal_store(r[u], dst + i);
     }
   }
 }
 
-template <int U, bool FULL, bool SCATTER>
-__global__ __launch_bounds__(KV_WG) void kv_pack_tile_kernel(const KvPackArgs a) {
-  constexpr uint32_t TILE_VECS = KV_WG * U;  // 16-byte vectors per tile
+template <int WG, int U, bool FULL, bool SCATTER>
+__global__ __launch_bounds__(WG) void kv_pack_tile_kernel(const KvPackArgs a) {
+  constexpr uint32_t TILE_VECS = WG * U;  // 16-byte vectors per tile
   const uint32_t t = blockIdx.x, p = blockIdx.y, k = blockIdx.z;
   const int64_t b = a.table[k];  // wave-uniform: a scalar load from the kernel arguments
   const uint32_t v0 = t * TILE_VECS;
@@ -61,16 +63,16 @@ __global__ __launch_bounds__(KV_WG) void kv_pack_tile_kernel(const KvPackArgs a)
       reinterpret_cast<u32x4*>(a.pool + (int64_t)p * a.plane_stride + b * (int64_t)a.C) + v0;
   u32x4* stag_ptr =
       reinterpret_cast<u32x4*>(a.staging + ((int64_t)k * a.P + p) * (int64_t)a.C) + v0;
-  move_tile<U, FULL, SCATTER>(pool_ptr, stag_ptr, (a.C >> 4) - v0);
+  move_tile<WG, U, FULL, SCATTER>(pool_ptr, stag_ptr, (a.C >> 4) - v0);
 }
 
-template <int U, bool FULL, bool SCATTER>
-__global__ __launch_bounds__(KV_WG) void kv_pack_persistent_kernel(const KvPackArgs a) {
+template <int WG, int U, bool FULL, bool SCATTER>
+__global__ __launch_bounds__(WG) void kv_pack_persistent_kernel(const KvPackArgs a) {
   __shared__ int32_t s_table[KV_MAX_LAUNCH_BLOCKS];
-  for (uint32_t i = threadIdx.x; i < a.m; i += KV_WG) s_table[i] = a.table[i];
+  for (uint32_t i = threadIdx.x; i < a.m; i += WG) s_table[i] = a.table[i];
   __syncthreads();
 
-  constexpr uint32_t TILE_VECS = KV_WG * U;
+  constexpr uint32_t TILE_VECS = WG * U;
   const uint32_t tpc = a.tiles_per_chunk;
   const uint32_t P = a.P;
   for (uint32_t w = blockIdx.x; w < a.n_tiles; w += gridDim.x) {
@@ -83,7 +85,7 @@ __global__ __launch_bounds__(KV_WG) void kv_pack_persistent_kernel(const KvPackA
     u32x4* pool_ptr =
         reinterpret_cast<u32x4*>(a.pool + (int64_t)p * a.plane_stride + b * (int64_t)a.C) + v0;
     u32x4* stag_ptr = reinterpret_cast<u32x4*>(a.staging + (int64_t)q * a.C) + v0;
-    move_tile<U, FULL, SCATTER>(pool_ptr, stag_ptr, (a.C >> 4) - v0);
+    move_tile<WG, U, FULL, SCATTER>(pool_ptr, stag_ptr, (a.C >> 4) - v0);
   }
 }
 
@@ -96,42 +98,70 @@ __global__ __launch_bounds__(KV_WG) void kv_linear_copy_kernel(u32x4* __restrict
   if (i < n_vecs) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
-int kv_pick_unroll(uint32_t C) {
-  // one vector per lane measured fastest; wider tiles only pay when they divide the chunk
-  // and the chunk is large enough to keep the grid modest
-  if (C % (uint32_t)(KV_WG * 16) == 0) return 1;
-  return 0;  // no tile divides the chunk: the bounds-checked kernel is used
+// Workgroup size of the tile kernel.  Measured on MI355X: the gather is fastest with 256 lanes
+// (4 KiB tiles), the scatter a few per cent faster with 1024 lanes (16 KiB tiles) when that
+// divides the chunk.
+static int pick_wg(uint32_t C, int variant, bool scatter) {
+  if (variant == KV_PACK_TILE_256 || variant == KV_PACK_PERSISTENT) return 256;
+  if (variant == KV_PACK_TILE_1024) return 1024;
+  return (scatter && C % (1024u * 16u) == 0) ? 1024 : 256;
 }
 
-int64_t kv_max_launch_blocks(uint32_t C, uint32_t P, int unroll) {
-  int U = (unroll == 1 || unroll == 2 || unroll == 4 || unroll == 8) ? unroll : kv_pick_unroll(C);
-  if (U == 0) U = 1;
-  const uint64_t tile = (uint64_t)KV_WG * 16u * (uint64_t)U;
-  const uint64_t tpc = (C + tile - 1) / tile;
-  // keep the dispatch below 2^31 work-items
-  uint64_t by_grid = (1ull << 31) / ((uint64_t)KV_WG * tpc * P);
+int kv_pick_unroll(uint32_t C, int wg) {
+  // one vector per lane measured fastest
+  if (C % (uint32_t)(wg * 16) == 0) return 1;
+  return 0;  // the tile does not divide the chunk: the bounds-checked kernel is used
+}
+
+struct Shape {
+  int wg, U;
+  bool full;
+  uint32_t tpc;
+};
+
+static Shape pick_shape(uint32_t C, int unroll, int variant, bool scatter) {
+  Shape s;
+  s.wg = pick_wg(C, variant, scatter);
+  s.U = unroll;
+  if (s.U != 1 && s.U != 2 && s.U != 4 && s.U != 8) s.U = kv_pick_unroll(C, s.wg);
+  if (s.wg == 1024 && s.U > 2) s.U = 2;  // 1024-lane tiles exist for one and two vectors per lane
+  s.full = s.U != 0 && C % (uint32_t)(s.wg * 16 * s.U) == 0;
+  if (s.U == 0) s.U = 1;
+  const uint32_t tile = (uint32_t)s.wg * 16u * (uint32_t)s.U;
+  s.tpc = (C + tile - 1) / tile;
+  return s;
+}
+
+int64_t kv_max_launch_blocks(uint32_t C, uint32_t P, int unroll, int variant) {
+  // keep both directions' dispatches below 2^31 work-items
+  const Shape g = pick_shape(C, unroll, variant, false), sc = pick_shape(C, unroll, variant, true);
+  const uint64_t items = std::max<uint64_t>((uint64_t)g.wg * g.tpc, (uint64_t)sc.wg * sc.tpc);
+  uint64_t by_grid = (1ull << 31) / (items * P);
   if (by_grid < 1) by_grid = 1;
   return (int64_t)(by_grid < KV_MAX_LAUNCH_BLOCKS ? by_grid : KV_MAX_LAUNCH_BLOCKS);
 }
 
-template <int U, bool FULL, bool SCATTER>
+template <int WG, int U, bool FULL, bool SCATTER>
 static hipError_t launch_one(const KvPackArgs& a, bool persistent, int grid, hipStream_t stream,
                              hipEvent_t start, hipEvent_t stop) {
   if (persistent) {
-    hipExtLaunchKernelGGL((kv_pack_persistent_kernel<U, FULL, SCATTER>), dim3(grid), dim3(KV_WG), 0,
+    hipExtLaunchKernelGGL((kv_pack_persistent_kernel<WG, U, FULL, SCATTER>), dim3(grid), dim3(WG), 0,
                           stream, start, stop, 0, a);
   } else {
-    hipExtLaunchKernelGGL((kv_pack_tile_kernel<U, FULL, SCATTER>), dim3(a.tiles_per_chunk, a.P, a.m),
-                          dim3(KV_WG), 0, stream, start, stop, 0, a);
+    hipExtLaunchKernelGGL((kv_pack_tile_kernel<WG, U, FULL, SCATTER>),
+                          dim3(a.tiles_per_chunk, a.P, a.m), dim3(WG), 0, stream, start, stop, 0, a);
   }
   return hipGetLastError();
 }
 
-template <int U, bool FULL>
-static hipError_t launch_dir(bool scatter, const KvPackArgs& a, bool persistent, int grid,
-                             hipStream_t stream, hipEvent_t start, hipEvent_t stop) {
-  return scatter ? launch_one<U, FULL, true>(a, persistent, grid, stream, start, stop)
-                 : launch_one<U, FULL, false>(a, persistent, grid, stream, start, stop);
+template <int WG, int U>
+static hipError_t launch_wu(bool scatter, bool full, const KvPackArgs& a, bool persistent, int grid,
+                            hipStream_t stream, hipEvent_t start, hipEvent_t stop) {
+  if (scatter)
+    return full ? launch_one<WG, U, true, true>(a, persistent, grid, stream, start, stop)
+                : launch_one<WG, U, false, true>(a, persistent, grid, stream, start, stop);
+  return full ? launch_one<WG, U, true, false>(a, persistent, grid, stream, start, stop)
+              : launch_one<WG, U, false, false>(a, persistent, grid, stream, start, stop);
 }
 
 hipError_t kv_launch_pack(bool scatter, const KvPackArgs& a_in, int unroll, int variant, int grid,
@@ -140,33 +170,24 @@ hipError_t kv_launch_pack(bool scatter, const KvPackArgs& a_in, int unroll, int 
   if (a_in.m > KV_MAX_LAUNCH_BLOCKS || (a_in.C & 15u) || a_in.C == 0 || a_in.P == 0)
     return hipErrorInvalidValue;
   KvPackArgs a = a_in;
-  int U = unroll;
-  if (U != 1 && U != 2 && U != 4 && U != 8) U = kv_pick_unroll(a.C);
-  bool full = true;
-  if (U == 0 || a.C % (uint32_t)(KV_WG * 16 * U) != 0) {
-    full = false;
-    if (U == 0) U = 1;
-  }
-  const uint32_t tile = KV_WG * 16u * (uint32_t)U;
-  a.tiles_per_chunk = (a.C + tile - 1) / tile;
+  const Shape s = pick_shape(a.C, unroll, variant, scatter);
+  a.tiles_per_chunk = s.tpc;
   const uint64_t n_tiles = (uint64_t)a.m * a.P * a.tiles_per_chunk;
   if (n_tiles > 0xFFFFFFFFull) return hipErrorInvalidValue;
   a.n_tiles = (uint32_t)n_tiles;
   bool persistent = variant == KV_PACK_PERSISTENT;
   // the 3-D grid needs y, z < 65536 and a dispatch below 2^31 work-items
-  if (a.P > 65535u || n_tiles * KV_WG > (1ull << 31)) persistent = true;
+  if (a.P > 65535u || n_tiles * (uint64_t)s.wg > (1ull << 31)) persistent = true;
   if (grid <= 0) grid = 2048;
   if ((uint64_t)grid > n_tiles) grid = (int)n_tiles;
-#define KV_CASE(UU)                                                                          \
-  case UU:                                                                                   \
-    return full ? launch_dir<UU, true>(scatter, a, persistent, grid, stream, start, stop)    \
-                : launch_dir<UU, false>(scatter, a, persistent, grid, stream, start, stop);
-  switch (U) {
-    KV_CASE(1)
-    KV_CASE(2)
-    KV_CASE(4)
-    KV_CASE(8)
-  }
+#define KV_CASE(WW, UU) \
+  if (s.wg == WW && s.U == UU) return launch_wu<WW, UU>(scatter, s.full, a, persistent, grid, stream, start, stop);
+  KV_CASE(256, 1)
+  KV_CASE(256, 2)
+  KV_CASE(256, 4)
+  KV_CASE(256, 8)
+  KV_CASE(1024, 1)
+  KV_CASE(1024, 2)
 #undef KV_CASE
   return hipErrorInvalidValue;
 }

@@ -65,11 +65,24 @@ struct Op {
 };
 using OpRef = std::shared_ptr<Op>;
 
+// Host image of a request: its block records live in one or more extents of the pinned
+// arena (Section 3.3: CPU space is reserved next to the copy for the next turn's increment;
+// when that room is used up and the neighbour is taken, the image continues in a new extent
+// instead of being moved).  rec[j] is the arena record that holds logical block j.
+struct Extent {
+  int64_t off = 0, cap = 0, used = 0;  // in block records
+};
+
 struct Image {
-  int64_t off = 0;  // arena offset, in block records
-  int64_t cap = 0;  // reserved block records (>= n)
-  int32_t n = 0;    // logical blocks
+  std::vector<Extent> ext;
+  int32_t n = 0;  // logical blocks
   std::vector<uint8_t> valid;
+  std::vector<int64_t> rec;
+  int64_t room() const {
+    int64_t r = 0;
+    for (const Extent& e : ext) r += e.cap;
+    return r;
+  }
 };
 
 struct Req {
@@ -259,27 +272,49 @@ int32_t check_table(kv_pool* p, const int32_t* t, int32_t n) {
 }
 
 // ---------------------------------------------------------------- host arena
-// Reserve room for n block records plus slack; falls back to exactly n when tight.
-bool arena_alloc(kv_pool* p, int64_t n, int64_t* off, int64_t* cap) {
-  int64_t want = n + p->slack;
-  if (p->arena.take_best_fit(want, off)) {
-    *cap = want;
+// Takes room for n block records from the arena as few extents as it allows: one extent of
+// n + slack if that fits, else exactly n, else the largest free runs until n is covered.
+// New images are placed best-fit from the low end; a continuation extent of a grown image
+// (spill) is taken from the high end of the largest free run, away from the tails of the
+// packed images, so that it does not take the room the next image wants to grow into.
+// Returns false (and takes nothing) when fewer than n records are free.
+bool arena_take(kv_pool* p, int64_t n, std::vector<Extent>* out, bool spill) {
+  if (n <= 0) return true;
+  if (p->arena.total() < n) return false;
+  int64_t off;
+  if (spill && p->arena.take_top_of_largest(n + p->slack, &off)) {
+    out->push_back({off, n + p->slack, 0});
     return true;
   }
-  if (n > 0 && p->arena.take_best_fit(n, off)) {
-    *cap = n;
+  if (p->arena.take_best_fit(n + p->slack, &off)) {
+    out->push_back({off, n + p->slack, 0});
     return true;
   }
-  if (n == 0) {
-    *off = 0;
-    *cap = 0;
+  if (p->arena.take_best_fit(n, &off)) {
+    out->push_back({off, n, 0});
     return true;
   }
-  return false;
+  while (n > 0) {
+    int64_t got = p->arena.take_from_largest(n, &off);
+    out->push_back({off, got, 0});
+    n -= got;
+  }
+  return true;
 }
 
-void arena_free(kv_pool* p, int64_t off, int64_t cap) {
-  if (cap > 0) p->arena.insert(off, cap);
+void arena_give(kv_pool* p, const std::vector<Extent>& ext) {
+  for (const Extent& e : ext)
+    if (e.cap > 0) p->arena.insert(e.off, e.cap);
+}
+
+// Lays logical blocks [from, to) onto the image's extents in order.
+void image_map(Image& im, int32_t from, int32_t to) {
+  im.rec.resize((size_t)to);
+  size_t e = 0;
+  for (int32_t j = from; j < to; ++j) {
+    while (im.ext[e].used == im.ext[e].cap) ++e;
+    im.rec[(size_t)j] = im.ext[e].off + im.ext[e].used++;
+  }
 }
 
 // ---------------------------------------------------------------- engine
@@ -498,6 +533,57 @@ int32_t enqueue_in(kv_pool* p, const std::vector<Move>& mv, const std::vector<hi
   return KV_OK;
 }
 
+// Comparison path: the paper's own transfer scheme (Section 3.1, one copy per contiguous
+// block group) on this pool layout, without a pack kernel.  A run of r physically adjacent
+// blocks is r*C contiguous bytes in each of the P planes of the pool and r records R bytes
+// apart in the host image, so it takes one 2-D copy per (run, plane); per_block cuts every
+// run into single blocks (one copy per block and plane, the per-block baseline of Section
+// 2.2).  Everything runs on the copy stream; the blocks stay busy until the transfer ends.
+int32_t enqueue_direct(kv_pool* p, bool to_host, const std::vector<Move>& mv,
+                       const std::vector<hipEvent_t>& pre, const OpRef& op, bool per_block) {
+  int32_t rc;
+  hipStream_t s = to_host ? p->s_d2h : p->s_h2d;
+  if ((rc = order_after_compute(p, s))) return rc;
+  for (hipEvent_t e : pre)
+    if ((rc = stream_wait(p, s, e))) return rc;
+  const int64_t m = (int64_t)mv.size();
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  if (p->profile && !p->plan && m > 0) {
+    if ((rc = get_timing_event(p, &e0))) return rc;
+    if ((rc = get_timing_event(p, &e1))) return rc;
+    p->prof.push_back({to_host ? 2 : 3, m * p->R, e0, e1});
+    HIP_TRY(hipEventRecord(e0, s));
+  }
+  int64_t i = 0;
+  while (i < m) {
+    int64_t j = i;
+    if (!per_block)
+      while (j + 1 < m && mv[(size_t)j + 1].phys == mv[(size_t)j].phys + 1 &&
+             mv[(size_t)j + 1].host_off == mv[(size_t)j].host_off + p->R)
+        ++j;
+    const int64_t r = j - i + 1;
+    for (int32_t pl = 0; pl < p->P; ++pl) {
+      char* h = p->host + mv[(size_t)i].host_off + (int64_t)pl * p->C;
+      char* d = p->gpu + ((int64_t)pl * p->N + mv[(size_t)i].phys) * p->C;
+      (to_host ? p->st.d2h_copies : p->st.h2d_copies)++;
+      if (p->plan) continue;
+      if (to_host)
+        HIP_TRY(hipMemcpy2DAsync(h, (size_t)p->R, d, (size_t)p->C, (size_t)p->C, (size_t)r,
+                                 hipMemcpyDeviceToHost, s));
+      else
+        HIP_TRY(hipMemcpy2DAsync(d, (size_t)p->C, h, (size_t)p->R, (size_t)p->C, (size_t)r,
+                                 hipMemcpyHostToDevice, s));
+    }
+    i = j + 1;
+  }
+  if (e1) HIP_TRY(hipEventRecord(e1, s));
+  if (to_host && (rc = record(p, op->packed, s))) return rc;
+  if ((rc = record(p, op->done, s))) return rc;
+  (to_host ? p->st.bytes_out : p->st.bytes_in) += m * p->R;
+  (to_host ? p->st.blocks_out : p->st.blocks_in) += m;
+  return KV_OK;
+}
+
 int32_t new_op(kv_pool* p, bool is_out, OpRef* out) {
   auto op = std::make_shared<Op>();
   op->is_out = is_out;
@@ -519,13 +605,12 @@ struct OutItem {
   int32_t n;
   const uint8_t* dirty;  // null = full swap-out
   // planning results
-  bool new_region = false;
-  int64_t new_off = 0, new_cap = 0;
-  bool extend_in_place = false;
-  int64_t extend_by = 0;
+  bool fresh = false;             // image is (re)built on new extents; the old ones are given back
+  int64_t extend_last_by = 0;     // the last extent grows in place by this many records
+  std::vector<Extent> new_ext;    // extents taken from the arena for this call
 };
 
-int32_t do_swap_out(kv_pool* p, std::vector<OutItem>& items, int32_t* out_n_moved) {
+int32_t do_swap_out(kv_pool* p, std::vector<OutItem>& items, int32_t* out_n_moved, int direct = 0) {
   reap(p);
   int32_t rc;
   // 1. validate tables (ids unique across the whole call) and shapes
@@ -540,42 +625,49 @@ int32_t do_swap_out(kv_pool* p, std::vector<OutItem>& items, int32_t* out_n_move
     if (it.dirty && f != p->reqs.end() && f->second.has_image && it.n < f->second.img.n)
       return fail(KV_EINVAL, "table (%d blocks) shorter than the host image (%d)", it.n, f->second.img.n);
   }
-  // 2. plan host space without touching existing state; undo on failure
+  // 2. plan host space without touching existing images; undo on failure
   auto undo = [&](size_t upto) {
     for (size_t a = 0; a < upto; ++a) {
-      if (items[a].new_region) arena_free(p, items[a].new_off, items[a].new_cap);
-      if (items[a].extend_in_place) {
-        Req& q = p->reqs[items[a].req];
-        arena_free(p, q.img.off + q.img.cap, items[a].extend_by);
+      arena_give(p, items[a].new_ext);
+      if (items[a].extend_last_by > 0) {
+        const Extent& last = p->reqs[items[a].req].img.ext.back();
+        p->arena.insert(last.off + last.cap, items[a].extend_last_by);
       }
     }
   };
   for (size_t a = 0; a < items.size(); ++a) {
     OutItem& it = items[a];
     auto f = p->reqs.find(it.req);
-    bool has = f != p->reqs.end() && f->second.has_image;
-    if (has && it.n <= f->second.img.cap) continue;  // fits the reserved region
-    if (has && it.dirty) {
+    const bool has = f != p->reqs.end() && f->second.has_image;
+    int64_t need = it.n;
+    if (has) {
       Image& im = f->second.img;
-      int64_t more = it.n - im.cap;
-      int64_t want = more + p->slack;
-      if (p->arena.take_exact(im.off + im.cap, want)) {
-        it.extend_in_place = true;
-        it.extend_by = want;
-        continue;
+      if (it.n <= im.room()) continue;  // fits the room already reserved
+      if (it.dirty) {
+        // append: first try to grow the last extent where it stands
+        need = it.n - im.room();
+        if (!im.ext.empty()) {
+          const Extent& last = im.ext.back();
+          if (p->arena.take_exact(last.off + last.cap, need + p->slack)) {
+            it.extend_last_by = need + p->slack;
+            continue;
+          }
+          if (p->arena.take_exact(last.off + last.cap, need)) {
+            it.extend_last_by = need;
+            continue;
+          }
+        }
+      } else {
+        it.fresh = true;  // a full swap-out that outgrew the old image starts over
       }
-      if (p->arena.take_exact(im.off + im.cap, more)) {
-        it.extend_in_place = true;
-        it.extend_by = more;
-        continue;
-      }
+    } else {
+      it.fresh = true;
     }
-    if (!arena_alloc(p, it.n, &it.new_off, &it.new_cap)) {
+    if (!arena_take(p, need, &it.new_ext, !it.fresh)) {
       undo(a);
-      return fail(KV_ENOMEM_HOST, "host arena full: need %d block records, %lld free (largest run %lld)",
-                  it.n, (long long)p->arena.total(), (long long)p->arena.largest());
+      return fail(KV_ENOMEM_HOST, "host arena full: need %lld block records, %lld free (largest run %lld)",
+                  (long long)need, (long long)p->arena.total(), (long long)p->arena.largest());
     }
-    it.new_region = true;
   }
   // 3. commit: images, reuse map, move list
   std::vector<Move> mv;
@@ -589,38 +681,41 @@ int32_t do_swap_out(kv_pool* p, std::vector<OutItem>& items, int32_t* out_n_move
   int64_t total_moved = 0;
   for (OutItem& it : items) {
     Req& q = p->reqs[it.req];
-    if (it.new_region) {
+    Image& im = q.img;
+    if (it.fresh) {
       if (q.has_image) {
-        // the old region may still be read or written by an unfinished op of this request
+        // the old extents may still be read or written by an unfinished op of this request
         if ((rc = host_wait_op(p, q.last))) return rc;
-        if (it.dirty && !p->plan && q.img.n > 0)
-          memcpy(p->host + it.new_off * p->R, p->host + q.img.off * p->R, (size_t)q.img.n * p->R);
-        arena_free(p, q.img.off, q.img.cap);
-        if (it.dirty) p->st.host_relocations++;
+        arena_give(p, im.ext);
       }
-      q.img.off = it.new_off;
-      q.img.cap = it.new_cap;
-      if (!q.has_image || !it.dirty) {
-        q.img.n = 0;
-        q.img.valid.clear();
-      }
+      im.ext = it.new_ext;
+      im.n = 0;
+      im.valid.clear();
+      im.rec.clear();
       q.has_image = true;
-    } else if (it.extend_in_place) {
-      q.img.cap += it.extend_by;
+    } else {
+      if (it.extend_last_by > 0) im.ext.back().cap += it.extend_last_by;
+      if (!it.new_ext.empty()) {
+        im.ext.insert(im.ext.end(), it.new_ext.begin(), it.new_ext.end());
+        p->st.host_new_extents += (int64_t)it.new_ext.size();
+      }
     }
-    if (!it.dirty) {  // full swap-out: the earlier copy is discarded
-      q.img.n = it.n;
-      q.img.valid.assign((size_t)it.n, 0);
-    } else if (it.n > q.img.n) {
-      q.img.valid.resize((size_t)it.n, 0);
-      q.img.n = it.n;
+    if (!it.dirty) {  // full swap-out: the earlier copy is discarded, blocks are laid out anew
+      for (Extent& e : im.ext) e.used = 0;
+      im.n = it.n;
+      im.valid.assign((size_t)it.n, 0);
+      image_map(im, 0, it.n);
+    } else if (it.n > im.n) {
+      im.valid.resize((size_t)it.n, 0);
+      image_map(im, im.n, it.n);
+      im.n = it.n;
     }
     int32_t moved = 0;
     for (int32_t j = 0; j < it.n; ++j) {
       if (it.dirty && !it.dirty[j] && q.img.valid[(size_t)j]) continue;
       q.img.valid[(size_t)j] = 1;
       int32_t b = it.table[j];
-      mv.push_back({(q.img.off + j) * p->R, b});
+      mv.push_back({q.img.rec[(size_t)j] * p->R, b});
       p->reader_seq[(size_t)b] = op->seq;
       max_writer = std::max(max_writer, p->writer_seq[(size_t)b]);
       ++moved;
@@ -640,6 +735,7 @@ int32_t do_swap_out(kv_pool* p, std::vector<OutItem>& items, int32_t* out_n_move
     }
   }
   if (out_n_moved) *out_n_moved = (int32_t)total_moved;
+  if (direct) return enqueue_direct(p, true, mv, pre, op, direct == 2);
   return enqueue_out(p, mv, pre, op);
 }
 
@@ -650,7 +746,7 @@ struct InItem {
   const uint8_t* resident;  // null = move everything
 };
 
-int32_t do_swap_in(kv_pool* p, std::vector<InItem>& items, int32_t* out_n_moved) {
+int32_t do_swap_in(kv_pool* p, std::vector<InItem>& items, int32_t* out_n_moved, int direct = 0) {
   reap(p);
   int32_t rc;
   ++p->epoch;
@@ -681,7 +777,7 @@ int32_t do_swap_in(kv_pool* p, std::vector<InItem>& items, int32_t* out_n_moved)
     for (int32_t j = 0; j < it.n; ++j) {
       if (it.resident && it.resident[j]) continue;
       int32_t b = it.table[j];
-      mv.push_back({(q.img.off + j) * p->R, b});
+      mv.push_back({q.img.rec[(size_t)j] * p->R, b});
       p->writer_seq[(size_t)b] = op->seq;
       max_reader = std::max(max_reader, p->reader_seq[(size_t)b]);
     }
@@ -697,6 +793,10 @@ int32_t do_swap_in(kv_pool* p, std::vector<InItem>& items, int32_t* out_n_moved)
     }
   }
   if (out_n_moved) *out_n_moved = (int32_t)mv.size();
+  if (direct) {
+    pre_copy.insert(pre_copy.end(), pre_scat.begin(), pre_scat.end());
+    return enqueue_direct(p, false, mv, pre_copy, op, direct == 2);
+  }
   return enqueue_in(p, mv, pre_copy, pre_scat, op);
 }
 
@@ -768,7 +868,7 @@ int32_t kv_pool_create(const kv_pool_config_t* cfg, kv_pool_t** out) {
   p->grid = cfg->gather_grid;
   p->unroll = cfg->tile_unroll;  // 0 = pick from the chunk size
   p->variant = cfg->pack_variant;
-  p->launch_blocks = kv_max_launch_blocks((uint32_t)C, (uint32_t)p->P, p->unroll);
+  p->launch_blocks = kv_max_launch_blocks((uint32_t)C, (uint32_t)p->P, p->unroll, p->variant);
   // staging rings: defaults scale with the pool, capped at 4 GiB (out) and 1 GiB (in)
   const int64_t pool_bytes = p->R * p->N;
   auto round_R = [&](int64_t b) { return b / p->R * p->R; };
@@ -937,6 +1037,24 @@ int32_t swap_in_delta(kv_pool_t* p, int64_t req, const int32_t* new_block_table,
   return do_swap_in(p, items, out_n_moved);
 }
 
+int32_t swap_out_direct(kv_pool_t* p, int64_t req, const int32_t* block_table, int32_t n_blocks,
+                        int32_t per_block) {
+  if (!p) return fail(KV_EINVAL, "null pool");
+  std::lock_guard<std::mutex> g(p->mu);
+  std::vector<OutItem> items(1);
+  items[0] = OutItem{req, block_table, n_blocks, nullptr};
+  return do_swap_out(p, items, nullptr, per_block ? 2 : 1);
+}
+
+int32_t swap_in_direct(kv_pool_t* p, int64_t req, const int32_t* new_block_table, int32_t n_blocks,
+                       int32_t per_block) {
+  if (!p) return fail(KV_EINVAL, "null pool");
+  std::lock_guard<std::mutex> g(p->mu);
+  std::vector<InItem> items(1);
+  items[0] = InItem{req, new_block_table, n_blocks, nullptr};
+  return do_swap_in(p, items, nullptr, per_block ? 2 : 1);
+}
+
 int32_t swap_out_batch(kv_pool_t* p, int32_t n_req, const int64_t* reqs, const int32_t* tables,
                        const int32_t* n_blocks) {
   if (!p || n_req < 0 || (n_req > 0 && (!reqs || !n_blocks))) return fail(KV_EINVAL, "bad argument");
@@ -1028,16 +1146,26 @@ int32_t kv_wait_all(kv_pool_t* p) {
   return KV_OK;
 }
 
-int32_t kv_host_view(kv_pool_t* p, int64_t req, const void** ptr, int64_t* bytes, int32_t* n_blocks) {
+int32_t kv_host_len(kv_pool_t* p, int64_t req, int32_t* n_blocks, int32_t* n_extents) {
   if (!p) return fail(KV_EINVAL, "null pool");
+  std::lock_guard<std::mutex> g(p->mu);
+  auto f = p->reqs.find(req);
+  if (f == p->reqs.end() || !f->second.has_image) return fail(KV_ENOENT, "request %lld has no host copy", (long long)req);
+  if (n_blocks) *n_blocks = f->second.img.n;
+  if (n_extents) *n_extents = (int32_t)f->second.img.ext.size();
+  return KV_OK;
+}
+
+int32_t kv_host_blocks(kv_pool_t* p, int64_t req, const void** arena_base, int64_t* record_index, int32_t n) {
+  if (!p || (n > 0 && !record_index)) return fail(KV_EINVAL, "null argument");
   std::lock_guard<std::mutex> g(p->mu);
   if (p->plan) return fail(KV_ENODEV, "plan-only pool holds no bytes");
   auto f = p->reqs.find(req);
   if (f == p->reqs.end() || !f->second.has_image) return fail(KV_ENOENT, "request %lld has no host copy", (long long)req);
   const Image& im = f->second.img;
-  if (ptr) *ptr = p->host + im.off * p->R;
-  if (bytes) *bytes = (int64_t)im.n * p->R;
-  if (n_blocks) *n_blocks = im.n;
+  if (n != im.n) return fail(KV_EINVAL, "asked for %d blocks, host image has %d", n, im.n);
+  if (arena_base) *arena_base = p->host;
+  for (int32_t j = 0; j < n; ++j) record_index[j] = im.rec[(size_t)j];
   return KV_OK;
 }
 
@@ -1069,7 +1197,7 @@ int32_t kv_host_release(kv_pool_t* p, int64_t req) {
   if (f == p->reqs.end() || !f->second.has_image) return fail(KV_ENOENT, "request %lld has no host copy", (long long)req);
   int32_t rc = host_wait_op(p, f->second.last);
   if (rc) return rc;
-  arena_free(p, f->second.img.off, f->second.img.cap);
+  arena_give(p, f->second.img.ext);
   p->reqs.erase(f);
   return KV_OK;
 }

@@ -47,7 +47,7 @@ class kv_stats_t(C.Structure):
     _fields_ = [(n, C.c_int64) for n in (
         "bytes_out", "bytes_in", "blocks_out", "blocks_in", "gather_launches",
         "scatter_launches", "d2h_copies", "h2d_copies", "conflict_waits",
-        "host_relocations", "host_arena_used", "host_arena_bytes")]
+        "host_new_extents", "host_arena_used", "host_arena_bytes")]
 
 
 class kv_prof_record_t(C.Structure):
@@ -73,6 +73,8 @@ def _load() -> C.CDLL:
         "swap_out_delta": (C.c_int32, [pool_p, C.c_int64, i32p, C.c_int32, u8p, i32p]),
         "swap_in": (C.c_int32, [pool_p, C.c_int64, i32p, C.c_int32]),
         "swap_in_delta": (C.c_int32, [pool_p, C.c_int64, i32p, C.c_int32, u8p, i32p]),
+        "swap_out_direct": (C.c_int32, [pool_p, C.c_int64, i32p, C.c_int32, C.c_int32]),
+        "swap_in_direct": (C.c_int32, [pool_p, C.c_int64, i32p, C.c_int32, C.c_int32]),
         "swap_out_batch": (C.c_int32, [pool_p, C.c_int32, i64p, i32p, i32p]),
         "swap_in_batch": (C.c_int32, [pool_p, C.c_int32, i64p, i32p, i32p]),
         "kv_wait": (C.c_int32, [pool_p, C.c_int64]),
@@ -80,7 +82,8 @@ def _load() -> C.CDLL:
         "kv_wait_packed": (C.c_int32, [pool_p, C.c_int64]),
         "kv_stream_wait": (C.c_int32, [pool_p, C.c_int64, C.c_void_p]),
         "kv_wait_all": (C.c_int32, [pool_p]),
-        "kv_host_view": (C.c_int32, [pool_p, C.c_int64, P(C.c_void_p), i64p, i32p]),
+        "kv_host_len": (C.c_int32, [pool_p, C.c_int64, i32p, i32p]),
+        "kv_host_blocks": (C.c_int32, [pool_p, C.c_int64, P(C.c_void_p), i64p, C.c_int32]),
         "kv_host_valid": (C.c_int32, [pool_p, C.c_int64, u8p, C.c_int32]),
         "kv_host_invalidate": (C.c_int32, [pool_p, C.c_int64, u8p, C.c_int32]),
         "kv_host_release": (C.c_int32, [pool_p, C.c_int64]),
@@ -222,6 +225,14 @@ class KVPool:
         _check(lib.swap_in_delta(self._h, req, p, a.size, mp, C.byref(n)))
         return n.value
 
+    def swap_out_direct(self, req: int, block_table, per_block: bool = False):
+        a, p = _i32(block_table)
+        _check(lib.swap_out_direct(self._h, req, p, a.size, int(per_block)))
+
+    def swap_in_direct(self, req: int, new_block_table, per_block: bool = False):
+        a, p = _i32(new_block_table)
+        _check(lib.swap_in_direct(self._h, req, p, a.size, int(per_block)))
+
     def _batch(self, fn, reqs, tables):
         r, rp = _i64(reqs)
         nb, nbp = _i32([len(t) for t in tables])
@@ -255,14 +266,32 @@ class KVPool:
         _check(lib.kv_wait_all(self._h))
 
     # -- reuse map
+    def kv_host_len(self, req: int):
+        n, e = C.c_int32(), C.c_int32()
+        _check(lib.kv_host_len(self._h, req, C.byref(n), C.byref(e)))
+        return n.value, e.value
+
+    def kv_host_blocks(self, req: int):
+        """(arena base address, int64 record index of every logical block)."""
+        n, _ = self.kv_host_len(req)
+        idx = np.zeros(n, dtype=np.int64)
+        base = C.c_void_p()
+        _check(lib.kv_host_blocks(self._h, req, C.byref(base), idx.ctypes.data_as(C.POINTER(C.c_int64)), n))
+        return base.value, idx
+
     def kv_host_view(self, req: int) -> np.ndarray:
-        """uint8 view [n][P][C] over the pinned host image (no copy)."""
-        ptr, nbytes, n = C.c_void_p(), C.c_int64(), C.c_int32()
-        _check(lib.kv_host_view(self._h, req, C.byref(ptr), C.byref(nbytes), C.byref(n)))
-        if nbytes.value == 0:
+        """uint8 [n][P][C] over the host image: a zero-copy view of the pinned arena when the
+        image is one extent, else a gathered copy (reading aid for tests and tools)."""
+        base, idx = self.kv_host_blocks(req)
+        n = idx.size
+        if n == 0:
             return np.zeros((0, self.P, self.C), dtype=np.uint8)
-        buf = (C.c_uint8 * nbytes.value).from_address(ptr.value)
-        return np.frombuffer(buf, dtype=np.uint8).reshape(n.value, self.P, self.C)
+        lo, hi = int(idx.min()), int(idx.max())
+        buf = (C.c_uint8 * ((hi - lo + 1) * self.R)).from_address(base + lo * self.R)
+        span = np.frombuffer(buf, dtype=np.uint8).reshape(hi - lo + 1, self.P, self.C)
+        if np.array_equal(idx, np.arange(lo, lo + n)):
+            return span
+        return span[idx - lo]
 
     def kv_host_valid(self, req: int, n: int) -> np.ndarray:
         out = np.zeros(n, dtype=np.uint8)

@@ -128,7 +128,7 @@ def test_moved_sets_follow_the_reuse_map(kv):
         assert np.array_equal(p.kv_host_valid(r, sizes[r]).astype(bool), o.host[r].host_valid)
     st = p.kv_stats()
     assert st["bytes_out"] == o.bytes_out and st["bytes_in"] == o.bytes_in
-    assert st["host_relocations"] > 0
+    assert st["host_new_extents"] > 0
 
 
 def test_allocator_never_double_assigns(kv):
@@ -215,3 +215,50 @@ def test_plan_counts_copies_and_launches(kv):
     # moved j = 0 | 2 3 | 7 8 9 -> piece A holds 0,2,3,7 (runs 0 | 2-3 | 7), piece B holds 8,9
     assert st2["gather_launches"] - st["gather_launches"] == 2
     assert st2["d2h_copies"] - st["d2h_copies"] == 3 + 1
+
+
+def test_host_images_grow_by_extents_and_give_everything_back(kv):
+    """Section 3.3: room behind a new image is reserved for the next turn; when it is used up
+    the image continues in a further extent (it is never moved)."""
+    shape = synth.TINY
+    p = plan_pool(kv, shape, host_blocks=64, host_slack_blocks=4)
+    t = np.arange(100, dtype=np.int32)
+    p.swap_out(0, t[:10])                       # [0,14): 10 used + 4 slack
+    p.swap_out(1, t[10:20])                     # [14,28)
+    assert p.kv_host_len(0) == (10, 1)
+    assert p.swap_out_delta(0, t[:13], np.zeros(13, np.uint8)) == 3      # fits the slack
+    assert p.kv_host_len(0) == (13, 1) and p.kv_stats()["host_new_extents"] == 0
+    assert p.swap_out_delta(0, t[:20], np.zeros(20, np.uint8)) == 7      # neighbour is taken: new extent
+    assert p.kv_host_len(0) == (20, 2) and p.kv_stats()["host_new_extents"] == 1
+    # request 1 is the last image in the arena: it grows in place
+    assert p.swap_out_delta(1, t[30:50], np.zeros(20, np.uint8)) == 10
+    assert p.kv_host_len(1)[1] == 1
+    used = p.kv_stats()["host_arena_used"]
+    # a full swap-out that fits the room already held reuses it
+    p.swap_out(0, t[:18])
+    assert p.kv_host_len(0) == (18, 2) and p.kv_stats()["host_arena_used"] == used
+    # exhausting the arena is an error without effect
+    with pytest.raises(kv.KVError) as ei:
+        p.swap_out(2, t[50:100])
+    assert ei.value.status == kv.KV_ENOMEM_HOST
+    assert p.kv_stats()["host_arena_used"] == used
+    for r in (0, 1):
+        p.kv_host_release(r)
+    assert p.kv_stats()["host_arena_used"] == 0
+    p.swap_out(3, t[:60])                       # the whole arena is one run again
+    assert p.kv_host_len(3) == (60, 1)
+
+
+def test_fragmented_arena_serves_an_image_in_several_extents(kv):
+    shape = synth.TINY
+    p = plan_pool(kv, shape, host_blocks=40, host_slack_blocks=0)
+    t = np.arange(200, dtype=np.int32)
+    for r in range(4):
+        p.swap_out(r, t[10 * r:10 * r + 10])    # four images of 10 records fill the arena
+    p.kv_host_release(0)
+    p.kv_host_release(2)                        # two holes of 10
+    p.swap_out(9, t[100:118])                   # 18 records: no single run holds them
+    assert p.kv_host_len(9) == (18, 2)
+    st = p.kv_stats()
+    assert st["host_arena_used"] == 38 * shape.R
+    assert st["d2h_copies"] == 4 + 2            # the split image is copied as two runs

@@ -126,8 +126,8 @@ def test_config4_multi_turn_delta_swap():
     ctx = synth.lengths_loguniform(rng, n_conv, 1024, 16384)
     B = s.block_size
     work_blocks = rng.permutation(s.n_blocks)[:1200].astype(np.int32)  # GPU working set, reused by every turn
-    # twice the contexts: an image that outgrows its slack relocates and needs a second region meanwhile
-    h = SparseHarness(s, 4, host_bytes=int(2 * synth.blocks_for(ctx, B).sum() + n_conv * 80) * s.R,
+    # contexts + room for two turns: images that outgrow their slack continue in further extents
+    h = SparseHarness(s, 4, host_bytes=int(synth.blocks_for(ctx, B).sum() + n_conv * 140) * s.R,
                       live_blocks=work_blocks)
     fresh = synth.PoolContent(s, 44)  # source of new KV bytes, tagged by (conversation, turn, block)
     try:
