@@ -83,6 +83,8 @@ def main() -> int:
     ap.add_argument("--preemptions", type=int, default=200, help="config 3: length of the stream")
     ap.add_argument("--conversations", type=int, default=32, help="config 4: conversations held on the host")
     ap.add_argument("--requests", type=int, default=4, help="config 5: 10 GiB requests per run length")
+    ap.add_argument("--four-streams", action="store_true",
+                    help="give kernels and copies of each direction their own streams (KV_FLAG_FOUR_STREAMS)")
     args = ap.parse_args()
     if args.gpus != 1:
         log("bench.py: this build measures one GPU only (the swap path has no cross-GPU step); "
@@ -125,7 +127,7 @@ def main() -> int:
     pool = kv.KVPool(n_layers=s.n_layers, n_kv_heads=s.n_kv_heads, head_dim=s.head_dim,
                      block_size=s.block_size, elt_bytes=s.elt_bytes, n_gpu_blocks=s.n_blocks,
                      gpu_base=gpu.data_ptr(), host_bytes=payload + 64 * len(victims) * s.R,
-                     flags=kv.KV_FLAG_PROFILE)
+                     flags=kv.KV_FLAG_PROFILE | (kv.KV_FLAG_FOUR_STREAMS if args.four_streams else 0))
     cur = [work.tables[v] for v in victims]
     nxt = list(work.resume_tables)
 
@@ -282,6 +284,7 @@ def main() -> int:
             "overlapped_p99": percentile(ov_ms, 99),
             "median_request_MiB": round(float(np.median([len(t) for t in cur])) * s.R / (1 << 20), 1),
         },
+        "streams": 4 if args.four_streams else 2,
         "verified_samples_ok": ok,
         "stats": {k: stats[k] for k in ("gather_launches", "scatter_launches", "d2h_copies", "h2d_copies")},
     }

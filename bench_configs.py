@@ -102,7 +102,8 @@ def config3(args):
     rng = synth.rng_for(3)
     nblk = synth.blocks_for(rng.integers(512, 4097, size=n_pre), s.block_size)
     host_bytes = int((lag + 2) * (256 + 40)) * s.R
-    gpu, pool = _pool(kv, torch, s, host_bytes, flags=kv.KV_FLAG_PROFILE)
+    gpu, pool = _pool(kv, torch, s, host_bytes,
+                      flags=kv.KV_FLAG_PROFILE | (kv.KV_FLAG_FOUR_STREAMS if args.four_streams else 0))
     a = torch.randn(8192, 8192, device="cuda:0", dtype=torch.bfloat16)
     comp = torch.cuda.Stream()
 
@@ -121,13 +122,15 @@ def config3(args):
     e0, e1 = compute(200)
     comp.synchronize()
     alone_ms = e0.elapsed_time(e1) / 200
+    # about as much compute per iteration as the median swap takes on the link
+    per_iter = max(1, int(float(np.median(nblk)) * s.R / 57e9 * 1e3 / alone_ms))
     # tables from the library's block-group allocator (groups of >= 8 where the pool allows)
     lat, evs = [], []
     in_tables = {}
     moved = 0
     t_start = time.perf_counter()
     for i in range(n_pre + lag):
-        evs.append(compute(8))
+        evs.append(compute(per_iter))  # keeps the compute stream busy for about one iteration
         t0 = time.perf_counter()
         waits = []
         if i < n_pre:
@@ -151,7 +154,7 @@ def config3(args):
             pool.free_block_group(10**6 + j, in_tables.pop(j))
     total_s = time.perf_counter() - t_start
     comp.synchronize()
-    busy_ms = sum(x.elapsed_time(y) for x, y in evs) / (8 * len(evs))
+    busy_ms = sum(x.elapsed_time(y) for x, y in evs) / (per_iter * len(evs))
     rates = _rates(pool.kv_profile_read())
     st = pool.kv_stats()
     pool.kv_pool_destroy()
@@ -165,8 +168,10 @@ def config3(args):
             "request_MiB": {"median": round(float(np.median(nblk)) * s.R / MiB, 1),
                             "max": round(float(nblk.max()) * s.R / MiB, 1)},
             "kernels_and_copies": rates,
-            "compute_matmul_ms": {"alone": round(alone_ms, 4), "beside_swaps": round(busy_ms, 4),
+            "compute_matmul_ms": {"what": "8192^3 bf16 matmul on the compute stream, %d per iteration" % per_iter,
+                                  "alone": round(alone_ms, 4), "beside_swaps": round(busy_ms, 4),
                                   "slowdown": round(busy_ms / alone_ms, 4)},
+            "streams": 4 if args.four_streams else 2,
             "conflict_waits": st["conflict_waits"], "host_arena_bytes": st["host_arena_bytes"]}
 
 

@@ -60,6 +60,8 @@ typedef enum {
                                        allocator and reuse-map bookkeeping run (host-logic tests) */
 #define KV_FLAG_PROFILE          2u /* time every kernel launch and copy with HIP events (kv_profile_*) */
 #define KV_FLAG_ORDER_COMPUTE    4u /* order swaps after work already enqueued on compute_stream */
+#define KV_FLAG_FOUR_STREAMS     8u /* separate streams for kernels and copies of each direction (default:
+                                       one stream per direction, which needs fewer hardware queues) */
 
 typedef struct kv_pool kv_pool_t;
 

@@ -10,7 +10,9 @@
 // two orders of magnitude faster than the host link, so the extra pass is nearly free and
 // the copy size no longer depends on fragmentation.
 //
-// Streams (all default priority, non-blocking):
+// Streams (all default priority, non-blocking): one per direction by default (gathers and
+// device-to-host copies on one, host-to-device copies and scatters on the other); with
+// KV_FLAG_FOUR_STREAMS kernels and copies of each direction get streams of their own:
 //   s_pack : gather kernels           s_d2h : device-to-host copies
 //   s_h2d  : host-to-device copies    s_scat: scatter kernels
 // Swap-out packs first and drains afterwards: all gathers of a call that fit the staging ring
@@ -125,7 +127,7 @@ struct ProfRec {
 
 struct kv_pool {
   kv_pool_config_t cfg{};
-  bool plan = false, profile = false, order_compute = false;
+  bool plan = false, profile = false, order_compute = false, four_streams = false;
   int64_t N = 0, C = 0, R = 0;
   int32_t P = 0;
   char* gpu = nullptr;
@@ -819,6 +821,7 @@ void destroy_pool(kv_pool* p) {
       (void)hipEventDestroy(r.stop);
     }
     if (p->ev_compute) (void)hipEventDestroy(p->ev_compute);
+    if (!p->four_streams) p->s_d2h = p->s_scat = nullptr;  // aliases of the other two
     for (hipStream_t s : {p->s_pack, p->s_d2h, p->s_h2d, p->s_scat})
       if (s) (void)hipStreamDestroy(s);
     if (p->own_staging && p->staging) (void)hipFree(p->staging);
@@ -920,10 +923,21 @@ int32_t kv_pool_create(const kv_pool_config_t* cfg, kv_pool_t** out) {
       TRY_OR_BAIL(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
       p->grid = cus * 8;
     }
+    // Side streams.  A process has few hardware queues (4 by default) and streams beyond that
+    // share one: a scatter that lands behind the caller's compute kernels on a shared queue
+    // waits for all of them.  Two streams (one per direction) are therefore the default;
+    // KV_FLAG_FOUR_STREAMS gives kernels and copies of each direction streams of their own,
+    // which lets a scatter run under the next piece's copy.
     TRY_OR_BAIL(hipStreamCreateWithFlags(&p->s_pack, hipStreamNonBlocking));
-    TRY_OR_BAIL(hipStreamCreateWithFlags(&p->s_d2h, hipStreamNonBlocking));
     TRY_OR_BAIL(hipStreamCreateWithFlags(&p->s_h2d, hipStreamNonBlocking));
-    TRY_OR_BAIL(hipStreamCreateWithFlags(&p->s_scat, hipStreamNonBlocking));
+    if (cfg->flags & KV_FLAG_FOUR_STREAMS) {
+      TRY_OR_BAIL(hipStreamCreateWithFlags(&p->s_d2h, hipStreamNonBlocking));
+      TRY_OR_BAIL(hipStreamCreateWithFlags(&p->s_scat, hipStreamNonBlocking));
+      p->four_streams = true;
+    } else {
+      p->s_d2h = p->s_pack;
+      p->s_scat = p->s_h2d;
+    }
     TRY_OR_BAIL(hipEventCreateWithFlags(&p->ev_compute, hipEventDisableTiming));
     if (p->arena_blocks > 0) {
       hipError_t e = hipHostMalloc((void**)&p->host, (size_t)(p->arena_blocks * p->R), hipHostMallocDefault);

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libkvswap.so")
 
 KV_OK, KV_EINVAL, KV_ENOMEM_GPU, KV_ENOMEM_HOST = 0, -1, -2, -3
 KV_ENOENT, KV_EBUSY, KV_EHIP, KV_ENODEV = -4, -5, -6, -7
-KV_FLAG_PLAN_ONLY, KV_FLAG_PROFILE, KV_FLAG_ORDER_COMPUTE = 1, 2, 4
+KV_FLAG_PLAN_ONLY, KV_FLAG_PROFILE, KV_FLAG_ORDER_COMPUTE, KV_FLAG_FOUR_STREAMS = 1, 2, 4, 8
 
 _STATUS_NAMES = {0: "KV_OK", -1: "KV_EINVAL", -2: "KV_ENOMEM_GPU", -3: "KV_ENOMEM_HOST",
                  -4: "KV_ENOENT", -5: "KV_EBUSY", -6: "KV_EHIP", -7: "KV_ENODEV"}
