@@ -180,11 +180,12 @@ def main() -> int:
     pool.kv_wait_all()
 
     # ---- per-preemption switch latency: one victim out, one in, call -> completion
-    out_ms, in_ms, sw_ms = [], [], []
+    out_ms, in_ms, sw_ms, call_us = [], [], [], []
     for _ in range(args.latency_reps):
         for i, v in enumerate(victims):
             t_a = time.perf_counter()
             pool.swap_out(v, cur[i])
+            call_us.append((time.perf_counter() - t_a) * 1e6)
             pool.kv_wait(v)
             t_b = time.perf_counter()
             pool.swap_in(v, nxt[i])
@@ -209,6 +210,22 @@ def main() -> int:
     if args.latency_reps > 0:
         pool.swap_in(victims[-1], nxt[-1])
     pool.kv_wait_all()
+    # the same swaps submitted through the swap manager: what the scheduler's thread pays
+    submit_us, mgr_stats = [], None
+    if args.latency_reps > 0:
+        mgr = kv.KVManager(pool)
+        for _ in range(args.latency_reps):
+            for i, v in enumerate(victims):
+                t_a = time.perf_counter()
+                tk = mgr.kv_manager_submit(kv.KV_TASK_SWAP_OUT, v, cur[i])
+                submit_us.append((time.perf_counter() - t_a) * 1e6)
+                t_a = time.perf_counter()
+                mgr.kv_manager_submit(kv.KV_TASK_SWAP_IN, v, nxt[i])
+                submit_us.append((time.perf_counter() - t_a) * 1e6)
+            mgr.kv_manager_drain()
+            cur, nxt = nxt, cur
+        mgr_stats = mgr.kv_manager_stats()
+        mgr.kv_manager_destroy()
     all_recs = pool.kv_profile_read()  # every launch and copy of this process
     stats = pool.kv_stats()
     pool.kv_pool_destroy()
@@ -283,6 +300,14 @@ def main() -> int:
             "overlapped_median": percentile(ov_ms, 50),
             "overlapped_p99": percentile(ov_ms, 99),
             "median_request_MiB": round(float(np.median([len(t) for t in cur])) * s.R / (1 << 20), 1),
+        },
+        "dispatch_us": {
+            "what": "host time of one swap_out per victim: direct call vs submit to the swap manager "
+                    "(Python + ctypes included in both)",
+            "direct_call_median": percentile(call_us, 50),
+            "manager_submit_median": percentile(submit_us, 50),
+            "manager_dispatcher_avg": (round(mgr_stats["dispatch_us_sum"] / max(1, mgr_stats["dispatched"]), 2)
+                                       if mgr_stats else None),
         },
         "streams": 4 if args.four_streams else 2,
         "verified_samples_ok": ok,

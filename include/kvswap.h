@@ -209,6 +209,60 @@ int32_t kv_link_probe(int64_t bytes, int32_t direction, int32_t reps, double* ou
 /* Device copy ceiling: plain device-to-device copy kernel, read+write GB/s. */
 int32_t kv_hbm_probe(int64_t bytes, int32_t reps, double* out_gbps);
 
+/* R = bytes of one block record (all planes of one block). */
+int32_t kv_record_bytes(kv_pool_t* pool, int64_t* out);
+
+/* ---------------------------------------------------------------------------------------
+ * Swap manager (Section 3.2, Algorithm 1): dispatch of swaps on a thread of its own.
+ * submit copies the table and returns at once; a dispatcher thread calls the pool's entry
+ * points in submission order (the order conflict detection relies on); poll reports tasks
+ * whose device work has finished (Algorithm 1, step 1); wait / drain are the Synchronize
+ * steps; strategy is step 4's choice between asynchronous and synchronous swap-in.
+ * One dispatcher is enough here: a swap is a handful of runtime calls, not one per block
+ * group.  The manager does not own the pool; destroy the manager first. */
+typedef struct kv_manager kv_manager_t;
+
+#define KV_TASK_SWAP_OUT       0
+#define KV_TASK_SWAP_IN        1
+#define KV_TASK_SWAP_OUT_DELTA 2 /* mask = dirty mask */
+#define KV_TASK_SWAP_IN_DELTA  3 /* mask = resident mask */
+
+typedef struct {
+  int32_t window;        /* r_info: how many recent swaps the strategy remembers; <= 0: 64 */
+  int32_t reserved;
+  double  link_gbps;     /* host-link rate the strategy uses to estimate swap-in time; <= 0: 55 */
+  double  sync_below_ms; /* swap-ins estimated shorter than this are waited for (synchronous)
+                            rather than tracked across iterations; <= 0: 0.5 */
+} kv_manager_config_t;
+
+typedef struct {
+  int64_t submitted, dispatched, failed, queued, in_flight;
+  int64_t strategy_calls, strategy_async;
+  double  dispatch_us_sum;    /* time the dispatcher spent inside the pool's entry points */
+  double  queue_wait_us_sum;  /* submit -> start of dispatch */
+} kv_manager_stats_t;
+
+int32_t kv_manager_create(kv_pool_t* pool, const kv_manager_config_t* cfg /* may be NULL */,
+                          kv_manager_t** out);
+int32_t kv_manager_destroy(kv_manager_t* mgr);  /* dispatches what is queued, waits for it */
+/* kind = KV_TASK_*; table / mask as for the entry point of that kind (copied before return).
+ * *ticket (may be NULL) names the task in poll / wait.  Validation errors of the entry point
+ * are reported as the task's status, not here. */
+int32_t kv_manager_submit(kv_manager_t* mgr, int32_t kind, int64_t req, const int32_t* table,
+                          int32_t n_blocks, const uint8_t* mask, uint64_t* ticket);
+/* Up to cap finished tasks (device work done, or dispatch failed): tickets[i], status[i]
+ * (status may be NULL).  Non-blocking.  Each task is reported once, by poll or by wait. */
+int32_t kv_manager_poll(kv_manager_t* mgr, uint64_t* tickets, int32_t* status, int32_t cap,
+                        int32_t* n_out);
+/* Blocks until the task has been dispatched and its device work is done. */
+int32_t kv_manager_wait(kv_manager_t* mgr, uint64_t ticket, int32_t* status /* may be NULL */);
+int32_t kv_manager_drain(kv_manager_t* mgr);    /* everything submitted so far is done */
+/* Step 4: the scheduler wants n_swap_in requests of swap_in_blocks blocks in total back now.
+ * *async_out = 1: let them proceed asynchronously and poll; 0: wait for them (stall). */
+int32_t kv_manager_strategy(kv_manager_t* mgr, int32_t n_swap_in, int64_t swap_in_blocks,
+                            int32_t* async_out);
+int32_t kv_manager_stats(kv_manager_t* mgr, kv_manager_stats_t* out);
+
 /* Thread-local text of the last error. */
 const char* kv_last_error(void);
 const char* kv_version(void);

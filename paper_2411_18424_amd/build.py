@@ -13,14 +13,14 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libkvswap.so")
-SOURCES = ["kv_kernels.hip", "kvswap.cpp"]
+SOURCES = ["kv_kernels.hip", "kvswap.cpp", "kv_manager.cpp"]
 
 # -packed-fp32-ops is switched off on purpose: packed fp32 forms are not trusted on the
 # target machines.  (The library does no floating point at all, the flag is policy.)
 HIP_FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-    "-Wall", "-Wno-unused-command-line-argument",
+    "-Wall", "-Wno-unused-command-line-argument", "-pthread",
 ]
 
 

@@ -1216,6 +1216,12 @@ int32_t kv_host_release(kv_pool_t* p, int64_t req) {
   return KV_OK;
 }
 
+int32_t kv_record_bytes(kv_pool_t* p, int64_t* out) {
+  if (!p || !out) return fail(KV_EINVAL, "null argument");
+  *out = p->R;
+  return KV_OK;
+}
+
 int32_t kv_stats(kv_pool_t* p, kv_stats_t* out) {
   if (!p || !out) return fail(KV_EINVAL, "null argument");
   std::lock_guard<std::mutex> g(p->mu);

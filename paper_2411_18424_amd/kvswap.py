@@ -19,6 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libkvswap.so")
 KV_OK, KV_EINVAL, KV_ENOMEM_GPU, KV_ENOMEM_HOST = 0, -1, -2, -3
 KV_ENOENT, KV_EBUSY, KV_EHIP, KV_ENODEV = -4, -5, -6, -7
 KV_FLAG_PLAN_ONLY, KV_FLAG_PROFILE, KV_FLAG_ORDER_COMPUTE, KV_FLAG_FOUR_STREAMS = 1, 2, 4, 8
+KV_TASK_SWAP_OUT, KV_TASK_SWAP_IN, KV_TASK_SWAP_OUT_DELTA, KV_TASK_SWAP_IN_DELTA = 0, 1, 2, 3
 
 _STATUS_NAMES = {0: "KV_OK", -1: "KV_EINVAL", -2: "KV_ENOMEM_GPU", -3: "KV_ENOMEM_HOST",
                  -4: "KV_ENOENT", -5: "KV_EBUSY", -6: "KV_EHIP", -7: "KV_ENODEV"}
@@ -48,6 +49,17 @@ class kv_stats_t(C.Structure):
         "bytes_out", "bytes_in", "blocks_out", "blocks_in", "gather_launches",
         "scatter_launches", "d2h_copies", "h2d_copies", "conflict_waits",
         "host_new_extents", "host_arena_used", "host_arena_bytes")]
+
+
+class kv_manager_config_t(C.Structure):
+    _fields_ = [("window", C.c_int32), ("reserved", C.c_int32), ("link_gbps", C.c_double),
+                ("sync_below_ms", C.c_double)]
+
+
+class kv_manager_stats_t(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in ("submitted", "dispatched", "failed", "queued", "in_flight",
+                                         "strategy_calls", "strategy_async")] + \
+               [("dispatch_us_sum", C.c_double), ("queue_wait_us_sum", C.c_double)]
 
 
 class kv_prof_record_t(C.Structure):
@@ -92,6 +104,16 @@ def _load() -> C.CDLL:
         "kv_profile_reset": (C.c_int32, [pool_p]),
         "kv_link_probe": (C.c_int32, [C.c_int64, C.c_int32, C.c_int32, P(C.c_double)]),
         "kv_hbm_probe": (C.c_int32, [C.c_int64, C.c_int32, P(C.c_double)]),
+        "kv_record_bytes": (C.c_int32, [pool_p, i64p]),
+        "kv_manager_create": (C.c_int32, [pool_p, P(kv_manager_config_t), P(C.c_void_p)]),
+        "kv_manager_destroy": (C.c_int32, [C.c_void_p]),
+        "kv_manager_submit": (C.c_int32, [C.c_void_p, C.c_int32, C.c_int64, i32p, C.c_int32, u8p,
+                                          P(C.c_uint64)]),
+        "kv_manager_poll": (C.c_int32, [C.c_void_p, P(C.c_uint64), i32p, C.c_int32, i32p]),
+        "kv_manager_wait": (C.c_int32, [C.c_void_p, C.c_uint64, i32p]),
+        "kv_manager_drain": (C.c_int32, [C.c_void_p]),
+        "kv_manager_strategy": (C.c_int32, [C.c_void_p, C.c_int32, C.c_int64, i32p]),
+        "kv_manager_stats": (C.c_int32, [C.c_void_p, P(kv_manager_stats_t)]),
         "kv_last_error": (C.c_char_p, []),
         "kv_version": (C.c_char_p, []),
     }
@@ -320,3 +342,62 @@ class KVPool:
 
     def kv_profile_reset(self):
         _check(lib.kv_profile_reset(self._h))
+
+
+class KVManager:
+    """Owner of one ``kv_manager_t*`` over a KVPool (destroy it before the pool)."""
+
+    def __init__(self, pool: KVPool, window: int = 0, link_gbps: float = 0.0, sync_below_ms: float = 0.0):
+        cfg = kv_manager_config_t(window=window, reserved=0, link_gbps=link_gbps, sync_below_ms=sync_below_ms)
+        self._m = C.c_void_p()
+        self._pool = pool  # keeps the pool alive
+        _check(lib.kv_manager_create(pool._h, C.byref(cfg), C.byref(self._m)))
+
+    def kv_manager_destroy(self):
+        if self._m:
+            _check(lib.kv_manager_destroy(self._m))
+            self._m = C.c_void_p()
+
+    close = kv_manager_destroy
+
+    def __del__(self):
+        try:
+            self.kv_manager_destroy()
+        except Exception:
+            pass
+
+    def kv_manager_submit(self, kind: int, req: int, table, mask=None) -> int:
+        a, p = _i32(table)
+        mp = None
+        if mask is not None:
+            m, mp = _u8(mask)
+            if m.size != a.size:
+                raise KVError(KV_EINVAL, "mask length differs from table length")
+        t = C.c_uint64()
+        _check(lib.kv_manager_submit(self._m, kind, req, p, a.size, mp, C.byref(t)))
+        return t.value
+
+    def kv_manager_poll(self, cap: int = 64):
+        tickets = (C.c_uint64 * cap)()
+        status = (C.c_int32 * cap)()
+        n = C.c_int32()
+        _check(lib.kv_manager_poll(self._m, tickets, status, cap, C.byref(n)))
+        return [(tickets[i], status[i]) for i in range(n.value)]
+
+    def kv_manager_wait(self, ticket: int) -> int:
+        st = C.c_int32()
+        _check(lib.kv_manager_wait(self._m, ticket, C.byref(st)))
+        return st.value
+
+    def kv_manager_drain(self):
+        _check(lib.kv_manager_drain(self._m))
+
+    def kv_manager_strategy(self, n_swap_in: int, swap_in_blocks: int) -> bool:
+        a = C.c_int32()
+        _check(lib.kv_manager_strategy(self._m, n_swap_in, swap_in_blocks, C.byref(a)))
+        return bool(a.value)
+
+    def kv_manager_stats(self) -> dict:
+        st = kv_manager_stats_t()
+        _check(lib.kv_manager_stats(self._m, C.byref(st)))
+        return {n: getattr(st, n) for n, _ in kv_manager_stats_t._fields_}

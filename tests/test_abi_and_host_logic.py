@@ -262,3 +262,82 @@ def test_fragmented_arena_serves_an_image_in_several_extents(kv):
     st = p.kv_stats()
     assert st["host_arena_used"] == 38 * shape.R
     assert st["d2h_copies"] == 4 + 2            # the split image is copied as two runs
+
+
+def test_swap_manager_dispatches_in_order_and_reports_each_task_once(kv):
+    """Algorithm 1 primitives on a plan-only pool: submit returns tickets, the dispatcher
+    applies tasks in submission order, poll / wait report every task exactly once with the
+    status the entry point returned."""
+    shape = synth.KVShape("s", 1, 1, 8, 1, 2, 512, "fp16")
+    p = plan_pool(kv, shape, host_blocks=2048)
+    m = kv.KVManager(p)
+    o = KVOracle(1, 1, 8, 1, 2, 512)
+    rng = synth.rng_for(31)
+    tickets, expect_fail = [], set()
+    for r in range(20):
+        t = rng.permutation(512)[:int(rng.integers(1, 30))].astype(np.int32)
+        tickets.append(m.kv_manager_submit(kv.KV_TASK_SWAP_OUT, r, t))
+        o.swap_out(r, t)
+        t2 = rng.permutation(512)[:len(t)].astype(np.int32)
+        tickets.append(m.kv_manager_submit(kv.KV_TASK_SWAP_IN, r, t2))   # must follow its swap-out
+        o.swap_in(r, t2)
+    bad = m.kv_manager_submit(kv.KV_TASK_SWAP_IN, 999, np.arange(3, dtype=np.int32))  # no host copy
+    expect_fail.add(bad)
+    tickets.append(bad)
+    d = rng.permutation(512)[:25].astype(np.int32)
+    tickets.append(m.kv_manager_submit(kv.KV_TASK_SWAP_OUT_DELTA, 0, np.concatenate([d]), np.ones(25, np.uint8)))
+    first = tickets[0]
+    assert m.kv_manager_wait(first) == kv.KV_OK
+    m.kv_manager_drain()
+    seen = {}
+    while True:
+        got = m.kv_manager_poll(7)
+        if not got:
+            break
+        for tk, st in got:
+            assert tk not in seen
+            seen[tk] = st
+    assert set(seen) == set(tickets) - {first}
+    for tk, st in seen.items():
+        if tk in expect_fail:
+            assert st == kv.KV_ENOENT
+        elif tk == tickets[-1]:
+            assert st in (kv.KV_OK, kv.KV_EINVAL)  # request 0 had fewer or more than 25 blocks
+        else:
+            assert st == kv.KV_OK
+    with pytest.raises(kv.KVError):
+        m.kv_manager_wait(first)  # already reported
+    st = p.kv_stats()
+    ms = m.kv_manager_stats()
+    assert ms["submitted"] == ms["dispatched"] == len(tickets) and ms["failed"] >= 1
+    assert ms["queued"] == 0 and ms["in_flight"] == 0
+    assert st["bytes_in"] == o.bytes_in  # every swap-in found its swap-out dispatched before it
+    m.kv_manager_destroy()
+
+
+def test_swap_manager_strategy_follows_swap_in_size(kv):
+    """Step 4: short swap-ins are waited for, long ones proceed asynchronously; the recent
+    window damps single outliers."""
+    shape = synth.LLAMA3_8B  # R = 2 MiB: 0.5 ms of link time at 55 GB/s is about 13 blocks
+    p = plan_pool(kv, shape.with_blocks(4096), host_blocks=4096)
+    m = kv.KVManager(p, link_gbps=55.0, sync_below_ms=0.5)
+    assert m.kv_manager_strategy(0, 0) is False
+    assert m.kv_manager_strategy(4, 4 * 2) is False        # four swap-ins of 2 blocks: 0.08 ms each
+    assert m.kv_manager_strategy(4, 4 * 200) is True       # 7.6 ms each
+    # a window full of long swap-ins keeps the mode asynchronous for one short request ...
+    for r in range(8):
+        m.kv_manager_submit(kv.KV_TASK_SWAP_OUT, r, np.arange(r * 300, r * 300 + 300, dtype=np.int32))
+        m.kv_manager_submit(kv.KV_TASK_SWAP_IN, r, np.arange(r * 300, r * 300 + 300, dtype=np.int32))
+    m.kv_manager_drain()
+    assert m.kv_manager_strategy(1, 2) is True
+    # ... and a window full of short ones makes it synchronous
+    m2 = kv.KVManager(p, window=8, link_gbps=55.0, sync_below_ms=0.5)
+    for r in range(100, 108):
+        m2.kv_manager_submit(kv.KV_TASK_SWAP_OUT, r, np.arange(3500 + (r - 100) * 2, 3502 + (r - 100) * 2, dtype=np.int32))
+        m2.kv_manager_submit(kv.KV_TASK_SWAP_IN, r, np.arange(3500 + (r - 100) * 2, 3502 + (r - 100) * 2, dtype=np.int32))
+    m2.kv_manager_drain()
+    assert m2.kv_manager_strategy(1, 20) is False  # (0.76 + 0.08) / 2 = 0.42 ms < 0.5 ms
+    s = m.kv_manager_stats()
+    assert s["strategy_calls"] == 4 and s["strategy_async"] == 2
+    m.kv_manager_destroy()
+    m2.kv_manager_destroy()

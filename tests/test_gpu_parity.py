@@ -414,3 +414,82 @@ def test_direct_copy_comparison_path(harness, per_block):
     runs_out = (5 + 2 + 1) if not per_block else 28
     assert st["d2h_copies"] == runs_out * shape.P
     assert st["h2d_copies"] == 28 * shape.P  # fully fragmented resume tables: one copy per block and plane
+
+
+def test_swap_manager_path_matches_oracle(harness):
+    """Swaps submitted through the manager's dispatcher thread give the same bytes; a resume
+    into blocks that a queued swap-out is still to read is kept in order."""
+    shape = synth.KVShape("s", 4, 8, 128, 16, 2, 128, "bf16")
+    h = harness(shape, cfg=16, host_bytes=512 * MiB)
+    kv = h.kv
+    m = kv.KVManager(h.pool)
+    try:
+        rng = synth.rng_for(16)
+        ta, tb, tc = synth.deal_tables(rng, 128, [30, 30, 20])
+        tickets = [m.kv_manager_submit(kv.KV_TASK_SWAP_OUT, 1, tb)]
+        h.oracle.swap_out(1, tb)
+        for rep in range(4):
+            tickets.append(m.kv_manager_submit(kv.KV_TASK_SWAP_OUT, 0, ta))
+            tickets.append(m.kv_manager_submit(kv.KV_TASK_SWAP_IN, 1, ta[::-1].copy()))  # into A's blocks
+            h.oracle.swap_out(0, ta)
+            h.oracle.swap_in(1, ta[::-1].copy())
+            tickets.append(m.kv_manager_submit(kv.KV_TASK_SWAP_OUT, 1, ta[::-1].copy()))
+            tickets.append(m.kv_manager_submit(kv.KV_TASK_SWAP_IN, 0, tb))
+            h.oracle.swap_out(1, ta[::-1].copy())
+            h.oracle.swap_in(0, tb)
+            ta, tb = tb, ta
+        dirty = synth.random_mask(rng, 30, 0.4)
+        tickets.append(m.kv_manager_submit(kv.KV_TASK_SWAP_OUT_DELTA, 0, ta, dirty))
+        h.oracle.swap_out_delta(0, ta, dirty)
+        assert m.kv_manager_wait(tickets[-1]) == kv.KV_OK
+        m.kv_manager_drain()
+        done = dict(m.kv_manager_poll(64))
+        assert set(done) == set(tickets[:-1]) and all(s == kv.KV_OK for s in done.values())
+        h.assert_image_equal(0)
+        h.assert_image_equal(1)
+        h.assert_pool_equal()
+    finally:
+        m.kv_manager_destroy()
+
+
+def test_concurrent_host_threads(harness):
+    """The pool may be driven from several host threads: four threads swap disjoint requests
+    out and back in at the same time."""
+    import threading
+    shape = synth.KVShape("s", 4, 8, 128, 16, 2, 256, "bf16")
+    h = harness(shape, cfg=17, host_bytes=1024 * MiB)
+    rng = synth.rng_for(17)
+    tables = synth.deal_tables(rng, 256, [24] * 8)
+    tables2 = synth.deal_tables(synth.rng_for(17, stream=1), 256, [24] * 8)
+    # resume tables overlap other requests' current tables: keep each thread's pair disjoint
+    # from the others by resuming into a permutation of its own blocks
+    errors = []
+
+    def worker(k):
+        try:
+            for rep in range(5):
+                for r in (2 * k, 2 * k + 1):
+                    h.pool.swap_out(r, tables[r])
+                for r in (2 * k, 2 * k + 1):
+                    h.pool.kv_wait(r)
+                    h.pool.swap_in(r, tables[r][::-1].copy() if rep % 2 == 0 else tables[r])
+                for r in (2 * k, 2 * k + 1):
+                    h.pool.kv_wait(r)
+        except Exception as e:  # pragma: no cover
+            errors.append(e)
+
+    threads = [threading.Thread(target=worker, args=(k,)) for k in range(4)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors
+    for r in range(8):
+        for rep in range(5):
+            h.oracle.swap_out(r, tables[r])
+            h.oracle.swap_in(r, tables[r][::-1].copy() if rep % 2 == 0 else tables[r])
+    del tables2
+    h.pool.kv_wait_all()
+    for r in range(8):
+        h.assert_image_equal(r)
+    h.assert_pool_equal()
