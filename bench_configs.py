@@ -21,12 +21,17 @@ def _pct(xs, q):
 
 def _rates(recs):
     out = {}
-    for kind, name, mult in ((0, "gather", 2), (1, "scatter", 2), (2, "d2h", 1), (3, "h2d", 1)):
+    for kind, name, mult in ((0, "gather", 2), (1, "scatter", 2), (2, "d2h", 1), (3, "h2d", 1), (4, "mapped_in", 1)):
         rs = [r for r in recs if r[0] == kind]
         ms = sum(r[2] for r in rs)
         out[name + "_gbps"] = round(mult * sum(r[1] for r in rs) / ms / 1e6, 1) if ms > 0 else None
         out[name + "_n"] = len(rs)
     return out
+
+
+def _flags(args, kv, base=0):
+    return (base | (kv.KV_FLAG_FOUR_STREAMS if args.four_streams else 0)
+            | (kv.KV_FLAG_MAPPED_SWAP_IN if args.mapped_swap_in else 0))
 
 
 def _pool(kv, torch, s, host_bytes, **kw):
@@ -46,7 +51,7 @@ def config1(args):
     nblk = synth.blocks_for(synth.lengths_uniform(rng, 8, 16, 256), s.block_size)
     tables = synth.deal_tables(rng, s.n_blocks, nblk)
     tables2 = synth.deal_tables(rng, s.n_blocks, nblk)
-    gpu, pool = _pool(kv, torch, s, 64 * MiB)
+    gpu, pool = _pool(kv, torch, s, 64 * MiB, flags=_flags(args, kv))
     gpu.random_(0, 256)
     torch.cuda.synchronize()
     out_us, in_us, all_ms = [], [], []
@@ -89,7 +94,8 @@ def config1(args):
             "per_request_out_us": {"median": _pct(out_us, 50), "p99": _pct(out_us, 99)},
             "per_request_in_us": {"median": _pct(in_us, 50), "p99": _pct(in_us, 99)},
             "batched_all8_out_in_ms": {"median": _pct(b_ms, 50), "p99": _pct(b_ms, 99)},
-            "batched_gbps": round(2 * payload / (np.median(b_ms) * 1e-3) / 1e9, 3)}
+            "batched_gbps": round(2 * payload / (np.median(b_ms) * 1e-3) / 1e9, 3),
+            "mapped_swap_in": bool(args.mapped_swap_in)}
 
 
 def config3(args):
@@ -103,7 +109,7 @@ def config3(args):
     nblk = synth.blocks_for(rng.integers(512, 4097, size=n_pre), s.block_size)
     host_bytes = int((lag + 2) * (256 + 40)) * s.R
     gpu, pool = _pool(kv, torch, s, host_bytes,
-                      flags=kv.KV_FLAG_PROFILE | (kv.KV_FLAG_FOUR_STREAMS if args.four_streams else 0))
+                      flags=_flags(args, kv, kv.KV_FLAG_PROFILE))
     a = torch.randn(8192, 8192, device="cuda:0", dtype=torch.bfloat16)
     comp = torch.cuda.Stream()
 
@@ -171,7 +177,7 @@ def config3(args):
             "compute_matmul_ms": {"what": "8192^3 bf16 matmul on the compute stream, %d per iteration" % per_iter,
                                   "alone": round(alone_ms, 4), "beside_swaps": round(busy_ms, 4),
                                   "slowdown": round(busy_ms / alone_ms, 4)},
-            "streams": 4 if args.four_streams else 2,
+            "streams": 4 if args.four_streams else 2, "mapped_swap_in": bool(args.mapped_swap_in),
             "conflict_waits": st["conflict_waits"], "host_arena_bytes": st["host_arena_bytes"]}
 
 
@@ -187,7 +193,7 @@ def config4(args):
     ctx = synth.lengths_loguniform(rng, n_conv, 1024, 16384)
     nb0 = synth.blocks_for(ctx, B)
     host_bytes = int(nb0.sum() + 140 * n_conv) * s.R
-    gpu, pool = _pool(kv, torch, s, host_bytes, flags=kv.KV_FLAG_PROFILE)
+    gpu, pool = _pool(kv, torch, s, host_bytes, flags=_flags(args, kv, kv.KV_FLAG_PROFILE))
     gpu.random_(0, 256)
     torch.cuda.synchronize()
     work = rng.permutation(s.n_blocks)[:1200].astype(np.int32)
@@ -245,7 +251,7 @@ def config4(args):
             "swap_in_ms": {"median": _pct(in_ms, 50), "p99": _pct(in_ms, 99)},
             "full_swap_out_kernels_and_copies": _rates(full_recs),
             "all_kernels_and_copies": _rates(pool_recs),
-            "bytes_moved_equals_dirty_blocks": True,
+            "bytes_moved_equals_dirty_blocks": True, "mapped_swap_in": bool(args.mapped_swap_in),
             "host_new_extents": st["host_new_extents"], "d2h_copies": st["d2h_copies"]}
 
 
@@ -260,7 +266,7 @@ def config5(args):
            "config": {"workload": "config 5: Qwen2-72B-shaped GQA KV (80 layers, 8 KV heads, head_dim 128, bf16), pool %d blocks "
                                   "= %.1f GB, %d requests of 2048 blocks (10 GiB) per run length, one at a time"
                                   % (s.n_blocks, s.n_blocks * s.R / 1e9, n_req)}}
-    gpu, pool = _pool(kv, torch, s, (2048 + 40) * s.R, flags=kv.KV_FLAG_PROFILE)
+    gpu, pool = _pool(kv, torch, s, (2048 + 40) * s.R, flags=_flags(args, kv, kv.KV_FLAG_PROFILE))
     payload = 2048 * s.R
     for run in (1, 16):
         rng = synth.rng_for(5, stream=run)

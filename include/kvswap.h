@@ -60,6 +60,9 @@ typedef enum {
                                        allocator and reuse-map bookkeeping run (host-logic tests) */
 #define KV_FLAG_PROFILE          2u /* time every kernel launch and copy with HIP events (kv_profile_*) */
 #define KV_FLAG_ORDER_COMPUTE    4u /* order swaps after work already enqueued on compute_stream */
+#define KV_FLAG_MAPPED_SWAP_IN  16u /* swap-in reads the pinned host image directly from a small scatter
+                                       kernel (no staging, no copy engine): lower latency, and the cost no
+                                       longer depends on how fragmented the moved set is */
 #define KV_FLAG_FOUR_STREAMS     8u /* separate streams for kernels and copies of each direction (default:
                                        one stream per direction, which needs fewer hardware queues) */
 
@@ -91,6 +94,8 @@ typedef struct {
                                (default, fastest measured); 1 = persistent grid-stride workgroups
                                with the block table in LDS; 2 / 3 = tile kernel forced to 256 /
                                1024 lanes */
+  int32_t mapped_in_grid;   /* workgroups of the mapped swap-in kernel; 0 = default 64 */
+  int32_t reserved;
 } kv_pool_config_t;
 
 /* Section 3.1 (KV pool + block groups).  Creates the pool object: pinned host arena,

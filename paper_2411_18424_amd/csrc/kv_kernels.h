@@ -21,6 +21,27 @@ struct KvPackArgs {
   int32_t table[KV_MAX_LAUNCH_BLOCKS];  // physical block id of each of the m blocks
 };
 
+// Swap-in straight from the pinned host image (no staging, no copy engine): the launch's
+// table pairs each block's physical id with the arena record that holds its bytes.
+#define KV_MAX_MAPPED_BLOCKS 440
+struct KvMappedArgs {
+  char* pool;            // device: pool[p][b][C]
+  const char* host;      // device-visible address of the pinned arena
+  int64_t plane_stride;  // N * C bytes
+  int64_t R;             // record bytes = P * C
+  uint32_t C;
+  uint32_t P;
+  uint32_t m;            // blocks in this launch (<= KV_MAX_MAPPED_BLOCKS)
+  uint32_t tiles_per_chunk;
+  uint32_t n_tiles;
+  uint32_t pad;
+  int32_t phys[KV_MAX_MAPPED_BLOCKS];
+  uint32_t rec[KV_MAX_MAPPED_BLOCKS];
+};
+// grid: workgroups (few: the host link, not the CUs, is the limit).
+hipError_t kv_launch_mapped_scatter(const KvMappedArgs& a, int grid, hipStream_t stream,
+                                    hipEvent_t start, hipEvent_t stop);
+
 #define KV_PACK_TILE 0        // one tile per workgroup, 3-D grid, workgroup size by chunk (default)
 #define KV_PACK_PERSISTENT 1  // grid-stride loop, block table staged in LDS, 256 lanes
 #define KV_PACK_TILE_256 2    // tile kernel, 256 lanes

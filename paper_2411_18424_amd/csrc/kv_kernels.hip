@@ -89,6 +89,48 @@ __global__ __launch_bounds__(WG) void kv_pack_persistent_kernel(const KvPackArgs
   }
 }
 
+// Swap-in without staging: a small persistent grid reads the block records straight from
+// pinned host memory (loads travel over the host link; 8 vectors per lane in flight) and
+// stores them into the pool.  A few dozen workgroups saturate the link, and - unlike a
+// kernel that *stores* to host memory - host reads cost an HBM-bound neighbour only ~2 %.
+// The table (physical id, arena record) of the launch is staged in LDS once per workgroup.
+template <bool FULL>
+__global__ __launch_bounds__(256) void kv_mapped_scatter_kernel(const KvMappedArgs a) {
+  __shared__ int32_t s_phys[KV_MAX_MAPPED_BLOCKS];
+  __shared__ uint32_t s_rec[KV_MAX_MAPPED_BLOCKS];
+  for (uint32_t i = threadIdx.x; i < a.m; i += 256) {
+    s_phys[i] = a.phys[i];
+    s_rec[i] = a.rec[i];
+  }
+  __syncthreads();
+  constexpr int U = 8;
+  constexpr uint32_t TILE_VECS = 256 * U;
+  const uint32_t tpc = a.tiles_per_chunk;
+  const uint32_t P = a.P;
+  const uint32_t chunk_vecs = a.C >> 4;
+  for (uint32_t w = blockIdx.x; w < a.n_tiles; w += gridDim.x) {
+    const uint32_t q = w / tpc;  // q = k*P + p: tiles walk each host record front to back
+    const uint32_t t = w - q * tpc;
+    const uint32_t k = q / P;
+    const uint32_t p = q - k * P;
+    const uint32_t v0 = t * TILE_VECS;
+    const u32x4* src = reinterpret_cast<const u32x4*>(a.host + (int64_t)s_rec[k] * a.R + (int64_t)p * a.C) + v0;
+    u32x4* dst = reinterpret_cast<u32x4*>(a.pool + (int64_t)p * a.plane_stride + (int64_t)s_phys[k] * a.C) + v0;
+    const uint32_t rem = chunk_vecs - v0;
+    u32x4 r[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const uint32_t i = threadIdx.x + u * 256;
+      if (FULL || i < rem) r[u] = src[i];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const uint32_t i = threadIdx.x + u * 256;
+      if (FULL || i < rem) __builtin_nontemporal_store(r[u], dst + i);
+    }
+  }
+}
+
 // Plain linear copy, one 4 KiB tile per workgroup: the device-copy ceiling the pack
 // kernels are compared with.
 __global__ __launch_bounds__(KV_WG) void kv_linear_copy_kernel(u32x4* __restrict__ dst,
@@ -201,5 +243,25 @@ hipError_t kv_launch_linear_copy(void* dst, const void* src, int64_t bytes, hipS
   hipExtLaunchKernelGGL(kv_linear_copy_kernel, dim3((unsigned)grid), dim3(KV_WG), 0, stream, start,
                         stop, 0, reinterpret_cast<u32x4*>(dst), reinterpret_cast<const u32x4*>(src),
                         n_vecs);
+  return hipGetLastError();
+}
+
+hipError_t kv_launch_mapped_scatter(const KvMappedArgs& a_in, int grid, hipStream_t stream,
+                                    hipEvent_t start, hipEvent_t stop) {
+  if (a_in.m == 0) return hipSuccess;
+  if (a_in.m > KV_MAX_MAPPED_BLOCKS || (a_in.C & 15u) || a_in.C == 0 || a_in.P == 0)
+    return hipErrorInvalidValue;
+  KvMappedArgs a = a_in;
+  const uint32_t tile = 256u * 16u * 8u;
+  a.tiles_per_chunk = (a.C + tile - 1) / tile;
+  const uint64_t n_tiles = (uint64_t)a.m * a.P * a.tiles_per_chunk;
+  if (n_tiles > 0xFFFFFFFFull) return hipErrorInvalidValue;
+  a.n_tiles = (uint32_t)n_tiles;
+  if (grid <= 0) grid = 64;
+  if ((uint64_t)grid > n_tiles) grid = (int)n_tiles;
+  if (a.C % tile == 0)
+    hipExtLaunchKernelGGL((kv_mapped_scatter_kernel<true>), dim3(grid), dim3(256), 0, stream, start, stop, 0, a);
+  else
+    hipExtLaunchKernelGGL((kv_mapped_scatter_kernel<false>), dim3(grid), dim3(256), 0, stream, start, stop, 0, a);
   return hipGetLastError();
 }

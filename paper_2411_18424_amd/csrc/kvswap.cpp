@@ -131,7 +131,10 @@ struct kv_pool {
   int64_t N = 0, C = 0, R = 0;
   int32_t P = 0;
   char* gpu = nullptr;
-  char* host = nullptr;  // pinned arena
+  char* host = nullptr;      // pinned arena
+  char* host_dev = nullptr;  // the arena as the device addresses it
+  bool mapped_in = false;
+  int mapped_grid = 64;
   int64_t arena_blocks = 0;
   bool own_staging = false;
   char* staging = nullptr;
@@ -586,6 +589,49 @@ int32_t enqueue_direct(kv_pool* p, bool to_host, const std::vector<Move>& mv,
   return KV_OK;
 }
 
+// Swap-in straight from the pinned image (KV_FLAG_MAPPED_SWAP_IN): one persistent kernel per
+// 440 blocks reads the host records over the link and writes the pool; no staging, no copy
+// engine, no per-run copies - fragmented images and partial swap-ins cost the same as
+// contiguous ones.
+int32_t enqueue_in_mapped(kv_pool* p, const std::vector<Move>& mv, const std::vector<hipEvent_t>& pre,
+                          const OpRef& op) {
+  int32_t rc;
+  hipStream_t s = p->s_scat;
+  if ((rc = order_after_compute(p, s))) return rc;
+  for (hipEvent_t e : pre)
+    if ((rc = stream_wait(p, s, e))) return rc;
+  const int64_t m = (int64_t)mv.size();
+  for (int64_t i = 0; i < m; i += KV_MAX_MAPPED_BLOCKS) {
+    const int64_t ml = std::min<int64_t>(KV_MAX_MAPPED_BLOCKS, m - i);
+    p->st.scatter_launches++;
+    if (p->plan) continue;
+    KvMappedArgs a;
+    a.pool = p->gpu;
+    a.host = p->host_dev;
+    a.plane_stride = p->N * p->C;
+    a.R = p->R;
+    a.C = (uint32_t)p->C;
+    a.P = (uint32_t)p->P;
+    a.m = (uint32_t)ml;
+    a.tiles_per_chunk = a.n_tiles = a.pad = 0;
+    for (int64_t k = 0; k < ml; ++k) {
+      a.phys[k] = mv[(size_t)(i + k)].phys;
+      a.rec[k] = (uint32_t)(mv[(size_t)(i + k)].host_off / p->R);
+    }
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (p->profile) {
+      if ((rc = get_timing_event(p, &e0))) return rc;
+      if ((rc = get_timing_event(p, &e1))) return rc;
+      p->prof.push_back({4, ml * p->R, e0, e1});
+    }
+    HIP_TRY(kv_launch_mapped_scatter(a, p->mapped_grid, s, e0, e1));
+  }
+  if ((rc = record(p, op->done, s))) return rc;
+  p->st.bytes_in += m * p->R;
+  p->st.blocks_in += m;
+  return KV_OK;
+}
+
 int32_t new_op(kv_pool* p, bool is_out, OpRef* out) {
   auto op = std::make_shared<Op>();
   op->is_out = is_out;
@@ -799,6 +845,10 @@ int32_t do_swap_in(kv_pool* p, std::vector<InItem>& items, int32_t* out_n_moved,
     pre_copy.insert(pre_copy.end(), pre_scat.begin(), pre_scat.end());
     return enqueue_direct(p, false, mv, pre_copy, op, direct == 2);
   }
+  if (p->mapped_in) {
+    pre_copy.insert(pre_copy.end(), pre_scat.begin(), pre_scat.end());
+    return enqueue_in_mapped(p, mv, pre_copy, op);
+  }
   return enqueue_in(p, mv, pre_copy, pre_scat, op);
 }
 
@@ -871,6 +921,8 @@ int32_t kv_pool_create(const kv_pool_config_t* cfg, kv_pool_t** out) {
   p->grid = cfg->gather_grid;
   p->unroll = cfg->tile_unroll;  // 0 = pick from the chunk size
   p->variant = cfg->pack_variant;
+  p->mapped_in = (cfg->flags & KV_FLAG_MAPPED_SWAP_IN) != 0;
+  if (cfg->mapped_in_grid > 0) p->mapped_grid = cfg->mapped_in_grid;
   p->launch_blocks = kv_max_launch_blocks((uint32_t)C, (uint32_t)p->P, p->unroll, p->variant);
   // staging rings: defaults scale with the pool, capped at 4 GiB (out) and 1 GiB (in)
   const int64_t pool_bytes = p->R * p->N;
@@ -897,6 +949,10 @@ int32_t kv_pool_create(const kv_pool_config_t* cfg, kv_pool_t** out) {
   p->ring_in.cap = in_cap;
   p->ring_in.piece_blocks = piece_blocks(in_cap, 256ll << 20);
   p->arena_blocks = cfg->host_bytes / p->R;
+  if (p->arena_blocks > 0xFFFFFFFFll) {
+    delete p;
+    return fail(KV_EINVAL, "host arena of %lld records: record indices are 32-bit", (long long)p->arena_blocks);
+  }
   p->arena.insert(0, p->arena_blocks);
   p->alloc.init(p->N);
   p->reader_seq.assign((size_t)p->N, 0);
@@ -942,6 +998,7 @@ int32_t kv_pool_create(const kv_pool_config_t* cfg, kv_pool_t** out) {
     if (p->arena_blocks > 0) {
       hipError_t e = hipHostMalloc((void**)&p->host, (size_t)(p->arena_blocks * p->R), hipHostMallocDefault);
       if (e != hipSuccess) return bail(fail(KV_ENOMEM_HOST, "hipHostMalloc(%lld): %s", (long long)(p->arena_blocks * p->R), hipGetErrorString(e)));
+      TRY_OR_BAIL(hipHostGetDevicePointer((void**)&p->host_dev, p->host, 0));
     }
     if (cfg->staging_base) {
       p->staging = (char*)cfg->staging_base;

@@ -493,3 +493,45 @@ def test_concurrent_host_threads(harness):
     for r in range(8):
         h.assert_image_equal(r)
     h.assert_pool_equal()
+
+
+@pytest.mark.parametrize("L,H,D,B,e,N", [
+    (2, 4, 64, 16, 2, 256),    # tiny config: C = 8 KiB (bounds-checked 32 KiB tiles)
+    (4, 8, 128, 16, 2, 96),    # C = 32 KiB: exactly one tile per chunk
+    (2, 40, 128, 16, 2, 24),   # C = 160 KiB: 5 tiles per chunk
+    (3, 3, 40, 16, 2, 96),     # C = 3840: ragged
+    (1, 1, 32, 16, 2, 2048),   # many small blocks: more than 440 per swap-in -> several launches
+])
+def test_mapped_swap_in_reads_the_host_image_directly(harness, L, H, D, B, e, N):
+    """KV_FLAG_MAPPED_SWAP_IN: swap-in by a kernel that reads pinned host memory; same bytes
+    as the staged path, for full, partial and multi-extent images."""
+    shape = synth.KVShape("s", L, H, D, B, e, N, "fp16")
+    h = harness(shape, cfg=18, fill="random", flags=16, host_slack_blocks=2)
+    rng = synth.rng_for(18, stream=N)
+    n = min(N // 3, 700)
+    t = rng.permutation(N)[:n].astype(np.int32)
+    u = rng.permutation(N)[:5].astype(np.int32)
+    n0 = n - 9 if n > 18 else n // 2     # first image; it later grows by more than its slack
+    h.pool.swap_out(0, t[:n0])
+    h.oracle.swap_out(0, t[:n0])
+    h.pool.swap_out(1, u)                     # takes the arena space right behind request 0
+    h.oracle.swap_out(1, u)
+    dirty = np.zeros(n, np.uint8)
+    h.pool.swap_out_delta(0, t, dirty)        # grows past its slack: the image gets a second extent
+    h.oracle.swap_out_delta(0, t, dirty)
+    assert h.pool.kv_host_len(0) == (n, 2)
+    h.assert_image_equal(0)
+    t2 = rng.permutation(N)[:n].astype(np.int32)
+    res = synth.random_mask(rng, n, 0.3)
+    assert h.pool.swap_in_delta(0, t2, res) == len(h.oracle.swap_in(0, t2, resident=res))
+    h.pool.kv_wait(0)
+    h.assert_pool_equal()
+    t3 = rng.permutation(N)[:n].astype(np.int32)
+    h.pool.swap_in(0, t3)
+    h.oracle.swap_in(0, t3)
+    h.pool.swap_out(0, t3)                    # and straight out again: gather after mapped scatter
+    h.oracle.swap_out(0, t3)
+    h.assert_image_equal(0)
+    h.assert_pool_equal()
+    st = h.pool.kv_stats()
+    assert st["h2d_copies"] == 0 and st["bytes_in"] == h.oracle.bytes_in
