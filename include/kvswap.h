@@ -121,6 +121,30 @@ int32_t free_block_group(kv_pool_t* pool, int64_t req, const int32_t* blocks, in
 /* Number of blocks currently free (including those waiting for a gather to finish). */
 int32_t kv_free_blocks(kv_pool_t* pool, int64_t* out_free, int64_t* out_largest_run);
 
+/* Section 3.1, Dynamic Block Group Manager: requests that grow.  A request owns block groups
+ * (contiguous runs); its newest group is the active one and carries a reserved tail the request
+ * grows into.  kv_bg_append gives req n_blocks more blocks (a request is created by its first
+ * append): from the active group's tail, else by growing that group in place, else from a new
+ * group of the expected size (first_group_blocks, default 64, shrunk to the free run that is
+ * there; plus reserve_tail blocks of headroom), else - when no free group is left - from the
+ * tail of a randomly chosen other request's active group (seeded splitmix64), all of it or
+ * max(need, half).  Ids are written to out_blocks[n_blocks] in logical order.  KV_ENOMEM_GPU
+ * (nothing changes) if free blocks and other requests' tails together are fewer than n_blocks.
+ * kv_bg_table returns the current table (ids of the used blocks in logical order; *out_n is the
+ * length even when cap is smaller).  kv_bg_close returns every block of the request, tails
+ * included; blocks an unfinished gather still reads stay unavailable until it has finished.
+ * Shares the free lists with alloc_block_group / free_block_group. */
+typedef struct {
+  int64_t n_requests, n_groups /* with at least one used block */, used_blocks, tail_blocks;
+  int64_t steals, opened, appended_groups, grown_in_place;
+} kv_bg_stats_t;
+int32_t kv_bg_configure(kv_pool_t* pool, int32_t first_group_blocks /* 0 = 64 */, uint64_t seed);
+int32_t kv_bg_append(kv_pool_t* pool, int64_t req, int32_t n_blocks, int32_t reserve_tail,
+                     int32_t* out_blocks);
+int32_t kv_bg_table(kv_pool_t* pool, int64_t req, int32_t* out_blocks, int32_t cap, int32_t* out_n);
+int32_t kv_bg_close(kv_pool_t* pool, int64_t req);
+int32_t kv_bg_stats(kv_pool_t* pool, kv_bg_stats_t* out);
+
 /* Sections 2.1 / 3.3.  Full swap-out: every logical block j (block_table[j] = its physical
  * id) is copied into the request's host image, replacing any earlier image.
  * KV_EINVAL: id out of range or repeated.  KV_ENOMEM_HOST: arena full. */

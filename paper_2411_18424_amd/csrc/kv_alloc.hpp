@@ -10,6 +10,7 @@
 #include <algorithm>
 #include <map>
 #include <set>
+#include <unordered_map>
 #include <utility>
 #include <vector>
 
@@ -154,6 +155,24 @@ class BlockGroupAllocator {
     return count_runs(*out, runs);
   }
 
+  // One contiguous run of up to `want` blocks: the best-fitting free run if one holds `want`,
+  // else the largest free run (shorter).  Returns the length taken (0 if nothing is free).
+  int64_t alloc_run(int64_t want, int64_t* start) {
+    if (want <= 0) return 0;
+    int64_t got = want;
+    if (!free_.take_best_fit(want, start)) got = free_.take_from_largest(want, start);
+    for (int64_t i = 0; i < got; ++i) state_[(size_t)(*start + i)] = USED;
+    return got;
+  }
+
+  // Extends a used run in place: takes [start, start+len) if it is entirely free.
+  bool alloc_exact(int64_t start, int64_t len) {
+    if (len <= 0 || start < 0 || start + len > n_) return false;
+    if (!free_.take_exact(start, len)) return false;
+    for (int64_t i = 0; i < len; ++i) state_[(size_t)(start + i)] = USED;
+    return true;
+  }
+
   // True if every id is in range, USED and named once.  scratch is a caller-kept stamp array.
   bool can_free(const int32_t* ids, int32_t n, std::vector<uint32_t>* stamp, uint32_t* epoch) const {
     if ((int64_t)stamp->size() != n_) stamp->assign((size_t)n_, 0);
@@ -247,6 +266,137 @@ class BlockGroupAllocator {
   RunSet free_;
   std::vector<Parked> draining_;
   int64_t n_draining_ = 0;
+};
+
+// Dynamic Block Group Manager (Section 3.1): requests own block groups (contiguous runs); the
+// newest group of a request is its active group, whose unused tail the request grows into
+// and from which other requests may be served when the free groups run out.
+class BlockGroupManager {
+ public:
+  struct Group {
+    int64_t start, len, used;  // blocks [start, start+used) hold KV, the rest is reserved tail
+  };
+  struct Stats {
+    int64_t n_requests = 0, n_groups = 0, used_blocks = 0, tail_blocks = 0;
+    int64_t steals = 0, opened = 0, appended_groups = 0, grown_in_place = 0;
+  };
+
+  void configure(BlockGroupAllocator* a, int64_t first_group, uint64_t seed) {
+    alloc_ = a;
+    first_group_ = first_group > 0 ? first_group : 64;
+    rng_ = seed ? seed : 0x9E3779B97F4A7C15ull;
+  }
+  int64_t first_group() const { return first_group_; }
+  bool has(int64_t req) const { return owners_.count(req) != 0; }
+
+  // Blocks the manager could still hand to `req`: free blocks plus the tails of other
+  // requests' active groups.
+  int64_t obtainable(int64_t req) const {
+    int64_t n = alloc_->n_free();
+    for (const auto& kv : owners_)
+      if (kv.first != req && !kv.second.empty()) n += kv.second.back().len - kv.second.back().used;
+    auto f = owners_.find(req);
+    if (f != owners_.end() && !f->second.empty()) n += f->second.back().len - f->second.back().used;
+    return n;
+  }
+
+  // Gives `req` n more blocks (appended to out): from its active group's tail, then by
+  // growing that group in place, then from new groups of the expected size (first_group,
+  // shrunk to what is free), then from the tail of a randomly chosen other request's active
+  // group.  Caller has checked n <= obtainable(req).
+  void append(int64_t req, int64_t n, int64_t reserve_tail, std::vector<int32_t>* out) {
+    std::vector<Group>& gs = owners_[req];
+    while (n > 0) {
+      if (!gs.empty() && gs.back().used < gs.back().len) {
+        Group& g = gs.back();
+        int64_t k = std::min(n, g.len - g.used);
+        for (int64_t i = 0; i < k; ++i) out->push_back((int32_t)(g.start + g.used + i));
+        g.used += k;
+        n -= k;
+        continue;
+      }
+      if (!gs.empty()) {  // grow the active group where it stands
+        Group& g = gs.back();
+        int64_t want = std::max(n, std::min(first_group_, reserve_tail + n));
+        while (want >= n && want > 0 && !alloc_->alloc_exact(g.start + g.len, want)) want = want > n ? n : 0;
+        if (want > 0) {
+          g.len += want;
+          ++st_.grown_in_place;
+          continue;
+        }
+      }
+      int64_t start, want = std::max(n + reserve_tail, gs.empty() ? std::max(n, first_group_) : first_group_);
+      int64_t got = alloc_->alloc_run(want, &start);
+      if (got > 0) {
+        gs.push_back({start, got, 0});
+        gs.size() == 1 ? ++st_.opened : ++st_.appended_groups;
+        continue;
+      }
+      if (!steal(req, n, &gs)) break;  // nothing obtainable (caller checked, so not reached)
+    }
+  }
+
+  // The request's block table: used blocks of its groups in order.
+  void table(int64_t req, std::vector<int32_t>* out) const {
+    auto f = owners_.find(req);
+    if (f == owners_.end()) return;
+    for (const Group& g : f->second)
+      for (int64_t i = 0; i < g.used; ++i) out->push_back((int32_t)(g.start + i));
+  }
+
+  // All blocks of the request, tails included (for release).
+  void all_blocks(int64_t req, std::vector<int32_t>* out) const {
+    auto f = owners_.find(req);
+    if (f == owners_.end()) return;
+    for (const Group& g : f->second)
+      for (int64_t i = 0; i < g.len; ++i) out->push_back((int32_t)(g.start + i));
+  }
+  void forget(int64_t req) { owners_.erase(req); }
+
+  Stats stats() const {
+    Stats s = st_;
+    s.n_requests = (int64_t)owners_.size();
+    for (const auto& kv : owners_)
+      for (const Group& g : kv.second) {
+        if (g.used > 0) ++s.n_groups;
+        s.used_blocks += g.used;
+        s.tail_blocks += g.len - g.used;
+      }
+    return s;
+  }
+
+ private:
+  uint64_t next_random() {  // splitmix64
+    uint64_t z = (rng_ += 0x9E3779B97F4A7C15ull);
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    return z ^ (z >> 31);
+  }
+
+  // No free group is left: split the unused tail of a randomly selected other request's
+  // active group - all of it if it is no longer than the need, else the need or half of it,
+  // whichever is more - and give the split-off end to `req` as a new group.
+  bool steal(int64_t req, int64_t need, std::vector<Group>* gs) {
+    std::vector<int64_t> victims;
+    for (const auto& kv : owners_)
+      if (kv.first != req && !kv.second.empty() && kv.second.back().len > kv.second.back().used)
+        victims.push_back(kv.first);
+    if (victims.empty()) return false;
+    std::sort(victims.begin(), victims.end());  // map order is not deterministic
+    Group& v = owners_[victims[(size_t)(next_random() % victims.size())]].back();
+    const int64_t tail = v.len - v.used;
+    const int64_t k = tail <= need ? tail : std::max(need, tail / 2);
+    v.len -= k;
+    gs->push_back({v.start + v.len, k, 0});
+    ++st_.steals;
+    return true;
+  }
+
+  BlockGroupAllocator* alloc_ = nullptr;
+  int64_t first_group_ = 64;
+  uint64_t rng_ = 0;
+  std::unordered_map<int64_t, std::vector<Group>> owners_;
+  Stats st_;
 };
 
 }  // namespace kv

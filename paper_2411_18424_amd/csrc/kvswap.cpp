@@ -151,6 +151,7 @@ struct kv_pool {
   std::unordered_map<int64_t, Req> reqs;
   kv::RunSet arena;
   kv::BlockGroupAllocator alloc;
+  kv::BlockGroupManager groups;
   std::vector<uint64_t> reader_seq, writer_seq;  // per physical block
   std::vector<uint32_t> stamp;                   // duplicate detection
   uint32_t epoch = 0;
@@ -955,6 +956,7 @@ int32_t kv_pool_create(const kv_pool_config_t* cfg, kv_pool_t** out) {
   }
   p->arena.insert(0, p->arena_blocks);
   p->alloc.init(p->N);
+  p->groups.configure(&p->alloc, 64, 20241127);
   p->reader_seq.assign((size_t)p->N, 0);
   p->writer_seq.assign((size_t)p->N, 0);
   p->stamp.assign((size_t)p->N, 0);
@@ -1059,6 +1061,86 @@ int32_t free_block_group(kv_pool_t* p, int64_t req, const int32_t* blocks, int32
   if (!p->alloc.can_free(blocks, n_blocks, &p->free_stamp, &p->free_epoch))
     return fail(KV_EINVAL, "free of a block that is out of range, repeated, or not allocated");
   p->alloc.free_ids(blocks, n_blocks, p->reader_seq, p->pack_done_seq);
+  return KV_OK;
+}
+
+// Waits (fine-grained) for gathers that still read parked blocks until `need` blocks are free.
+static int32_t make_free(kv_pool* p, int64_t need) {
+  reap(p);
+  while (p->alloc.n_free() < need && p->alloc.n_draining() > 0) {
+    uint64_t seq = p->alloc.seq_to_release(std::min(need - p->alloc.n_free(), p->alloc.n_draining()));
+    Op* o = find_op(p->ops_out, seq);
+    if (o && o->packed && !o->packed_done && !p->plan) {
+      HIP_TRY(hipEventSynchronize(o->packed));
+      p->st.conflict_waits++;
+    }
+    int64_t before = p->alloc.n_draining();
+    reap(p);
+    if (p->alloc.n_draining() == before) break;
+  }
+  return KV_OK;
+}
+
+int32_t kv_bg_configure(kv_pool_t* p, int32_t first_group_blocks, uint64_t seed) {
+  if (!p || first_group_blocks < 0) return fail(KV_EINVAL, "bad argument");
+  std::lock_guard<std::mutex> g(p->mu);
+  p->groups.configure(&p->alloc, first_group_blocks, seed);
+  return KV_OK;
+}
+
+int32_t kv_bg_append(kv_pool_t* p, int64_t req, int32_t n_blocks, int32_t reserve_tail, int32_t* out_blocks) {
+  if (!p || n_blocks < 0 || reserve_tail < 0 || (n_blocks > 0 && !out_blocks)) return fail(KV_EINVAL, "bad argument");
+  std::lock_guard<std::mutex> g(p->mu);
+  reap(p);
+  if (p->groups.obtainable(req) < n_blocks) {
+    int32_t rc = make_free(p, n_blocks);
+    if (rc) return rc;
+    if (p->groups.obtainable(req) < n_blocks)
+      return fail(KV_ENOMEM_GPU, "need %d blocks, %lld obtainable", n_blocks, (long long)p->groups.obtainable(req));
+  }
+  std::vector<int32_t> ids;
+  ids.reserve((size_t)n_blocks);
+  p->groups.append(req, n_blocks, reserve_tail, &ids);
+  if ((int32_t)ids.size() != n_blocks) return fail(KV_ENOMEM_GPU, "block groups exhausted");
+  if (n_blocks > 0) memcpy(out_blocks, ids.data(), sizeof(int32_t) * (size_t)n_blocks);
+  return KV_OK;
+}
+
+int32_t kv_bg_table(kv_pool_t* p, int64_t req, int32_t* out_blocks, int32_t cap, int32_t* out_n) {
+  if (!p || !out_n || cap < 0) return fail(KV_EINVAL, "bad argument");
+  std::lock_guard<std::mutex> g(p->mu);
+  if (!p->groups.has(req)) return fail(KV_ENOENT, "request %lld owns no block group", (long long)req);
+  std::vector<int32_t> ids;
+  p->groups.table(req, &ids);
+  *out_n = (int32_t)ids.size();
+  if (out_blocks && cap > 0) memcpy(out_blocks, ids.data(), sizeof(int32_t) * (size_t)std::min<int64_t>(cap, (int64_t)ids.size()));
+  return KV_OK;
+}
+
+int32_t kv_bg_close(kv_pool_t* p, int64_t req) {
+  if (!p) return fail(KV_EINVAL, "null pool");
+  std::lock_guard<std::mutex> g(p->mu);
+  if (!p->groups.has(req)) return fail(KV_ENOENT, "request %lld owns no block group", (long long)req);
+  reap(p);
+  std::vector<int32_t> ids;
+  p->groups.all_blocks(req, &ids);
+  p->groups.forget(req);
+  p->alloc.free_ids(ids.data(), (int32_t)ids.size(), p->reader_seq, p->pack_done_seq);
+  return KV_OK;
+}
+
+int32_t kv_bg_stats(kv_pool_t* p, kv_bg_stats_t* out) {
+  if (!p || !out) return fail(KV_EINVAL, "null argument");
+  std::lock_guard<std::mutex> g(p->mu);
+  const kv::BlockGroupManager::Stats s = p->groups.stats();
+  out->n_requests = s.n_requests;
+  out->n_groups = s.n_groups;
+  out->used_blocks = s.used_blocks;
+  out->tail_blocks = s.tail_blocks;
+  out->steals = s.steals;
+  out->opened = s.opened;
+  out->appended_groups = s.appended_groups;
+  out->grown_in_place = s.grown_in_place;
   return KV_OK;
 }
 

@@ -53,6 +53,11 @@ class kv_stats_t(C.Structure):
         "host_new_extents", "host_arena_used", "host_arena_bytes")]
 
 
+class kv_bg_stats_t(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in ("n_requests", "n_groups", "used_blocks", "tail_blocks",
+                                         "steals", "opened", "appended_groups", "grown_in_place")]
+
+
 class kv_manager_config_t(C.Structure):
     _fields_ = [("window", C.c_int32), ("reserved", C.c_int32), ("link_gbps", C.c_double),
                 ("sync_below_ms", C.c_double)]
@@ -83,6 +88,11 @@ def _load() -> C.CDLL:
         "alloc_block_group": (C.c_int32, [pool_p, C.c_int64, C.c_int32, C.c_int32, i32p, i32p]),
         "free_block_group": (C.c_int32, [pool_p, C.c_int64, i32p, C.c_int32]),
         "kv_free_blocks": (C.c_int32, [pool_p, i64p, i64p]),
+        "kv_bg_configure": (C.c_int32, [pool_p, C.c_int32, C.c_uint64]),
+        "kv_bg_append": (C.c_int32, [pool_p, C.c_int64, C.c_int32, C.c_int32, i32p]),
+        "kv_bg_table": (C.c_int32, [pool_p, C.c_int64, i32p, C.c_int32, i32p]),
+        "kv_bg_close": (C.c_int32, [pool_p, C.c_int64]),
+        "kv_bg_stats": (C.c_int32, [pool_p, P(kv_bg_stats_t)]),
         "swap_out": (C.c_int32, [pool_p, C.c_int64, i32p, C.c_int32]),
         "swap_out_delta": (C.c_int32, [pool_p, C.c_int64, i32p, C.c_int32, u8p, i32p]),
         "swap_in": (C.c_int32, [pool_p, C.c_int64, i32p, C.c_int32]),
@@ -222,6 +232,31 @@ class KVPool:
         f, l = C.c_int64(), C.c_int64()
         _check(lib.kv_free_blocks(self._h, C.byref(f), C.byref(l)))
         return f.value, l.value
+
+    # -- block groups of growing requests
+    def kv_bg_configure(self, first_group_blocks: int = 0, seed: int = 20241127):
+        _check(lib.kv_bg_configure(self._h, first_group_blocks, seed))
+
+    def kv_bg_append(self, req: int, n_blocks: int, reserve_tail: int = 0) -> np.ndarray:
+        out = np.empty(n_blocks, dtype=np.int32)
+        _check(lib.kv_bg_append(self._h, req, n_blocks, reserve_tail,
+                                out.ctypes.data_as(C.POINTER(C.c_int32))))
+        return out
+
+    def kv_bg_table(self, req: int) -> np.ndarray:
+        n = C.c_int32()
+        _check(lib.kv_bg_table(self._h, req, None, 0, C.byref(n)))
+        out = np.empty(n.value, dtype=np.int32)
+        _check(lib.kv_bg_table(self._h, req, out.ctypes.data_as(C.POINTER(C.c_int32)), n.value, C.byref(n)))
+        return out
+
+    def kv_bg_close(self, req: int):
+        _check(lib.kv_bg_close(self._h, req))
+
+    def kv_bg_stats(self) -> dict:
+        st = kv_bg_stats_t()
+        _check(lib.kv_bg_stats(self._h, C.byref(st)))
+        return {n: getattr(st, n) for n, _ in kv_bg_stats_t._fields_}
 
     # -- swaps
     def swap_out(self, req: int, block_table):

@@ -341,3 +341,86 @@ def test_swap_manager_strategy_follows_swap_in_size(kv):
     assert s["strategy_calls"] == 4 and s["strategy_async"] == 2
     m.kv_manager_destroy()
     m2.kv_manager_destroy()
+
+
+def test_block_groups_grow_steal_and_return(kv):
+    """Section 3.1: a request grows inside its active group; when no free group is left the
+    tail of another request's active group is split off; closing returns everything."""
+    shape = synth.KVShape("s", 1, 1, 8, 1, 2, 96, "fp16")
+    p = plan_pool(kv, shape)
+    p.kv_bg_configure(32, 1)
+    chk = AllocChecker(96)
+    a = p.kv_bg_append(1, 5)                       # opens a group of 32, uses 5
+    assert a.tolist() == [0, 1, 2, 3, 4]
+    chk.on_alloc(1, a)
+    b = p.kv_bg_append(2, 3)                       # second request: its own group of 32
+    assert b.tolist() == [32, 33, 34]
+    chk.on_alloc(2, b)
+    for k in range(5, 32):                         # request 1 grows one block at a time, contiguously
+        x = p.kv_bg_append(1, 1)
+        assert x.tolist() == [k]
+        chk.on_alloc(1, x)
+    x = p.kv_bg_append(1, 1)                       # active group full and its neighbour taken: new group
+    assert x.tolist() == [64]
+    chk.on_alloc(1, x)
+    st = p.kv_bg_stats()
+    assert (st["n_requests"], st["used_blocks"], st["tail_blocks"], st["steals"]) == (2, 36, 60, 0)
+    assert p.kv_free_blocks()[0] == 0              # every block is used or reserved as a tail
+    c = p.kv_bg_append(3, 10)                      # no free group: steals from an active tail
+    chk.on_alloc(3, c)
+    assert AllocChecker.run_lengths(c) == [10]
+    st = p.kv_bg_stats()
+    assert st["steals"] == 1 and st["used_blocks"] == 46
+    assert np.array_equal(p.kv_bg_table(1), np.concatenate([np.arange(32), [64]]))
+    assert np.array_equal(p.kv_bg_table(3), c)
+    with pytest.raises(kv.KVError) as ei:
+        p.kv_bg_append(4, 60)                      # more than free blocks + other requests' tails
+    assert ei.value.status == kv.KV_ENOMEM_GPU
+    assert p.kv_bg_stats()["used_blocks"] == 46
+    for r in (1, 2, 3):
+        p.kv_bg_close(r)
+    assert p.kv_free_blocks() == (96, 96)
+    with pytest.raises(kv.KVError):
+        p.kv_bg_close(1)
+
+
+def test_block_groups_never_double_assign_under_churn(kv):
+    shape = synth.KVShape("s", 1, 1, 8, 1, 2, 600, "fp16")
+    p = plan_pool(kv, shape)
+    p.kv_bg_configure(24, 5)
+    chk = AllocChecker(600)
+    rng = synth.rng_for(33)
+    owned = {}
+    for step in range(3000):
+        r = int(rng.integers(0, 24))
+        if r in owned and rng.random() < 0.08:
+            assert np.array_equal(p.kv_bg_table(r), np.concatenate(owned[r]))
+            p.kv_bg_close(r)
+            chk.on_free(r, np.concatenate(owned.pop(r)))
+            continue
+        n = int(rng.integers(1, 4)) if r in owned else int(rng.integers(1, 60))
+        try:
+            ids = p.kv_bg_append(r, n, int(rng.integers(0, 8)))
+        except kv.KVError as e:
+            assert e.status == kv.KV_ENOMEM_GPU
+            continue
+        chk.on_alloc(r, ids)
+        owned.setdefault(r, []).append(ids)
+    st = p.kv_bg_stats()
+    assert st["used_blocks"] == chk.n_used() and st["steals"] > 0
+    assert st["used_blocks"] + st["tail_blocks"] + p.kv_free_blocks()[0] == 600
+    for r in list(owned):
+        p.kv_bg_close(r)
+    assert p.kv_free_blocks() == (600, 600)
+
+
+def test_granularity_grows_with_the_first_group_size():
+    """The synthetic serving loop: larger first groups give fewer, longer groups per swap-out
+    (Section 5.3.1 measures this on its traces; here only the direction is checked)."""
+    from paper_2411_18424_amd import granularity
+    small = granularity.simulate(first_group=1, pattern="markov", n_iters=1500)
+    large = granularity.simulate(first_group=64, pattern="markov", n_iters=1500)
+    assert small["swap_outs"] > 50 and large["swap_outs"] > 50
+    assert large["avg_blocks_per_group"] > 1.5 * small["avg_blocks_per_group"]
+    assert large["avg_groups_per_swap"] < small["avg_groups_per_swap"]
+    assert granularity.run_lengths([3, 4, 5, 9, 10, 2]) == [3, 2, 1]

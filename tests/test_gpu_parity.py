@@ -535,3 +535,44 @@ def test_mapped_swap_in_reads_the_host_image_directly(harness, L, H, D, B, e, N)
     h.assert_pool_equal()
     st = h.pool.kv_stats()
     assert st["h2d_copies"] == 0 and st["bytes_in"] == h.oracle.bytes_in
+
+
+def test_growing_requests_through_block_groups(harness):
+    """Requests grow through the block-group manager, are preempted (swap-out, groups closed
+    while the gather may still be reading them) and resumed into whatever groups are free."""
+    shape = synth.KVShape("s", 2, 4, 64, 16, 2, 160, "fp16")
+    h = harness(shape, cfg=19, host_bytes=256 * MiB)
+    h.pool.kv_bg_configure(16, 3)
+    rng = synth.rng_for(19)
+    chk = AllocChecker(shape.n_blocks)
+    n_of = {}
+    for r in range(6):
+        ids = h.pool.kv_bg_append(r, int(rng.integers(4, 20)), 4)
+        chk.on_alloc(r, ids)
+        h.overwrite_blocks(ids, synth.fresh_tokens(rng, shape, len(ids)))
+        n_of[r] = len(ids)
+    for rnd in range(4):
+        for r in range(6):                     # everybody decodes: one more block each
+            ids = h.pool.kv_bg_append(r, 1)
+            chk.on_alloc(r, ids)
+            h.overwrite_blocks(ids, synth.fresh_tokens(rng, shape, 1))
+            n_of[r] += 1
+        victims = [int(v) for v in rng.permutation(6)[:3]]
+        for v in victims:                      # preempt three of them
+            t = h.pool.kv_bg_table(v)
+            assert len(t) == n_of[v]
+            h.pool.swap_out(v, t)
+            h.oracle.swap_out(v, t)
+            h.pool.kv_bg_close(v)
+            chk.on_free(v, t)
+        for v in victims:                      # ... and resume them right away
+            ids = h.pool.kv_bg_append(v, n_of[v], 2)
+            chk.on_alloc(v, ids)
+            h.pool.swap_in(v, ids)
+            h.oracle.swap_in(v, ids)
+        h.pool.kv_wait_all()
+        for v in victims:
+            h.assert_image_equal(v)
+        h.assert_pool_equal()
+    st = h.pool.kv_bg_stats()
+    assert st["used_blocks"] == chk.n_used() == sum(n_of.values())
