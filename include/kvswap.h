@@ -63,6 +63,12 @@ typedef enum {
 #define KV_FLAG_MAPPED_SWAP_IN  16u /* swap-in reads the pinned host image directly from a small scatter
                                        kernel (no staging, no copy engine): lower latency, and the cost no
                                        longer depends on how fragmented the moved set is */
+#define KV_FLAG_HOST_EVICT      32u /* when the host arena is full, reclaim the host copies of other requests
+                                       (Section 3.3: contamination by higher-priority requests): lowest
+                                       priority first, least recently used first, never from a request of
+                                       higher priority than the caller's or with work in flight.  Room held
+                                       in reserve goes first, then the records of the victim's last logical
+                                       blocks, whose host_valid bits are cleared */
 #define KV_FLAG_FOUR_STREAMS     8u /* separate streams for kernels and copies of each direction (default:
                                        one stream per direction, which needs fewer hardware queues) */
 
@@ -199,7 +205,8 @@ int32_t kv_wait_all(kv_pool_t* pool);
  * and the arena space behind it is taken - an image is never moved.  kv_host_len reports
  * its length and extent count; kv_host_blocks reports where each logical block is:
  * record_index[j] (caller-allocated, n = image length) is the index of the R-byte record
- * [P][C] of logical block j, i.e. its bytes start at *arena_base + record_index[j]*R.
+ * [P][C] of logical block j, i.e. its bytes start at *arena_base + record_index[j]*R
+ * (-1: the block has no record because its space was reclaimed; its host_valid bit is 0).
  * Consecutive logical blocks are adjacent inside an extent.  Valid until the image is
  * released or rebuilt by a full swap_out; wait for the request before reading the bytes. */
 int32_t kv_host_len(kv_pool_t* pool, int64_t req, int32_t* n_blocks, int32_t* n_extents);
@@ -208,6 +215,8 @@ int32_t kv_host_blocks(kv_pool_t* pool, int64_t req, const void** arena_base, in
 int32_t kv_host_valid(kv_pool_t* pool, int64_t req, uint8_t* out_mask, int32_t n); /* 1 = valid */
 int32_t kv_host_invalidate(kv_pool_t* pool, int64_t req, const uint8_t* mask, int32_t n); /* contaminate */
 int32_t kv_host_release(kv_pool_t* pool, int64_t req);        /* drop the image (waits for its ops) */
+int32_t kv_host_set_priority(kv_pool_t* pool, int64_t req, int32_t priority); /* default 0; used by
+                                                                 KV_FLAG_HOST_EVICT */
 
 typedef struct {
   int64_t bytes_out, bytes_in;          /* payload bytes enqueued per direction (moved blocks * R) */
@@ -216,6 +225,7 @@ typedef struct {
   int64_t d2h_copies, h2d_copies;
   int64_t conflict_waits;               /* device-side waits inserted by conflict detection */
   int64_t host_new_extents;             /* image growths that had to open a new arena extent */
+  int64_t host_evicted_blocks;          /* logical blocks whose host copy was reclaimed (KV_FLAG_HOST_EVICT) */
   int64_t host_arena_used, host_arena_bytes;
 } kv_stats_t;
 int32_t kv_stats(kv_pool_t* pool, kv_stats_t* out);

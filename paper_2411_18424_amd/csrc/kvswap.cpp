@@ -77,9 +77,10 @@ struct Extent {
 
 struct Image {
   std::vector<Extent> ext;
-  int32_t n = 0;  // logical blocks
+  int32_t n = 0;       // logical blocks
+  int32_t mapped = 0;  // logical blocks [0, mapped) have a record; the rest lost theirs to eviction
   std::vector<uint8_t> valid;
-  std::vector<int64_t> rec;
+  std::vector<int64_t> rec;  // -1 = no record
   int64_t room() const {
     int64_t r = 0;
     for (const Extent& e : ext) r += e.cap;
@@ -92,6 +93,8 @@ struct Req {
   Image img;
   OpRef last;      // last op of any kind
   OpRef last_out;  // last swap-out
+  int32_t prio = 0;       // host copies of lower-priority requests are reclaimed first
+  uint64_t last_use = 0;  // for least-recently-used order among equals
 };
 
 // Staging is a byte ring: a piece of a swap takes exactly the bytes it needs, so many small
@@ -134,6 +137,8 @@ struct kv_pool {
   char* host = nullptr;      // pinned arena
   char* host_dev = nullptr;  // the arena as the device addresses it
   bool mapped_in = false;
+  bool host_evict = false;
+  uint64_t use_clock = 0;
   int mapped_grid = 64;
   int64_t arena_blocks = 0;
   bool own_staging = false;
@@ -321,6 +326,69 @@ void image_map(Image& im, int32_t from, int32_t to) {
     while (im.ext[e].used == im.ext[e].cap) ++e;
     im.rec[(size_t)j] = im.ext[e].off + im.ext[e].used++;
   }
+}
+
+// Gives the last k records of an image back to the arena: unused room first, then the records
+// of its last logical blocks, which thereby lose their host copy (Section 3.3: the CPU copy is
+// contaminated when its space is reclaimed for a higher-priority request).  Returns the number
+// of logical blocks that lost their copy.
+int64_t image_trim_tail(kv_pool* p, Image& im, int64_t k) {
+  int64_t lost = 0;
+  while (k > 0 && !im.ext.empty()) {
+    Extent& e = im.ext.back();
+    const int64_t cut = std::min(k, e.cap);
+    const int64_t new_cap = e.cap - cut;
+    if (e.used > new_cap) {
+      const int64_t un = e.used - new_cap;
+      for (int64_t i = 0; i < un; ++i) {
+        const size_t j = (size_t)(--im.mapped);
+        im.valid[j] = 0;
+        im.rec[j] = -1;
+      }
+      lost += un;
+      e.used = new_cap;
+    }
+    p->arena.insert(e.off + new_cap, cut);
+    e.cap = new_cap;
+    if (e.cap == 0) im.ext.pop_back();
+    k -= cut;
+  }
+  return lost;
+}
+
+// KV_FLAG_HOST_EVICT: makes `need` records free by reclaiming the host copies of other
+// requests - lowest priority first, least recently used first, never a request of higher
+// priority than the caller's, never one whose last op is still in flight, never one named in
+// `keep`.  All or nothing: returns false without touching anything if that is not enough.
+bool arena_evict(kv_pool* p, int64_t need, int32_t prio, const std::vector<int64_t>& keep) {
+  if (!p->host_evict) return false;
+  struct Cand {
+    int32_t prio;
+    uint64_t last_use;
+    int64_t req, room;
+  };
+  std::vector<Cand> cands;
+  int64_t avail = p->arena.total();
+  for (auto& kvp : p->reqs) {
+    Req& q = kvp.second;
+    if (!q.has_image || q.prio > prio) continue;
+    if (q.last && !q.last->all_done) continue;
+    if (std::find(keep.begin(), keep.end(), kvp.first) != keep.end()) continue;
+    const int64_t room = q.img.room();
+    if (room <= 0) continue;
+    cands.push_back({q.prio, q.last_use, kvp.first, room});
+    avail += room;
+  }
+  if (avail < need) return false;
+  std::sort(cands.begin(), cands.end(), [](const Cand& a, const Cand& b) {
+    return a.prio != b.prio ? a.prio < b.prio : (a.last_use != b.last_use ? a.last_use < b.last_use : a.req < b.req);
+  });
+  for (const Cand& c : cands) {
+    if (p->arena.total() >= need) break;
+    Image& im = p->reqs[c.req].img;
+    p->st.host_evicted_blocks += image_trim_tail(p, im, std::min(c.room, need - p->arena.total()));
+  }
+  return p->arena.total() >= need;
 }
 
 // ---------------------------------------------------------------- engine
@@ -712,7 +780,16 @@ int32_t do_swap_out(kv_pool* p, std::vector<OutItem>& items, int32_t* out_n_move
     } else {
       it.fresh = true;
     }
-    if (!arena_take(p, need, &it.new_ext, !it.fresh)) {
+    bool got = arena_take(p, need, &it.new_ext, !it.fresh);
+    if (!got) {
+      // reclaim host copies of lower-priority requests (not those of this very call)
+      std::vector<int64_t> keep;
+      for (const OutItem& o : items) keep.push_back(o.req);
+      auto fq = p->reqs.find(it.req);
+      got = arena_evict(p, need, fq != p->reqs.end() ? fq->second.prio : 0, keep) &&
+            arena_take(p, need, &it.new_ext, !it.fresh);
+    }
+    if (!got) {
       undo(a);
       return fail(KV_ENOMEM_HOST, "host arena full: need %lld block records, %lld free (largest run %lld)",
                   (long long)need, (long long)p->arena.total(), (long long)p->arena.largest());
@@ -738,7 +815,7 @@ int32_t do_swap_out(kv_pool* p, std::vector<OutItem>& items, int32_t* out_n_move
         arena_give(p, im.ext);
       }
       im.ext = it.new_ext;
-      im.n = 0;
+      im.n = im.mapped = 0;
       im.valid.clear();
       im.rec.clear();
       q.has_image = true;
@@ -754,11 +831,15 @@ int32_t do_swap_out(kv_pool* p, std::vector<OutItem>& items, int32_t* out_n_move
       im.n = it.n;
       im.valid.assign((size_t)it.n, 0);
       image_map(im, 0, it.n);
-    } else if (it.n > im.n) {
-      im.valid.resize((size_t)it.n, 0);
-      image_map(im, im.n, it.n);
-      im.n = it.n;
+    } else {
+      if (it.n > im.n) {
+        im.valid.resize((size_t)it.n, 0);
+        im.n = it.n;
+      }
+      if (im.mapped < im.n) image_map(im, im.mapped, im.n);  // new blocks, and blocks that lost their record
     }
+    im.mapped = im.n;
+    q.last_use = ++p->use_clock;
     int32_t moved = 0;
     for (int32_t j = 0; j < it.n; ++j) {
       if (it.dirty && !it.dirty[j] && q.img.valid[(size_t)j]) continue;
@@ -832,6 +913,7 @@ int32_t do_swap_in(kv_pool* p, std::vector<InItem>& items, int32_t* out_n_moved,
     }
     if (q.last && !q.last->all_done && q.last->done) pre_copy.push_back(q.last->done);
     q.last = op;
+    q.last_use = ++p->use_clock;
   }
   if (max_reader > p->pack_done_seq) {  // a gather still reads blocks we are about to overwrite
     if (Op* r = find_op(p->ops_out, max_reader)) {
@@ -923,6 +1005,7 @@ int32_t kv_pool_create(const kv_pool_config_t* cfg, kv_pool_t** out) {
   p->unroll = cfg->tile_unroll;  // 0 = pick from the chunk size
   p->variant = cfg->pack_variant;
   p->mapped_in = (cfg->flags & KV_FLAG_MAPPED_SWAP_IN) != 0;
+  p->host_evict = (cfg->flags & KV_FLAG_HOST_EVICT) != 0;
   if (cfg->mapped_in_grid > 0) p->mapped_grid = cfg->mapped_in_grid;
   p->launch_blocks = kv_max_launch_blocks((uint32_t)C, (uint32_t)p->P, p->unroll, p->variant);
   // staging rings: defaults scale with the pool, capped at 4 GiB (out) and 1 GiB (in)
@@ -1340,6 +1423,13 @@ int32_t kv_host_invalidate(kv_pool_t* p, int64_t req, const uint8_t* mask, int32
   if (n != f->second.img.n) return fail(KV_EINVAL, "mask has %d entries, host image has %d blocks", n, f->second.img.n);
   for (int32_t j = 0; j < n; ++j)
     if (mask[j]) f->second.img.valid[(size_t)j] = 0;
+  return KV_OK;
+}
+
+int32_t kv_host_set_priority(kv_pool_t* p, int64_t req, int32_t priority) {
+  if (!p) return fail(KV_EINVAL, "null pool");
+  std::lock_guard<std::mutex> g(p->mu);
+  p->reqs[req].prio = priority;
   return KV_OK;
 }
 

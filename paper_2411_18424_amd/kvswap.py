@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libkvswap.so")
 KV_OK, KV_EINVAL, KV_ENOMEM_GPU, KV_ENOMEM_HOST = 0, -1, -2, -3
 KV_ENOENT, KV_EBUSY, KV_EHIP, KV_ENODEV = -4, -5, -6, -7
 KV_FLAG_PLAN_ONLY, KV_FLAG_PROFILE, KV_FLAG_ORDER_COMPUTE, KV_FLAG_FOUR_STREAMS = 1, 2, 4, 8
-KV_FLAG_MAPPED_SWAP_IN = 16
+KV_FLAG_MAPPED_SWAP_IN, KV_FLAG_HOST_EVICT = 16, 32
 KV_TASK_SWAP_OUT, KV_TASK_SWAP_IN, KV_TASK_SWAP_OUT_DELTA, KV_TASK_SWAP_IN_DELTA = 0, 1, 2, 3
 
 _STATUS_NAMES = {0: "KV_OK", -1: "KV_EINVAL", -2: "KV_ENOMEM_GPU", -3: "KV_ENOMEM_HOST",
@@ -50,7 +50,7 @@ class kv_stats_t(C.Structure):
     _fields_ = [(n, C.c_int64) for n in (
         "bytes_out", "bytes_in", "blocks_out", "blocks_in", "gather_launches",
         "scatter_launches", "d2h_copies", "h2d_copies", "conflict_waits",
-        "host_new_extents", "host_arena_used", "host_arena_bytes")]
+        "host_new_extents", "host_evicted_blocks", "host_arena_used", "host_arena_bytes")]
 
 
 class kv_bg_stats_t(C.Structure):
@@ -111,6 +111,7 @@ def _load() -> C.CDLL:
         "kv_host_valid": (C.c_int32, [pool_p, C.c_int64, u8p, C.c_int32]),
         "kv_host_invalidate": (C.c_int32, [pool_p, C.c_int64, u8p, C.c_int32]),
         "kv_host_release": (C.c_int32, [pool_p, C.c_int64]),
+        "kv_host_set_priority": (C.c_int32, [pool_p, C.c_int64, C.c_int32]),
         "kv_stats": (C.c_int32, [pool_p, P(kv_stats_t)]),
         "kv_profile_read": (C.c_int32, [pool_p, P(kv_prof_record_t), C.c_int32, i32p]),
         "kv_profile_reset": (C.c_int32, [pool_p]),
@@ -346,6 +347,15 @@ class KVPool:
         n = idx.size
         if n == 0:
             return np.zeros((0, self.P, self.C), dtype=np.uint8)
+        if (idx < 0).any():  # some blocks lost their record: they read as zeros
+            out = np.zeros((n, self.P, self.C), dtype=np.uint8)
+            have = np.flatnonzero(idx >= 0)
+            if have.size:
+                lo, hi = int(idx[have].min()), int(idx[have].max())
+                buf = (C.c_uint8 * ((hi - lo + 1) * self.R)).from_address(base + lo * self.R)
+                span = np.frombuffer(buf, dtype=np.uint8).reshape(hi - lo + 1, self.P, self.C)
+                out[have] = span[idx[have] - lo]
+            return out
         lo, hi = int(idx.min()), int(idx.max())
         buf = (C.c_uint8 * ((hi - lo + 1) * self.R)).from_address(base + lo * self.R)
         span = np.frombuffer(buf, dtype=np.uint8).reshape(hi - lo + 1, self.P, self.C)
@@ -364,6 +374,9 @@ class KVPool:
 
     def kv_host_release(self, req: int):
         _check(lib.kv_host_release(self._h, req))
+
+    def kv_host_set_priority(self, req: int, priority: int):
+        _check(lib.kv_host_set_priority(self._h, req, priority))
 
     # -- stats / profiling
     def kv_stats(self) -> dict:

@@ -23,11 +23,11 @@ def kv():
     return kvswap
 
 
-def plan_pool(kv, shape, host_blocks=64, **kw):
+def plan_pool(kv, shape, host_blocks=64, flags_extra=0, **kw):
     return kv.KVPool(n_layers=shape.n_layers, n_kv_heads=shape.n_kv_heads, head_dim=shape.head_dim,
                      block_size=shape.block_size, elt_bytes=shape.elt_bytes,
                      n_gpu_blocks=shape.n_blocks, host_bytes=host_blocks * shape.R,
-                     flags=kv.KV_FLAG_PLAN_ONLY, **kw)
+                     flags=kv.KV_FLAG_PLAN_ONLY | flags_extra, **kw)
 
 
 def test_header_symbols_are_exported(kv):
@@ -424,3 +424,60 @@ def test_granularity_grows_with_the_first_group_size():
     assert large["avg_blocks_per_group"] > 1.5 * small["avg_blocks_per_group"]
     assert large["avg_groups_per_swap"] < small["avg_groups_per_swap"]
     assert granularity.run_lengths([3, 4, 5, 9, 10, 2]) == [3, 2, 1]
+
+
+def test_host_eviction_by_priority_and_recency(kv):
+    """KV_FLAG_HOST_EVICT (Section 3.3, contamination): a full arena reclaims the host copies of
+    lower-priority requests - reserved room first, then their last logical blocks - never of
+    higher-priority ones; all or nothing."""
+    shape = synth.TINY
+    p = plan_pool(kv, shape, host_blocks=40, host_slack_blocks=2, flags_extra=kv.KV_FLAG_HOST_EVICT)
+    t = np.arange(200, dtype=np.int32)
+    for r, prio in ((0, 5), (1, 1), (2, 1), (3, 9)):
+        p.kv_host_set_priority(r, prio)
+        p.swap_out(r, t[10 * r:10 * r + 8])          # 8 records + 2 of room each: arena full
+    assert p.kv_stats()["host_arena_used"] == 40 * shape.R
+    p.swap_in(2, t[100:108])                         # request 2 was used more recently than 1
+    # request 0 (priority 5) needs 12 records more than it has room for
+    moved = p.swap_out_delta(0, t[40:60], np.zeros(20, np.uint8))
+    assert moved == 12
+    st = p.kv_stats()
+    # 10 + 2 slack wanted -> falls back to what can be had; victims: request 1 first (LRU), then 2
+    v1, v2, v3 = p.kv_host_valid(1, 8), p.kv_host_valid(2, 8), p.kv_host_valid(3, 8)
+    assert v3.all(), "a higher-priority request must never be evicted"
+    lost1, lost2 = int(8 - v1.sum()), int(8 - v2.sum())
+    assert lost1 > 0 and lost1 >= lost2
+    assert st["host_evicted_blocks"] == lost1 + lost2
+    assert (v1[:8 - lost1] == 1).all() and (v1[8 - lost1:] == 0).all()   # the tail goes first
+    assert st["host_arena_used"] <= 40 * shape.R
+    # the evicted request gets its blocks back on its next swap-out (it may evict in turn)
+    p.kv_host_set_priority(1, 7)
+    assert p.swap_out_delta(1, t[110:118], np.zeros(8, np.uint8)) == lost1
+    assert p.kv_host_valid(1, 8).all()
+    # a request that outranks nobody cannot evict: error without effect
+    p.kv_host_set_priority(7, 0)
+    before = (p.kv_stats(), p.kv_host_valid(0, 20).tolist(), p.kv_host_valid(2, 8).tolist())
+    with pytest.raises(kv.KVError) as ei:
+        p.swap_out(7, t[150:190])
+    assert ei.value.status == kv.KV_ENOMEM_HOST
+    assert (p.kv_stats(), p.kv_host_valid(0, 20).tolist(), p.kv_host_valid(2, 8).tolist()) == before
+    # swap-in of a block that lost its copy is refused unless it is resident
+    if lost2:
+        with pytest.raises(kv.KVError) as ei:
+            p.swap_in(2, t[120:128])
+        assert ei.value.status == kv.KV_ENOENT
+        res = 1 - p.kv_host_valid(2, 8)
+        assert p.swap_in_delta(2, t[120:128], res) == 8 - lost2
+
+
+def test_reuse_cuts_swap_out_volume_and_small_host_memory_erodes_it():
+    """Direction of the paper's microbenchmark (Section 5.3.3): with reuse far fewer blocks are
+    swapped out than when the whole context leaves every time; a smaller host arena means more
+    contaminated copies and more blocks sent again."""
+    from paper_2411_18424_amd import reuse_sim
+    base = reuse_sim.simulate(1 << 20, reuse=False, n_preempt=300)
+    big = reuse_sim.simulate(1 << 20, reuse=True, n_preempt=300)
+    small = reuse_sim.simulate(4000, reuse=True, n_preempt=300)
+    assert big["blocks_out"] < 0.5 * base["blocks_out"]
+    assert big["evicted_blocks"] == 0 and small["evicted_blocks"] > 0
+    assert big["blocks_out"] < small["blocks_out"] < base["blocks_out"]

@@ -576,3 +576,69 @@ def test_growing_requests_through_block_groups(harness):
         h.assert_pool_equal()
     st = h.pool.kv_bg_stats()
     assert st["used_blocks"] == chk.n_used() == sum(n_of.values())
+
+
+def test_host_arena_eviction_keeps_data_exact(harness):
+    """A small host arena with KV_FLAG_HOST_EVICT: which blocks get reclaimed is the policy's
+    choice (any lower-priority, idle victim is valid), so the oracle is told which bits the
+    library cleared; every byte that remains valid, and every later re-send, must be exact."""
+    shape = synth.KVShape("s", 2, 4, 64, 16, 2, 200, "fp16")
+    h = harness(shape, cfg=20, host_bytes=60 * synth.KVShape("s", 2, 4, 64, 16, 2, 200, "fp16").R,
+                flags=32, host_slack_blocks=2)
+    rng = synth.rng_for(20)
+    sizes, tables = {}, {}
+    prio = {r: int(rng.integers(0, 4)) for r in range(8)}
+    for r in range(8):
+        h.pool.kv_host_set_priority(r, prio[r])
+
+    def sync_evictions():
+        for r in sizes:
+            lib_valid = h.pool.kv_host_valid(r, sizes[r]).astype(bool)
+            ora = h.oracle.host[r].host_valid
+            assert not (lib_valid & ~ora).any()           # the library never validates on its own
+            gone = ora & ~lib_valid
+            if gone.any():
+                assert all(prio[r] <= prio[o] for o in [last_caller])  # only lower or equal priority
+                h.oracle.host_invalidate(r, gone.astype(np.uint8))
+
+    evicted_total = 0
+    for step in range(60):
+        r = int(rng.integers(0, 8))
+        last_caller = r
+        n = sizes.get(r, 0) + int(rng.integers(1, 10))
+        n = min(n, 24)
+        t = rng.permutation(200)[:n].astype(np.int32)
+        payload = synth.fresh_tokens(rng, shape, n)
+        h.overwrite_blocks(t, payload)
+        dirty = synth.random_mask(rng, n, 0.3)
+        try:
+            if r in sizes:
+                moved = h.pool.swap_out_delta(r, t, dirty)
+            else:
+                h.pool.swap_out(r, t)
+                moved = n
+        except h.kv.KVError as e:
+            assert e.status == h.kv.KV_ENOMEM_HOST
+            sync_evictions()                               # a failed call must have evicted nothing
+            continue
+        if r in sizes:
+            want = h.oracle.swap_out_delta(r, t, dirty)
+            # blocks evicted from r itself earlier are already invalid in the oracle
+            assert moved == len(want)
+        else:
+            h.oracle.swap_out(r, t)
+        sizes[r], tables[r] = n, t
+        h.pool.kv_wait(r)
+        sync_evictions()
+        for q in sizes:
+            h.assert_image_equal(q)
+        evicted_total = h.pool.kv_stats()["host_evicted_blocks"]
+    assert evicted_total > 0
+    # everything still valid can be swapped back in exactly
+    for r in sizes:
+        valid = h.pool.kv_host_valid(r, sizes[r])
+        t2 = rng.permutation(200)[:sizes[r]].astype(np.int32)
+        h.pool.swap_in_delta(r, t2, 1 - valid)
+        h.oracle.swap_in(r, t2, resident=1 - valid)
+        h.pool.kv_wait(r)
+        h.assert_pool_equal()
