@@ -481,3 +481,17 @@ def test_reuse_cuts_swap_out_volume_and_small_host_memory_erodes_it():
     assert big["blocks_out"] < 0.5 * base["blocks_out"]
     assert big["evicted_blocks"] == 0 and small["evicted_blocks"] > 0
     assert big["blocks_out"] < small["blocks_out"] < base["blocks_out"]
+
+
+def test_device_pool_fails_loudly_without_a_gpu(kv):
+    """No CPU fallback: without a device a real (non plan-only) pool cannot be created."""
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    s = synth.TINY
+    with pytest.raises(kv.KVError) as ei:
+        kv.KVPool(n_layers=s.n_layers, n_kv_heads=s.n_kv_heads, head_dim=s.head_dim, block_size=s.block_size,
+                  elt_bytes=s.elt_bytes, n_gpu_blocks=s.n_blocks, gpu_base=0x1000, host_bytes=1 << 20)
+    assert ei.value.status in (kv.KV_EHIP, kv.KV_ENOMEM_HOST, kv.KV_ENOMEM_GPU)
+    with pytest.raises(kv.KVError):
+        kv.kv_link_probe(1 << 20, 0, 1)
