@@ -130,7 +130,8 @@ def main() -> int:
                      block_size=s.block_size, elt_bytes=s.elt_bytes, n_gpu_blocks=s.n_blocks,
                      gpu_base=gpu.data_ptr(), host_bytes=payload + 64 * len(victims) * s.R,
                      flags=kv.KV_FLAG_PROFILE | (kv.KV_FLAG_FOUR_STREAMS if args.four_streams else 0)
-                     | (kv.KV_FLAG_MAPPED_SWAP_IN if args.mapped_swap_in else 0))
+                     | (kv.KV_FLAG_MAPPED_SWAP_IN if args.mapped_swap_in else 0),
+                     pack_variant=int(os.environ.get("KVSWAP_PACK_VARIANT", "0")))
     cur = [work.tables[v] for v in victims]
     nxt = list(work.resume_tables)
 

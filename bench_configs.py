@@ -35,6 +35,9 @@ def _flags(args, kv, base=0):
 
 
 def _pool(kv, torch, s, host_bytes, **kw):
+    import os
+    if "KVSWAP_PACK_VARIANT" in os.environ:  # development aid: force a kernel variant
+        kw["pack_variant"] = int(os.environ["KVSWAP_PACK_VARIANT"])
     gpu = torch.empty(s.R * s.n_blocks, dtype=torch.uint8, device="cuda:0")
     pool = kv.KVPool(n_layers=s.n_layers, n_kv_heads=s.n_kv_heads, head_dim=s.head_dim,
                      block_size=s.block_size, elt_bytes=s.elt_bytes, n_gpu_blocks=s.n_blocks,

@@ -96,10 +96,9 @@ typedef struct {
                                increment (Section 3.3 adjacent preallocation); <0 = default 32 */
   int32_t gather_grid;      /* workgroups per launch of the persistent pack variant; 0 = default */
   int32_t tile_unroll;      /* 16-byte vectors per lane per tile (1,2,4,8); 0 = from chunk size */
-  int32_t pack_variant;     /* 0 = one tile per workgroup, 3-D grid, 1024 or 256 lanes by chunk size
-                               (default, fastest measured); 1 = persistent grid-stride workgroups
-                               with the block table in LDS; 2 / 3 = tile kernel forced to 256 /
-                               1024 lanes */
+  int32_t pack_variant;     /* 0 = one tile per workgroup, 3-D grid, 256 lanes (default); 1 = persistent
+                               grid-stride workgroups with the block table in LDS; 2 = same as 0;
+                               3 = tile kernel with 1024 lanes */
   int32_t mapped_in_grid;   /* workgroups of the mapped swap-in kernel; 0 = default 64 */
   int32_t reserved;
 } kv_pool_config_t;

@@ -42,7 +42,7 @@ struct KvMappedArgs {
 hipError_t kv_launch_mapped_scatter(const KvMappedArgs& a, int grid, hipStream_t stream,
                                     hipEvent_t start, hipEvent_t stop);
 
-#define KV_PACK_TILE 0        // one tile per workgroup, 3-D grid, workgroup size by chunk (default)
+#define KV_PACK_TILE 0        // one tile per workgroup, 3-D grid, 256 lanes (default)
 #define KV_PACK_PERSISTENT 1  // grid-stride loop, block table staged in LDS, 256 lanes
 #define KV_PACK_TILE_256 2    // tile kernel, 256 lanes
 #define KV_PACK_TILE_1024 3   // tile kernel, 1024 lanes

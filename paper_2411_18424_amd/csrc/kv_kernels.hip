@@ -140,14 +140,13 @@ __global__ __launch_bounds__(KV_WG) void kv_linear_copy_kernel(u32x4* __restrict
   if (i < n_vecs) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
-// Workgroup size of the tile kernel.  Measured on MI355X: the gather is fastest with 256 lanes
-// (4 KiB tiles), the scatter a few per cent faster with 1024 lanes (16 KiB tiles) when that
-// divides the chunk.
-static int pick_wg(uint32_t C, int variant, bool scatter) {
-  if (variant == KV_PACK_TILE_256 || variant == KV_PACK_PERSISTENT) return 256;
-  if (variant == KV_PACK_TILE_1024) return 1024;
-  return (scatter && C % (1024u * 16u) == 0) ? 1024 : 256;
-}
+// Workgroup size of the tile kernel: 256 lanes (4 KiB tiles).  Measured on MI355X: alone, the
+// gather is fastest with 256 lanes and the scatter ~2 % faster with 1024 lanes (16 KiB tiles);
+// but beside a GEMM that fills the CUs a 1024-lane workgroup needs 16 free wave slots at once
+// and the scatter drops to half the rate of the 256-lane one (0.6 vs 1.2 TB/s), so 256 lanes
+// are the default for both directions.  64-lane workgroups do better still beside a GEMM
+// (gather 3.4 vs 2.2 TB/s) but lose 12 % alone.
+static int pick_wg(int variant) { return variant == KV_PACK_TILE_1024 ? 1024 : 256; }
 
 int kv_pick_unroll(uint32_t C, int wg) {
   // one vector per lane measured fastest
@@ -163,7 +162,8 @@ struct Shape {
 
 static Shape pick_shape(uint32_t C, int unroll, int variant, bool scatter) {
   Shape s;
-  s.wg = pick_wg(C, variant, scatter);
+  (void)scatter;
+  s.wg = pick_wg(variant);
   s.U = unroll;
   if (s.U != 1 && s.U != 2 && s.U != 4 && s.U != 8) s.U = kv_pick_unroll(C, s.wg);
   if (s.wg == 1024 && s.U > 2) s.U = 2;  // 1024-lane tiles exist for one and two vectors per lane
@@ -230,6 +230,7 @@ hipError_t kv_launch_pack(bool scatter, const KvPackArgs& a_in, int unroll, int 
   KV_CASE(256, 8)
   KV_CASE(1024, 1)
   KV_CASE(1024, 2)
+
 #undef KV_CASE
   return hipErrorInvalidValue;
 }
