@@ -13,7 +13,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libkvswap.so")
-SOURCES = ["kv_kernels.hip", "kvswap.cpp", "kv_manager.cpp"]
+SOURCES = ["kv_kernels.hip", "kv_engine.cpp", "kv_reuse.cpp", "kvswap.cpp", "kv_probe.cpp", "kv_manager.cpp"]
 
 # -packed-fp32-ops is switched off on purpose: packed fp32 forms are not trusted on the
 # target machines.  (The library does no floating point at all, the flag is policy.)

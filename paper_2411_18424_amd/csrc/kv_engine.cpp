@@ -1,0 +1,436 @@
+// Copy engine of the KV-swap library: event pool, completion polling, staging byte rings,
+// pack-kernel launches, host-link copies and their ordering (FastSwitch, arXiv 2411.18424,
+// Section 3.2: asynchronous swapping on side streams, progress recorded with pooled events,
+// conflicts resolved by waiting for exactly the transfer concerned).
+//
+// Swap-out packs first and drains afterwards: all gathers of a call that fit the staging ring
+// run back to back (the request's GPU blocks are reusable after about a millisecond), then
+// the copies drain the ring; only a call larger than the ring interleaves the two.  Swap-in
+// is pipelined piece by piece.
+
+#include "kv_pool.hpp"
+
+namespace kvi {
+
+// ---------------------------------------------------------------- events
+int32_t get_event(kv_pool* p, hipEvent_t* ev) {
+  if (p->plan) {
+    *ev = nullptr;
+    return KV_OK;
+  }
+  if (!p->event_pool.empty()) {
+    *ev = p->event_pool.back();
+    p->event_pool.pop_back();
+    return KV_OK;
+  }
+  HIP_TRY(hipEventCreateWithFlags(ev, hipEventDisableTiming));
+  return KV_OK;
+}
+
+int32_t get_timing_event(kv_pool* p, hipEvent_t* ev) {
+  if (!p->timing_pool.empty()) {
+    *ev = p->timing_pool.back();
+    p->timing_pool.pop_back();
+    return KV_OK;
+  }
+  HIP_TRY(hipEventCreate(ev));
+  return KV_OK;
+}
+
+void put_event(kv_pool* p, hipEvent_t ev) {
+  if (ev) p->event_pool.push_back(ev);
+}
+
+// Polls completion of the oldest ops; recycles their events.  Ops of one direction finish
+// in issue order (their kernels share one stream), so polling stops at the first unfinished.
+void reap(kv_pool* p) {
+  if (p->plan) {
+    for (auto& o : p->ops_out) o->packed_done = o->all_done = true;
+    for (auto& o : p->ops_in) o->all_done = true;
+    p->pack_done_seq = p->out_seq;
+    p->scat_done_seq = p->in_seq;
+    p->ops_out.clear();
+    p->ops_in.clear();
+    p->ring_out.live.clear();
+    p->ring_in.live.clear();
+    p->alloc.reap(p->pack_done_seq);
+    return;
+  }
+  for (auto& o : p->ops_out) {
+    if (o->packed_done) continue;
+    if (hipEventQuery(o->packed) != hipSuccess) break;
+    o->packed_done = true;
+    p->pack_done_seq = o->seq;
+  }
+  while (!p->ops_out.empty()) {
+    Op& o = *p->ops_out.front();
+    if (!o.packed_done || hipEventQuery(o.done) != hipSuccess) break;
+    o.all_done = true;
+    put_event(p, o.packed);
+    put_event(p, o.done);
+    o.packed = o.done = nullptr;
+    for (hipEvent_t e : o.aux) put_event(p, e);
+    o.aux.clear();
+    p->ops_out.pop_front();
+  }
+  while (!p->ops_in.empty()) {
+    Op& o = *p->ops_in.front();
+    if (hipEventQuery(o.done) != hipSuccess) break;
+    o.all_done = true;
+    p->scat_done_seq = o.seq;
+    put_event(p, o.done);
+    o.done = nullptr;
+    for (hipEvent_t e : o.aux) put_event(p, e);
+    o.aux.clear();
+    p->ops_in.pop_front();
+  }
+  for (ByteRing* r : {&p->ring_out, &p->ring_in}) {
+    while (!r->live.empty()) {
+      Region& f = r->live.front();
+      if (!f.recorded || hipEventQuery(f.freed) != hipSuccess) break;
+      put_event(p, f.freed);
+      r->live.pop_front();
+    }
+  }
+  p->alloc.reap(p->pack_done_seq);
+}
+
+Op* find_op(std::deque<OpRef>& dq, uint64_t seq) {
+  if (dq.empty() || seq < dq.front()->seq) return nullptr;
+  size_t i = (size_t)(seq - dq.front()->seq);
+  return i < dq.size() ? dq[i].get() : nullptr;
+}
+
+// Host wait for one op (lock held by caller; short waits only on rare paths).
+int32_t host_wait_op(kv_pool* p, const OpRef& op) {
+  if (!op || op->all_done || p->plan) return KV_OK;
+  if (op->done) HIP_TRY(hipEventSynchronize(op->done));
+  reap(p);
+  return KV_OK;
+}
+
+// ---------------------------------------------------------------- engine
+int32_t stream_wait(kv_pool* p, hipStream_t s, hipEvent_t ev) {
+  if (p->plan || !ev) return KV_OK;
+  HIP_TRY(hipStreamWaitEvent(s, ev, 0));
+  return KV_OK;
+}
+
+int32_t record(kv_pool* p, hipEvent_t ev, hipStream_t s) {
+  if (p->plan || !ev) return KV_OK;
+  HIP_TRY(hipEventRecord(ev, s));
+  return KV_OK;
+}
+
+int32_t launch_pack(kv_pool* p, bool scatter, char* staging, const Move* mv, int64_t m) {
+  hipStream_t s = scatter ? p->s_scat : p->s_pack;
+  (scatter ? p->st.scatter_launches : p->st.gather_launches)++;
+  if (p->plan) return KV_OK;
+  KvPackArgs a;
+  a.pool = p->gpu;
+  a.staging = staging;
+  a.plane_stride = p->N * p->C;
+  a.C = (uint32_t)p->C;
+  a.P = (uint32_t)p->P;
+  a.m = (uint32_t)m;
+  a.tiles_per_chunk = a.n_tiles = a.pad = 0;
+  for (int64_t i = 0; i < m; ++i) a.table[i] = mv[i].phys;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  if (p->profile) {
+    int32_t rc = get_timing_event(p, &e0);
+    if (rc) return rc;
+    rc = get_timing_event(p, &e1);
+    if (rc) return rc;
+    p->prof.push_back({scatter ? 1 : 0, m * p->R, e0, e1});
+  }
+  HIP_TRY(kv_launch_pack(scatter, a, p->unroll, p->variant, p->grid, s, e0, e1));
+  return KV_OK;
+}
+
+// Copies of one ring slot: one copy per maximal run of moves whose host records are
+// adjacent, each cut into pieces of at most copy_chunk bytes.
+int32_t issue_copies(kv_pool* p, bool to_host, char* slot, const Move* mv, int64_t m) {
+  hipStream_t s = to_host ? p->s_d2h : p->s_h2d;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  if (p->profile && !p->plan) {
+    int32_t rc = get_timing_event(p, &e0);
+    if (rc) return rc;
+    rc = get_timing_event(p, &e1);
+    if (rc) return rc;
+    p->prof.push_back({to_host ? 2 : 3, m * p->R, e0, e1});
+    HIP_TRY(hipEventRecord(e0, s));
+  }
+  int64_t i = 0;
+  while (i < m) {
+    int64_t j = i;
+    while (j + 1 < m && mv[j + 1].host_off == mv[j].host_off + p->R) ++j;
+    int64_t bytes = (j - i + 1) * p->R;
+    char* h = p->host + mv[i].host_off;
+    char* d = slot + i * p->R;
+    for (int64_t o = 0; o < bytes; o += p->copy_chunk) {
+      int64_t nb = std::min(p->copy_chunk, bytes - o);
+      (to_host ? p->st.d2h_copies : p->st.h2d_copies)++;
+      if (p->plan) continue;
+      if (to_host)
+        HIP_TRY(hipMemcpyAsync(h + o, d + o, (size_t)nb, hipMemcpyDeviceToHost, s));
+      else
+        HIP_TRY(hipMemcpyAsync(d + o, h + o, (size_t)nb, hipMemcpyHostToDevice, s));
+    }
+    i = j + 1;
+  }
+  if (e1) HIP_TRY(hipEventRecord(e1, s));
+  return KV_OK;
+}
+
+int32_t order_after_compute(kv_pool* p, hipStream_t s) {
+  if (!p->order_compute || p->plan) return KV_OK;
+  HIP_TRY(hipEventRecord(p->ev_compute, p->compute));
+  HIP_TRY(hipStreamWaitEvent(s, p->ev_compute, 0));
+  return KV_OK;
+}
+
+// Claims `len` bytes at the ring head for op `op_seq`.  Every live region the claim
+// overlaps (and every older one) must have been released by its consumer first: the
+// producer stream is made to wait for it on the device.  `flush` is called before waiting
+// on a region of the same op whose consumer work has not been issued yet.
+template <class Flush>
+int32_t ring_claim(kv_pool* p, ByteRing* r, int64_t len, uint64_t op_seq, hipStream_t producer,
+                   Flush&& flush, Region** out) {
+  int32_t rc;
+  auto evict = [&](int64_t lo, int64_t hi) -> int32_t {
+    int last = -1;
+    for (int i = 0; i < (int)r->live.size(); ++i)
+      if (r->live[(size_t)i].off < hi && lo < r->live[(size_t)i].off + r->live[(size_t)i].len) last = i;
+    for (int i = 0; i <= last; ++i) {
+      if (!r->live.front().recorded) {
+        if (r->live.front().op_seq != op_seq) return fail(KV_EBUSY, "staging region of another call is still open");
+        if ((rc = flush())) return rc;
+      }
+      Region f = r->live.front();
+      r->live.pop_front();
+      if ((rc = stream_wait(p, producer, f.freed))) return rc;
+      put_event(p, f.freed);
+    }
+    return KV_OK;
+  };
+  if (r->head + len > r->cap) {  // the tail is too short: skip it and start over at 0
+    if ((rc = evict(r->head, r->cap))) return rc;
+    r->head = 0;
+  }
+  if ((rc = evict(r->head, r->head + len))) return rc;
+  Region g;
+  g.off = r->head;
+  g.len = len;
+  g.op_seq = op_seq;
+  if ((rc = get_event(p, &g.freed))) return rc;
+  r->head += len;
+  r->live.push_back(g);
+  *out = &r->live.back();
+  return KV_OK;
+}
+
+// Swap-out of a move list: gather pieces into the staging ring, then drain them to the host.
+// pre: events the first gather must wait for.
+int32_t enqueue_out(kv_pool* p, const std::vector<Move>& mv, const std::vector<hipEvent_t>& pre,
+                    const OpRef& op) {
+  int32_t rc;
+  if ((rc = order_after_compute(p, p->s_pack))) return rc;
+  for (hipEvent_t e : pre)
+    if ((rc = stream_wait(p, p->s_pack, e))) return rc;
+  ByteRing& r = p->ring_out;
+  const int64_t m = (int64_t)mv.size();
+  struct Pending {
+    int64_t first, count, off;
+  };
+  std::vector<Pending> pending;  // gathered, copies not issued yet
+  auto flush = [&]() -> int32_t {
+    if (pending.empty()) return KV_OK;
+    int32_t rc2;
+    hipEvent_t ready;
+    if ((rc2 = get_event(p, &ready))) return rc2;
+    if (ready) op->aux.push_back(ready);
+    if ((rc2 = record(p, ready, p->s_pack))) return rc2;
+    if ((rc2 = stream_wait(p, p->s_d2h, ready))) return rc2;
+    for (const Pending& q : pending) {
+      if ((rc2 = issue_copies(p, true, r.base + q.off, &mv[(size_t)q.first], q.count))) return rc2;
+      for (Region& g : r.live)
+        if (g.off == q.off && g.op_seq == op->seq && !g.recorded) {
+          if ((rc2 = record(p, g.freed, p->s_d2h))) return rc2;
+          g.recorded = true;
+        }
+    }
+    pending.clear();
+    return KV_OK;
+  };
+  for (int64_t i = 0; i < m; i += r.piece_blocks) {
+    const int64_t mp = std::min(r.piece_blocks, m - i);
+    Region* g;
+    if ((rc = ring_claim(p, &r, mp * p->R, op->seq, p->s_pack, flush, &g))) return rc;
+    const int64_t off = g->off;
+    for (int64_t k = 0; k < mp; k += p->launch_blocks) {
+      int64_t ml = std::min<int64_t>(p->launch_blocks, mp - k);
+      if ((rc = launch_pack(p, false, r.base + off + k * p->R, &mv[(size_t)(i + k)], ml))) return rc;
+    }
+    pending.push_back({i, mp, off});
+  }
+  if ((rc = record(p, op->packed, p->s_pack))) return rc;
+  if ((rc = flush())) return rc;
+  if (m == 0 && (rc = stream_wait(p, p->s_d2h, op->packed))) return rc;
+  if ((rc = record(p, op->done, p->s_d2h))) return rc;
+  p->st.bytes_out += m * p->R;
+  p->st.blocks_out += m;
+  return KV_OK;
+}
+
+// Swap-in of a move list: copy host records into ring pieces, scatter each piece.
+// pre_copy: events the first host-to-device copy waits for (the image's last writer);
+// pre_scat: events the first scatter waits for (gathers still reading the target blocks).
+int32_t enqueue_in(kv_pool* p, const std::vector<Move>& mv, const std::vector<hipEvent_t>& pre_copy,
+                   const std::vector<hipEvent_t>& pre_scat, const OpRef& op) {
+  int32_t rc;
+  for (hipEvent_t e : pre_copy)
+    if ((rc = stream_wait(p, p->s_h2d, e))) return rc;
+  if ((rc = order_after_compute(p, p->s_scat))) return rc;
+  for (hipEvent_t e : pre_scat)
+    if ((rc = stream_wait(p, p->s_scat, e))) return rc;
+  ByteRing& r = p->ring_in;
+  const int64_t m = (int64_t)mv.size();
+  auto no_flush = []() -> int32_t { return KV_OK; };  // every region is closed before the next claim
+  for (int64_t i = 0; i < m; i += r.piece_blocks) {
+    const int64_t mp = std::min(r.piece_blocks, m - i);
+    Region* g;
+    if ((rc = ring_claim(p, &r, mp * p->R, op->seq, p->s_h2d, no_flush, &g))) return rc;
+    char* sb = r.base + g->off;
+    if ((rc = issue_copies(p, false, sb, &mv[(size_t)i], mp))) return rc;
+    hipEvent_t ready;
+    if ((rc = get_event(p, &ready))) return rc;
+    if (ready) op->aux.push_back(ready);
+    if ((rc = record(p, ready, p->s_h2d))) return rc;
+    if ((rc = stream_wait(p, p->s_scat, ready))) return rc;
+    for (int64_t k = 0; k < mp; k += p->launch_blocks) {
+      int64_t ml = std::min<int64_t>(p->launch_blocks, mp - k);
+      if ((rc = launch_pack(p, true, sb + k * p->R, &mv[(size_t)(i + k)], ml))) return rc;
+    }
+    if ((rc = record(p, g->freed, p->s_scat))) return rc;
+    g->recorded = true;
+  }
+  if (m == 0) {
+    // nothing moved: completion still follows the image's last writer
+    for (hipEvent_t e : pre_copy)
+      if ((rc = stream_wait(p, p->s_scat, e))) return rc;
+  }
+  if ((rc = record(p, op->done, p->s_scat))) return rc;
+  p->st.bytes_in += m * p->R;
+  p->st.blocks_in += m;
+  return KV_OK;
+}
+
+// Comparison path: the paper's own transfer scheme (Section 3.1, one copy per contiguous
+// block group) on this pool layout, without a pack kernel.  A run of r physically adjacent
+// blocks is r*C contiguous bytes in each of the P planes of the pool and r records R bytes
+// apart in the host image, so it takes one 2-D copy per (run, plane); per_block cuts every
+// run into single blocks (one copy per block and plane, the per-block baseline of Section
+// 2.2).  Everything runs on the copy stream; the blocks stay busy until the transfer ends.
+int32_t enqueue_direct(kv_pool* p, bool to_host, const std::vector<Move>& mv,
+                       const std::vector<hipEvent_t>& pre, const OpRef& op, bool per_block) {
+  int32_t rc;
+  hipStream_t s = to_host ? p->s_d2h : p->s_h2d;
+  if ((rc = order_after_compute(p, s))) return rc;
+  for (hipEvent_t e : pre)
+    if ((rc = stream_wait(p, s, e))) return rc;
+  const int64_t m = (int64_t)mv.size();
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  if (p->profile && !p->plan && m > 0) {
+    if ((rc = get_timing_event(p, &e0))) return rc;
+    if ((rc = get_timing_event(p, &e1))) return rc;
+    p->prof.push_back({to_host ? 2 : 3, m * p->R, e0, e1});
+    HIP_TRY(hipEventRecord(e0, s));
+  }
+  int64_t i = 0;
+  while (i < m) {
+    int64_t j = i;
+    if (!per_block)
+      while (j + 1 < m && mv[(size_t)j + 1].phys == mv[(size_t)j].phys + 1 &&
+             mv[(size_t)j + 1].host_off == mv[(size_t)j].host_off + p->R)
+        ++j;
+    const int64_t r = j - i + 1;
+    for (int32_t pl = 0; pl < p->P; ++pl) {
+      char* h = p->host + mv[(size_t)i].host_off + (int64_t)pl * p->C;
+      char* d = p->gpu + ((int64_t)pl * p->N + mv[(size_t)i].phys) * p->C;
+      (to_host ? p->st.d2h_copies : p->st.h2d_copies)++;
+      if (p->plan) continue;
+      if (to_host)
+        HIP_TRY(hipMemcpy2DAsync(h, (size_t)p->R, d, (size_t)p->C, (size_t)p->C, (size_t)r,
+                                 hipMemcpyDeviceToHost, s));
+      else
+        HIP_TRY(hipMemcpy2DAsync(d, (size_t)p->C, h, (size_t)p->R, (size_t)p->C, (size_t)r,
+                                 hipMemcpyHostToDevice, s));
+    }
+    i = j + 1;
+  }
+  if (e1) HIP_TRY(hipEventRecord(e1, s));
+  if (to_host && (rc = record(p, op->packed, s))) return rc;
+  if ((rc = record(p, op->done, s))) return rc;
+  (to_host ? p->st.bytes_out : p->st.bytes_in) += m * p->R;
+  (to_host ? p->st.blocks_out : p->st.blocks_in) += m;
+  return KV_OK;
+}
+
+// Swap-in straight from the pinned image (KV_FLAG_MAPPED_SWAP_IN): one persistent kernel per
+// 440 blocks reads the host records over the link and writes the pool; no staging, no copy
+// engine, no per-run copies - fragmented images and partial swap-ins cost the same as
+// contiguous ones.
+int32_t enqueue_in_mapped(kv_pool* p, const std::vector<Move>& mv, const std::vector<hipEvent_t>& pre,
+                          const OpRef& op) {
+  int32_t rc;
+  hipStream_t s = p->s_scat;
+  if ((rc = order_after_compute(p, s))) return rc;
+  for (hipEvent_t e : pre)
+    if ((rc = stream_wait(p, s, e))) return rc;
+  const int64_t m = (int64_t)mv.size();
+  for (int64_t i = 0; i < m; i += KV_MAX_MAPPED_BLOCKS) {
+    const int64_t ml = std::min<int64_t>(KV_MAX_MAPPED_BLOCKS, m - i);
+    p->st.scatter_launches++;
+    if (p->plan) continue;
+    KvMappedArgs a;
+    a.pool = p->gpu;
+    a.host = p->host_dev;
+    a.plane_stride = p->N * p->C;
+    a.R = p->R;
+    a.C = (uint32_t)p->C;
+    a.P = (uint32_t)p->P;
+    a.m = (uint32_t)ml;
+    a.tiles_per_chunk = a.n_tiles = a.pad = 0;
+    for (int64_t k = 0; k < ml; ++k) {
+      a.phys[k] = mv[(size_t)(i + k)].phys;
+      a.rec[k] = (uint32_t)(mv[(size_t)(i + k)].host_off / p->R);
+    }
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (p->profile) {
+      if ((rc = get_timing_event(p, &e0))) return rc;
+      if ((rc = get_timing_event(p, &e1))) return rc;
+      p->prof.push_back({4, ml * p->R, e0, e1});
+    }
+    HIP_TRY(kv_launch_mapped_scatter(a, p->mapped_grid, s, e0, e1));
+  }
+  if ((rc = record(p, op->done, s))) return rc;
+  p->st.bytes_in += m * p->R;
+  p->st.blocks_in += m;
+  return KV_OK;
+}
+
+int32_t new_op(kv_pool* p, bool is_out, OpRef* out) {
+  auto op = std::make_shared<Op>();
+  op->is_out = is_out;
+  int32_t rc;
+  if (is_out) {
+    if ((rc = get_event(p, &op->packed))) return rc;
+  }
+  if ((rc = get_event(p, &op->done))) return rc;
+  op->seq = is_out ? ++p->out_seq : ++p->in_seq;
+  (is_out ? p->ops_out : p->ops_in).push_back(op);
+  *out = op;
+  return KV_OK;
+}
+
+}  // namespace kvi
