@@ -132,11 +132,11 @@ class BlockGroupAllocator {
   int64_t n_draining() const { return n_draining_; }
   int64_t largest_run() const { return free_.largest(); }
 
-  // Allocates n ids into out (appended), fewest runs first.  Caller has checked n <= n_free().
-  // Returns the number of maximal runs used.
-  int32_t alloc(int64_t n, int64_t min_run, std::vector<int32_t>* out) {
-    (void)min_run;  // largest-first already uses short runs only when nothing longer is free
-    int32_t runs = 0;
+  // Allocates n ids into out (which must be empty), fewest runs first: the best-fitting free
+  // run if one holds the rest, else the largest run, repeatedly - so runs shorter than any
+  // wanted minimum are used only when nothing longer is free.  Caller has checked
+  // n <= n_free().  Returns the number of maximal runs of consecutive ids in out.
+  int32_t alloc(int64_t n, std::vector<int32_t>* out) {
     int64_t start;
     while (n > 0) {
       int64_t got;
@@ -150,9 +150,8 @@ class BlockGroupAllocator {
         out->push_back((int32_t)(start + i));
       }
       n -= got;
-      ++runs;
     }
-    return count_runs(*out, runs);
+    return count_runs(*out);
   }
 
   // One contiguous run of up to `want` blocks: the best-fitting free run if one holds `want`,
@@ -253,9 +252,8 @@ class BlockGroupAllocator {
     uint64_t seq;
     int64_t start, len;
   };
-  static int32_t count_runs(const std::vector<int32_t>& ids, int32_t fallback) {
+  static int32_t count_runs(const std::vector<int32_t>& ids) {
     if (ids.empty()) return 0;
-    (void)fallback;
     int32_t r = 1;
     for (size_t i = 1; i < ids.size(); ++i)
       if (ids[i] != ids[i - 1] + 1) ++r;

@@ -235,7 +235,8 @@ int32_t alloc_block_group(kv_pool_t* p, int64_t req, int32_t n_blocks, int32_t m
   }
   std::vector<int32_t> ids;
   ids.reserve((size_t)n_blocks);
-  int32_t runs = p->alloc.alloc(n_blocks, min_run, &ids);
+  (void)min_run;  // largest-first allocation already honours it (see BlockGroupAllocator::alloc)
+  int32_t runs = p->alloc.alloc(n_blocks, &ids);
   if (n_blocks > 0) memcpy(out_blocks, ids.data(), sizeof(int32_t) * (size_t)n_blocks);
   if (out_n_runs) *out_n_runs = runs;
   return KV_OK;
