@@ -120,8 +120,11 @@ int32_t kv_pool_destroy(kv_pool_t* pool);
 int32_t alloc_block_group(kv_pool_t* pool, int64_t req, int32_t n_blocks, int32_t min_run,
                           int32_t* out_blocks, int32_t* out_n_runs);
 /* Returns blocks to the free lists (adjacent free runs merge).  Blocks named by a swap_out
- * whose gather has not finished stay unavailable until it has.  KV_EINVAL if any block is
- * out of range, repeated, or not currently allocated (then nothing is freed). */
+ * whose gather has not finished stay unavailable until it has.  Blocks a swap_in is still
+ * writing are the caller's to order: free them after kv_wait, or after kv_stream_wait has put
+ * the stream that touches them next behind the swap-in (the library's own later swaps into
+ * them are ordered by it).  KV_EINVAL if any block is out of range, repeated, or not
+ * currently allocated (then nothing is freed). */
 int32_t free_block_group(kv_pool_t* pool, int64_t req, const int32_t* blocks, int32_t n_blocks);
 /* Number of blocks currently free (including those waiting for a gather to finish). */
 int32_t kv_free_blocks(kv_pool_t* pool, int64_t* out_free, int64_t* out_largest_run);
@@ -189,7 +192,8 @@ int32_t swap_out_direct(kv_pool_t* pool, int64_t req, const int32_t* block_table
 int32_t swap_in_direct(kv_pool_t* pool, int64_t req, const int32_t* new_block_table, int32_t n_blocks,
                        int32_t per_block);
 
-/* Completion (Algorithm 1, step 1: IsCompleted / Synchronize). */
+/* Completion (Algorithm 1, step 1: IsCompleted / Synchronize).  KV_ENOENT for a request the
+ * library does not know: one never swapped, or whose host copy was released. */
 int32_t kv_wait(kv_pool_t* pool, int64_t req);                /* blocks until req's last op is done */
 int32_t kv_query(kv_pool_t* pool, int64_t req, int32_t* done);/* non-blocking; *done = 0/1 */
 int32_t kv_wait_packed(kv_pool_t* pool, int64_t req);         /* until the last swap-out's gather has
