@@ -192,6 +192,22 @@ int32_t swap_out_direct(kv_pool_t* pool, int64_t req, const int32_t* block_table
 int32_t swap_in_direct(kv_pool_t* pool, int64_t req, const int32_t* new_block_table, int32_t n_blocks,
                        int32_t per_block);
 
+/* Layer-wise swap-in: the alternative Section 2.2 (Challenge #2) discusses, layer-wise
+ * asynchronous swapping as in earlier systems, built on this path for comparison.  Same result,
+ * validation and reuse-map effects as swap_in_delta (resident_mask may be NULL: move
+ * everything; out_n_moved may be NULL), but the KV arrives in steps of layers_per_step layers
+ * (1 .. n_layers), lowest layers first: per step one 2-D host-to-device copy per run of
+ * adjacent host records (the K and V planes of consecutive layers are one contiguous slice of
+ * each record) and one scatter over that plane range.  kv_stream_wait_layer makes a
+ * hipStream_t wait on the device, kv_wait_layer the calling thread, until the step that holds
+ * `layer` has landed, so attention over layer l can start while the layers above it are still
+ * on the link.  For a request whose last op is not a layer-wise swap-in both wait for that
+ * whole op.  KV_EINVAL for a layer outside [0, n_layers). */
+int32_t swap_in_layerwise(kv_pool_t* pool, int64_t req, const int32_t* new_block_table, int32_t n_blocks,
+                          const uint8_t* resident_mask, int32_t layers_per_step, int32_t* out_n_moved);
+int32_t kv_stream_wait_layer(kv_pool_t* pool, int64_t req, int32_t layer, void* stream);
+int32_t kv_wait_layer(kv_pool_t* pool, int64_t req, int32_t layer);
+
 /* Completion (Algorithm 1, step 1: IsCompleted / Synchronize).  KV_ENOENT for a request the
  * library does not know: one never swapped, or whose host copy was released. */
 int32_t kv_wait(kv_pool_t* pool, int64_t req);                /* blocks until req's last op is done */

@@ -82,6 +82,8 @@ void reap(kv_pool* p) {
     o.done = nullptr;
     for (hipEvent_t e : o.aux) put_event(p, e);
     o.aux.clear();
+    for (hipEvent_t e : o.layer_ev) put_event(p, e);
+    o.layer_ev.clear();
     p->ops_in.pop_front();
   }
   for (ByteRing* r : {&p->ring_out, &p->ring_in}) {
@@ -122,16 +124,20 @@ int32_t record(kv_pool* p, hipEvent_t ev, hipStream_t s) {
   return KV_OK;
 }
 
-int32_t launch_pack(kv_pool* p, bool scatter, char* staging, const Move* mv, int64_t m) {
+// One pack launch over m blocks and the planes [p0, p0 + np) (np = 0: all planes); staging
+// holds [m][np][C].
+int32_t launch_pack(kv_pool* p, bool scatter, char* staging, const Move* mv, int64_t m,
+                    int32_t p0 = 0, int32_t np = 0) {
   hipStream_t s = scatter ? p->s_scat : p->s_pack;
   (scatter ? p->st.scatter_launches : p->st.gather_launches)++;
   if (p->plan) return KV_OK;
+  if (np == 0) np = p->P;
   KvPackArgs a;
-  a.pool = p->gpu;
+  a.pool = p->gpu + (int64_t)p0 * p->N * p->C;
   a.staging = staging;
   a.plane_stride = p->N * p->C;
   a.C = (uint32_t)p->C;
-  a.P = (uint32_t)p->P;
+  a.P = (uint32_t)np;
   a.m = (uint32_t)m;
   a.tiles_per_chunk = a.n_tiles = a.pad = 0;
   for (int64_t i = 0; i < m; ++i) a.table[i] = mv[i].phys;
@@ -141,7 +147,7 @@ int32_t launch_pack(kv_pool* p, bool scatter, char* staging, const Move* mv, int
     if (rc) return rc;
     rc = get_timing_event(p, &e1);
     if (rc) return rc;
-    p->prof.push_back({scatter ? 1 : 0, m * p->R, e0, e1});
+    p->prof.push_back({scatter ? 1 : 0, m * np * p->C, e0, e1});
   }
   HIP_TRY(kv_launch_pack(scatter, a, p->unroll, p->variant, p->grid, s, e0, e1));
   return KV_OK;
@@ -318,6 +324,83 @@ int32_t enqueue_in(kv_pool* p, const std::vector<Move>& mv, const std::vector<hi
     // nothing moved: completion still follows the image's last writer
     for (hipEvent_t e : pre_copy)
       if ((rc = stream_wait(p, p->s_scat, e))) return rc;
+  }
+  if ((rc = record(p, op->done, p->s_scat))) return rc;
+  p->st.bytes_in += m * p->R;
+  p->st.blocks_in += m;
+  return KV_OK;
+}
+
+// Layer-wise swap-in (the layer-wise asynchronous swapping of earlier systems that Section
+// 2.2, Challenge #2, discusses): the request's KV arrives in steps of `step` layers, lowest
+// layers first, and an event per step lets the consumer start on layer l while the layers
+// above it are still on the link.  In the block-major host image the K and V planes of
+// `step` consecutive layers are one contiguous slice of 2*step*C bytes in every record, so a
+// step is one 2-D copy per run of adjacent records (rows = blocks, R bytes apart on the
+// host, packed in staging) followed by a scatter over that plane range.
+int32_t enqueue_in_layers(kv_pool* p, const std::vector<Move>& mv, const std::vector<hipEvent_t>& pre_copy,
+                          const std::vector<hipEvent_t>& pre_scat, const OpRef& op, int32_t step) {
+  int32_t rc;
+  for (hipEvent_t e : pre_copy)
+    if ((rc = stream_wait(p, p->s_h2d, e))) return rc;
+  if ((rc = order_after_compute(p, p->s_scat))) return rc;
+  for (hipEvent_t e : pre_scat)
+    if ((rc = stream_wait(p, p->s_scat, e))) return rc;
+  if (mv.empty())
+    for (hipEvent_t e : pre_copy)
+      if ((rc = stream_wait(p, p->s_scat, e))) return rc;
+  ByteRing& r = p->ring_in;
+  const int64_t m = (int64_t)mv.size();
+  const int32_t L = p->P / 2;
+  auto no_flush = []() -> int32_t { return KV_OK; };
+  op->layer_step = step;
+  for (int32_t l0 = 0; l0 < L; l0 += step) {
+    const int32_t np = 2 * std::min(step, L - l0), p0 = 2 * l0;
+    const int64_t slice = (int64_t)np * p->C;
+    const int64_t piece_blocks = std::max<int64_t>(1, r.piece_blocks * p->R / slice);
+    const int64_t rows_per_copy = std::max<int64_t>(1, p->copy_chunk / slice);
+    for (int64_t i = 0; i < m; i += piece_blocks) {
+      const int64_t mp = std::min(piece_blocks, m - i);
+      Region* g;
+      if ((rc = ring_claim(p, &r, mp * slice, op->seq, p->s_h2d, no_flush, &g))) return rc;
+      char* sb = r.base + g->off;
+      hipEvent_t e0 = nullptr, e1 = nullptr;
+      if (p->profile && !p->plan) {
+        if ((rc = get_timing_event(p, &e0))) return rc;
+        if ((rc = get_timing_event(p, &e1))) return rc;
+        p->prof.push_back({3, mp * slice, e0, e1});
+        HIP_TRY(hipEventRecord(e0, p->s_h2d));
+      }
+      int64_t a = 0;
+      while (a < mp) {
+        int64_t b = a;
+        while (b + 1 < mp && b + 1 - a < rows_per_copy &&
+               mv[(size_t)(i + b + 1)].host_off == mv[(size_t)(i + b)].host_off + p->R)
+          ++b;
+        p->st.h2d_copies++;
+        if (!p->plan)
+          HIP_TRY(hipMemcpy2DAsync(sb + a * slice, (size_t)slice,
+                                   p->host + mv[(size_t)(i + a)].host_off + (int64_t)p0 * p->C, (size_t)p->R,
+                                   (size_t)slice, (size_t)(b - a + 1), hipMemcpyHostToDevice, p->s_h2d));
+        a = b + 1;
+      }
+      if (e1) HIP_TRY(hipEventRecord(e1, p->s_h2d));
+      hipEvent_t ready;
+      if ((rc = get_event(p, &ready))) return rc;
+      if (ready) op->aux.push_back(ready);
+      if ((rc = record(p, ready, p->s_h2d))) return rc;
+      if ((rc = stream_wait(p, p->s_scat, ready))) return rc;
+      for (int64_t k = 0; k < mp; k += p->launch_blocks) {
+        int64_t ml = std::min<int64_t>(p->launch_blocks, mp - k);
+        if ((rc = launch_pack(p, true, sb + k * slice, &mv[(size_t)(i + k)], ml, p0, np))) return rc;
+      }
+      if ((rc = record(p, g->freed, p->s_scat))) return rc;
+      g->recorded = true;
+    }
+    hipEvent_t landed;
+    if ((rc = get_event(p, &landed))) return rc;
+    op->layer_ev.push_back(landed);
+    if ((rc = record(p, landed, p->s_scat))) return rc;
   }
   if ((rc = record(p, op->done, p->s_scat))) return rc;
   p->st.bytes_in += m * p->R;

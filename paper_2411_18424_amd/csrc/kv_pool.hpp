@@ -39,6 +39,9 @@ struct Op {
   hipEvent_t done = nullptr;    // recorded after the last copy (out) / scatter (in)
   bool packed_done = false, all_done = false;
   std::vector<hipEvent_t> aux;  // hand-off events of this op, recycled when it is done
+  std::vector<hipEvent_t> layer_ev;  // layer-wise swap-in: one per step of layer_step layers (null
+                                     // entries in a plan-only pool); recycled when the op is done
+  int32_t layer_step = 0;
 };
 using OpRef = std::shared_ptr<Op>;
 
@@ -181,6 +184,8 @@ int32_t enqueue_out(kv_pool* p, const std::vector<Move>& mv, const std::vector<h
                     const OpRef& op);
 int32_t enqueue_in(kv_pool* p, const std::vector<Move>& mv, const std::vector<hipEvent_t>& pre_copy,
                    const std::vector<hipEvent_t>& pre_scat, const OpRef& op);
+int32_t enqueue_in_layers(kv_pool* p, const std::vector<Move>& mv, const std::vector<hipEvent_t>& pre_copy,
+                          const std::vector<hipEvent_t>& pre_scat, const OpRef& op, int32_t step);
 int32_t enqueue_direct(kv_pool* p, bool to_host, const std::vector<Move>& mv,
                        const std::vector<hipEvent_t>& pre, const OpRef& op, bool per_block);
 int32_t enqueue_in_mapped(kv_pool* p, const std::vector<Move>& mv, const std::vector<hipEvent_t>& pre,
@@ -189,6 +194,7 @@ int32_t enqueue_in_mapped(kv_pool* p, const std::vector<Move>& mv, const std::ve
 // kv_reuse.cpp: validation, host arena and images, moved-set selection (the reuse map)
 void arena_give(kv_pool* p, const std::vector<Extent>& ext);
 int32_t do_swap_out(kv_pool* p, std::vector<OutItem>& items, int32_t* out_n_moved, int direct = 0);
-int32_t do_swap_in(kv_pool* p, std::vector<InItem>& items, int32_t* out_n_moved, int direct = 0);
+int32_t do_swap_in(kv_pool* p, std::vector<InItem>& items, int32_t* out_n_moved, int direct = 0,
+                   int32_t layer_step = 0);
 
 }  // namespace kvi

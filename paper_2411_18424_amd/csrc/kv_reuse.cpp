@@ -279,7 +279,8 @@ int32_t do_swap_out(kv_pool* p, std::vector<OutItem>& items, int32_t* out_n_move
 }
 
 
-int32_t do_swap_in(kv_pool* p, std::vector<InItem>& items, int32_t* out_n_moved, int direct) {
+int32_t do_swap_in(kv_pool* p, std::vector<InItem>& items, int32_t* out_n_moved, int direct,
+                   int32_t layer_step) {
   reap(p);
   int32_t rc;
   ++p->epoch;
@@ -331,6 +332,7 @@ int32_t do_swap_in(kv_pool* p, std::vector<InItem>& items, int32_t* out_n_moved,
     pre_copy.insert(pre_copy.end(), pre_scat.begin(), pre_scat.end());
     return enqueue_direct(p, false, mv, pre_copy, op, direct == 2);
   }
+  if (layer_step > 0) return enqueue_in_layers(p, mv, pre_copy, pre_scat, op, layer_step);
   if (p->mapped_in) {
     pre_copy.insert(pre_copy.end(), pre_scat.begin(), pre_scat.end());
     return enqueue_in_mapped(p, mv, pre_copy, op);

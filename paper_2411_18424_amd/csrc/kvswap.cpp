@@ -379,6 +379,17 @@ int32_t swap_in_delta(kv_pool_t* p, int64_t req, const int32_t* new_block_table,
   return do_swap_in(p, items, out_n_moved);
 }
 
+int32_t swap_in_layerwise(kv_pool_t* p, int64_t req, const int32_t* new_block_table, int32_t n_blocks,
+                          const uint8_t* resident_mask, int32_t layers_per_step, int32_t* out_n_moved) {
+  if (!p) return fail(KV_EINVAL, "null pool");
+  if (layers_per_step < 1 || layers_per_step > p->P / 2)
+    return fail(KV_EINVAL, "layers_per_step %d outside [1, %d]", layers_per_step, p->P / 2);
+  std::lock_guard<std::mutex> g(p->mu);
+  std::vector<InItem> items(1);
+  items[0] = InItem{req, new_block_table, n_blocks, resident_mask};
+  return do_swap_in(p, items, out_n_moved, 0, layers_per_step);
+}
+
 int32_t swap_out_direct(kv_pool_t* p, int64_t req, const int32_t* block_table, int32_t n_blocks,
                         int32_t per_block) {
   if (!p) return fail(KV_EINVAL, "null pool");
@@ -475,6 +486,48 @@ int32_t kv_stream_wait(kv_pool_t* p, int64_t req, void* stream) {
   const OpRef& op = f->second.last;
   if (!op || op->all_done || p->plan) return KV_OK;
   HIP_TRY(hipStreamWaitEvent((hipStream_t)stream, op->done, 0));
+  return KV_OK;
+}
+
+// The event after which layer `layer` of req's last op is on the GPU: the step's own event
+// for a layer-wise swap-in, the op's completion event otherwise.  Null = nothing to wait for.
+static int32_t layer_event(kv_pool* p, int64_t req, int32_t layer, hipEvent_t* ev) {
+  *ev = nullptr;
+  if (layer < 0 || layer >= p->P / 2) return fail(KV_EINVAL, "layer %d outside [0, %d)", layer, p->P / 2);
+  auto f = p->reqs.find(req);
+  if (f == p->reqs.end()) return fail(KV_ENOENT, "unknown request %lld", (long long)req);
+  reap(p);
+  const OpRef& op = f->second.last;
+  if (!op || op->all_done || p->plan) return KV_OK;
+  if (op->layer_step > 0 && !op->layer_ev.empty())
+    *ev = op->layer_ev[(size_t)(layer / op->layer_step)];
+  else
+    *ev = op->done;
+  return KV_OK;
+}
+
+int32_t kv_stream_wait_layer(kv_pool_t* p, int64_t req, int32_t layer, void* stream) {
+  if (!p) return fail(KV_EINVAL, "null pool");
+  std::lock_guard<std::mutex> g(p->mu);
+  hipEvent_t ev;
+  int32_t rc = layer_event(p, req, layer, &ev);
+  if (rc) return rc;
+  if (ev) HIP_TRY(hipStreamWaitEvent((hipStream_t)stream, ev, 0));
+  return KV_OK;
+}
+
+int32_t kv_wait_layer(kv_pool_t* p, int64_t req, int32_t layer) {
+  if (!p) return fail(KV_EINVAL, "null pool");
+  std::unique_lock<std::mutex> lk(p->mu);
+  hipEvent_t ev;
+  int32_t rc = layer_event(p, req, layer, &ev);
+  if (rc) return rc;
+  if (!ev) return KV_OK;
+  // not wait_event_unlocked: reaping here would be premature, the op's later steps still run
+  lk.unlock();
+  hipError_t e = hipEventSynchronize(ev);
+  lk.lock();
+  if (e != hipSuccess) return fail(KV_EHIP, "hipEventSynchronize: %s", hipGetErrorString(e));
   return KV_OK;
 }
 

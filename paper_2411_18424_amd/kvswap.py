@@ -99,6 +99,9 @@ def _load() -> C.CDLL:
         "swap_in_delta": (C.c_int32, [pool_p, C.c_int64, i32p, C.c_int32, u8p, i32p]),
         "swap_out_direct": (C.c_int32, [pool_p, C.c_int64, i32p, C.c_int32, C.c_int32]),
         "swap_in_direct": (C.c_int32, [pool_p, C.c_int64, i32p, C.c_int32, C.c_int32]),
+        "swap_in_layerwise": (C.c_int32, [pool_p, C.c_int64, i32p, C.c_int32, u8p, C.c_int32, i32p]),
+        "kv_stream_wait_layer": (C.c_int32, [pool_p, C.c_int64, C.c_int32, C.c_void_p]),
+        "kv_wait_layer": (C.c_int32, [pool_p, C.c_int64, C.c_int32]),
         "swap_out_batch": (C.c_int32, [pool_p, C.c_int32, i64p, i32p, i32p]),
         "swap_in_batch": (C.c_int32, [pool_p, C.c_int32, i64p, i32p, i32p]),
         "kv_wait": (C.c_int32, [pool_p, C.c_int64]),
@@ -285,6 +288,23 @@ class KVPool:
         n = C.c_int32()
         _check(lib.swap_in_delta(self._h, req, p, a.size, mp, C.byref(n)))
         return n.value
+
+    def swap_in_layerwise(self, req: int, new_block_table, layers_per_step: int, resident_mask=None) -> int:
+        a, p = _i32(new_block_table)
+        mp = None
+        if resident_mask is not None:
+            m, mp = _u8(resident_mask)
+            if m.size != a.size:
+                raise KVError(KV_EINVAL, "resident mask length differs from table length")
+        n = C.c_int32()
+        _check(lib.swap_in_layerwise(self._h, req, p, a.size, mp, layers_per_step, C.byref(n)))
+        return n.value
+
+    def kv_stream_wait_layer(self, req: int, layer: int, stream: int):
+        _check(lib.kv_stream_wait_layer(self._h, req, layer, stream or None))
+
+    def kv_wait_layer(self, req: int, layer: int):
+        _check(lib.kv_wait_layer(self._h, req, layer))
 
     def swap_out_direct(self, req: int, block_table, per_block: bool = False):
         a, p = _i32(block_table)

@@ -217,6 +217,46 @@ def test_plan_counts_copies_and_launches(kv):
     assert st2["d2h_copies"] - st["d2h_copies"] == 3 + 1
 
 
+def test_layerwise_swap_in_plan(kv):
+    """Layer-wise swap-in: per step of layers one 2-D copy per run of adjacent host records
+    (rows cut at copy_chunk_bytes) and one scatter per ring piece; pieces hold more blocks
+    because a step moves only a slice of each record."""
+    shape = synth.TINY  # 2 layers, C = 8 KiB, R = 32 KiB
+    p = plan_pool(kv, shape, host_blocks=256, staging_out_bytes=8 * shape.R,
+                  staging_in_bytes=8 * shape.R, copy_chunk_bytes=3 * shape.R)
+    t = np.arange(10, dtype=np.int32)
+    p.swap_out(0, t)
+    st0 = p.kv_stats()
+    assert p.swap_in_layerwise(0, t[::-1].copy(), 1) == 10
+    st1 = p.kv_stats()
+    # slice = R/2: pieces of 8 blocks (8 + 2), copies of at most 6 rows -> (2 + 1) per step
+    assert st1["h2d_copies"] - st0["h2d_copies"] == 2 * 3
+    assert st1["scatter_launches"] - st0["scatter_launches"] == 2 * 2
+    assert st1["bytes_in"] - st0["bytes_in"] == 10 * shape.R
+    assert p.swap_in_layerwise(0, t, 2) == 10
+    st2 = p.kv_stats()
+    # one step of both layers = the whole record: pieces 4 + 4 + 2, copies of at most 3 rows
+    assert st2["h2d_copies"] - st1["h2d_copies"] == 2 + 2 + 1
+    assert st2["scatter_launches"] - st1["scatter_launches"] == 3
+    res = np.array([1, 0, 0, 1, 1, 1, 0, 1, 1, 1], np.uint8)
+    assert p.swap_in_layerwise(0, t, 1, res) == 3          # j = 1 2 | 6 -> two runs per step
+    st3 = p.kv_stats()
+    assert st3["h2d_copies"] - st2["h2d_copies"] == 2 * 2
+    p.kv_wait_layer(0, 1)
+    p.kv_stream_wait_layer(0, 0, 0)
+    for bad in (0, 3, -1):
+        with pytest.raises(kv.KVError) as ei:
+            p.swap_in_layerwise(0, t, bad)
+        assert ei.value.status == kv.KV_EINVAL
+    with pytest.raises(kv.KVError) as ei:
+        p.kv_wait_layer(0, 2)
+    assert ei.value.status == kv.KV_EINVAL
+    with pytest.raises(kv.KVError) as ei:
+        p.kv_wait_layer(5, 0)
+    assert ei.value.status == kv.KV_ENOENT
+    assert p.kv_stats()["bytes_in"] == st3["bytes_in"]
+
+
 def test_host_images_grow_by_extents_and_give_everything_back(kv):
     """Section 3.3: room behind a new image is reserved for the next turn; when it is used up
     the image continues in a further extent (it is never moved)."""

@@ -537,6 +537,57 @@ def test_mapped_swap_in_reads_the_host_image_directly(harness, L, H, D, B, e, N)
     assert st["h2d_copies"] == 0 and st["bytes_in"] == h.oracle.bytes_in
 
 
+def test_layerwise_swap_in_lands_layer_by_layer(harness):
+    """Layer-wise swap-in (the alternative of Section 2.2, Challenge #2): same bytes as swap_in,
+    and a stream that waits for layer l sees that layer's K and V complete."""
+    import torch
+    shape = synth.KVShape("lw", 6, 4, 64, 16, 2, 160, "bf16")  # C = 8 KiB, R = 96 KiB
+    stream = torch.cuda.Stream()
+    h = harness(shape, cfg=31, host_bytes=64 * MiB, fill="random", host_slack_blocks=2,
+                staging_in_bytes=1 * MiB, copy_chunk_bytes=256 * 1024,
+                flags=4, compute_stream=stream.cuda_stream)  # KV_FLAG_ORDER_COMPUTE
+    rng = synth.rng_for(31)
+    view = h.gpu.view(shape.P, shape.n_blocks, shape.C)
+    n = 37
+    perm = rng.permutation(shape.n_blocks).astype(np.int32)
+    t = perm[:n].copy()
+    # an image in two extents: 30 blocks, a neighbour behind its slack, then 7 more
+    h.pool.swap_out(0, t[:30])
+    h.oracle.swap_out(0, t[:30])
+    h.pool.swap_out(1, perm[100:105].copy())
+    h.oracle.swap_out(1, perm[100:105].copy())
+    dirty = np.zeros(n, np.uint8)
+    assert h.pool.swap_out_delta(0, t, dirty) == 7
+    h.oracle.swap_out_delta(0, t, dirty)
+    assert h.pool.kv_host_len(0) == (n, 2)
+    h.assert_image_equal(0)
+    cursor = 37
+    for step, partial in ((1, False), (2, False), (4, False), (6, False), (3, True)):
+        t2 = perm[cursor:cursor + n].copy()
+        cursor = 37 + (cursor - 37 + n) % 60
+        idx = torch.from_numpy(t2.astype(np.int64)).to(h.dev)
+        with torch.cuda.stream(stream):
+            view[:, idx, :] = 0xEE  # stale bytes, written on the compute stream just before
+        h.oracle.G[:, t2.astype(np.int64), :] = 0xEE
+        res = synth.random_mask(rng, n, 0.4) if partial else None
+        moved = h.pool.swap_in_layerwise(0, t2, step, res)
+        assert moved == len(h.oracle.swap_in(0, t2, resident=res))
+        seen = []
+        for layer in range(shape.n_layers):
+            h.pool.kv_stream_wait_layer(0, layer, stream.cuda_stream)
+            with torch.cuda.stream(stream):
+                seen.append(view[2 * layer:2 * layer + 2, idx, :].clone())
+        h.pool.kv_wait_layer(0, 0)
+        stream.synchronize()
+        for layer, got in enumerate(seen):
+            want = h.oracle.G[2 * layer:2 * layer + 2, t2.astype(np.int64), :]
+            assert np.array_equal(got.cpu().numpy(), want), (step, layer)
+        h.pool.kv_wait(0)
+        h.assert_pool_equal()
+    st = h.pool.kv_stats()
+    assert st["bytes_in"] == h.oracle.bytes_in
+
+
 def test_growing_requests_through_block_groups(harness):
     """Requests grow through the block-group manager, are preempted (swap-out, groups closed
     while the gather may still be reading them) and resumed into whatever groups are free."""
