@@ -233,6 +233,42 @@ def main() -> int:
     all_recs = pool.kv_profile_read()  # every launch and copy of this process
     stats = pool.kv_stats()
     pool.kv_pool_destroy()
+
+    # layer-wise swap-in (the alternative the paper discusses): when does the first step of
+    # layers land, when the last, against whole-request swap-in.  A pool of its own without
+    # per-launch timing events, which would cost more than the steps themselves.
+    lw = {}
+    if args.latency_reps > 0:
+        pool = kv.KVPool(n_layers=s.n_layers, n_kv_heads=s.n_kv_heads, head_dim=s.head_dim,
+                         block_size=s.block_size, elt_bytes=s.elt_bytes, n_gpu_blocks=s.n_blocks,
+                         gpu_base=gpu.data_ptr(), host_bytes=payload + 64 * len(victims) * s.R,
+                         flags=(kv.KV_FLAG_FOUR_STREAMS if args.four_streams else 0)
+                         | (kv.KV_FLAG_MAPPED_SWAP_IN if args.mapped_swap_in else 0))
+        pool.swap_out_batch(victims, cur)
+        pool.kv_wait_all()
+        for lps in (0, s.n_layers, 4, 1):
+            call, first, last = [], [], []
+            for i, v in enumerate(victims):
+                t_a = time.perf_counter()
+                if lps:
+                    pool.swap_in_layerwise(v, nxt[i], lps)
+                    t_b = time.perf_counter()
+                    pool.kv_wait_layer(v, 0)
+                else:
+                    pool.swap_in(v, nxt[i])
+                    t_b = time.perf_counter()
+                    pool.kv_wait(v)
+                t_c = time.perf_counter()
+                pool.kv_wait(v)
+                t_d = time.perf_counter()
+                call.append((t_b - t_a) * 1e3)
+                first.append((t_c - t_a) * 1e3)
+                last.append((t_d - t_a) * 1e3)
+            cur, nxt = nxt, cur
+            lw["layers_per_step_%d" % lps if lps else "whole_request_swap_in"] = {
+                "call_median": percentile(call, 50), "first_step_median": percentile(first, 50),
+                "all_layers_median": percentile(last, 50), "all_victims_sum": round(sum(last), 3)}
+        pool.kv_pool_destroy()
     del gpu
     torch.cuda.empty_cache()
 
@@ -304,6 +340,11 @@ def main() -> int:
             "overlapped_median": percentile(ov_ms, 50),
             "overlapped_p99": percentile(ov_ms, 99),
             "median_request_MiB": round(float(np.median([len(t) for t in cur])) * s.R / (1 << 20), 1),
+        },
+        "layerwise_swap_in_ms": {
+            "what": "swap_in_layerwise per victim: host time of the call, call -> first step of layers landed "
+                    "(not before the call has returned), call -> all landed; host clock",
+            **lw,
         },
         "dispatch_us": {
             "what": "host time of one swap_out per victim: direct call vs submit to the swap manager "

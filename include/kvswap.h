@@ -198,7 +198,9 @@ int32_t swap_in_direct(kv_pool_t* pool, int64_t req, const int32_t* new_block_ta
  * everything; out_n_moved may be NULL), but the KV arrives in steps of layers_per_step layers
  * (1 .. n_layers), lowest layers first: per step one 2-D host-to-device copy per run of
  * adjacent host records (the K and V planes of consecutive layers are one contiguous slice of
- * each record) and one scatter over that plane range.  kv_stream_wait_layer makes a
+ * each record) and one scatter over that plane range; in a KV_FLAG_MAPPED_SWAP_IN pool a step
+ * is instead one launch of the kernel that reads the pinned image directly, over that plane
+ * range (no copies, no staging).  kv_stream_wait_layer makes a
  * hipStream_t wait on the device, kv_wait_layer the calling thread, until the step that holds
  * `layer` has landed, so attention over layer l can start while the layers above it are still
  * on the link.  For a request whose last op is not a layer-wise swap-in both wait for that

@@ -464,37 +464,51 @@ int32_t enqueue_direct(kv_pool* p, bool to_host, const std::vector<Move>& mv,
 // engine, no per-run copies - fragmented images and partial swap-ins cost the same as
 // contiguous ones.
 int32_t enqueue_in_mapped(kv_pool* p, const std::vector<Move>& mv, const std::vector<hipEvent_t>& pre,
-                          const OpRef& op) {
+                          const OpRef& op, int32_t layer_step) {
   int32_t rc;
   hipStream_t s = p->s_scat;
   if ((rc = order_after_compute(p, s))) return rc;
   for (hipEvent_t e : pre)
     if ((rc = stream_wait(p, s, e))) return rc;
   const int64_t m = (int64_t)mv.size();
-  for (int64_t i = 0; i < m; i += KV_MAX_MAPPED_BLOCKS) {
-    const int64_t ml = std::min<int64_t>(KV_MAX_MAPPED_BLOCKS, m - i);
-    p->st.scatter_launches++;
-    if (p->plan) continue;
-    KvMappedArgs a;
-    a.pool = p->gpu;
-    a.host = p->host_dev;
-    a.plane_stride = p->N * p->C;
-    a.R = p->R;
-    a.C = (uint32_t)p->C;
-    a.P = (uint32_t)p->P;
-    a.m = (uint32_t)ml;
-    a.tiles_per_chunk = a.n_tiles = a.pad = 0;
-    for (int64_t k = 0; k < ml; ++k) {
-      a.phys[k] = mv[(size_t)(i + k)].phys;
-      a.rec[k] = (uint32_t)(mv[(size_t)(i + k)].host_off / p->R);
+  const int32_t L = p->P / 2;
+  // layer-wise: one launch per step of layers over that slice of every record, and an event
+  // behind it; otherwise a single step over all planes
+  const int32_t step = layer_step > 0 ? layer_step : L;
+  op->layer_step = layer_step;
+  for (int32_t l0 = 0; l0 < L; l0 += step) {
+    const int32_t np = 2 * std::min(step, L - l0), p0 = 2 * l0;
+    for (int64_t i = 0; i < m; i += KV_MAX_MAPPED_BLOCKS) {
+      const int64_t ml = std::min<int64_t>(KV_MAX_MAPPED_BLOCKS, m - i);
+      p->st.scatter_launches++;
+      if (p->plan) continue;
+      KvMappedArgs a;
+      a.pool = p->gpu + (int64_t)p0 * p->N * p->C;
+      a.host = p->host_dev + (int64_t)p0 * p->C;
+      a.plane_stride = p->N * p->C;
+      a.R = p->R;
+      a.C = (uint32_t)p->C;
+      a.P = (uint32_t)np;
+      a.m = (uint32_t)ml;
+      a.tiles_per_chunk = a.n_tiles = a.pad = 0;
+      for (int64_t k = 0; k < ml; ++k) {
+        a.phys[k] = mv[(size_t)(i + k)].phys;
+        a.rec[k] = (uint32_t)(mv[(size_t)(i + k)].host_off / p->R);
+      }
+      hipEvent_t e0 = nullptr, e1 = nullptr;
+      if (p->profile) {
+        if ((rc = get_timing_event(p, &e0))) return rc;
+        if ((rc = get_timing_event(p, &e1))) return rc;
+        p->prof.push_back({4, ml * np * p->C, e0, e1});
+      }
+      HIP_TRY(kv_launch_mapped_scatter(a, p->mapped_grid, s, e0, e1));
     }
-    hipEvent_t e0 = nullptr, e1 = nullptr;
-    if (p->profile) {
-      if ((rc = get_timing_event(p, &e0))) return rc;
-      if ((rc = get_timing_event(p, &e1))) return rc;
-      p->prof.push_back({4, ml * p->R, e0, e1});
+    if (layer_step > 0) {
+      hipEvent_t landed;
+      if ((rc = get_event(p, &landed))) return rc;
+      op->layer_ev.push_back(landed);
+      if ((rc = record(p, landed, s))) return rc;
     }
-    HIP_TRY(kv_launch_mapped_scatter(a, p->mapped_grid, s, e0, e1));
   }
   if ((rc = record(p, op->done, s))) return rc;
   p->st.bytes_in += m * p->R;

@@ -189,7 +189,7 @@ int32_t enqueue_in_layers(kv_pool* p, const std::vector<Move>& mv, const std::ve
 int32_t enqueue_direct(kv_pool* p, bool to_host, const std::vector<Move>& mv,
                        const std::vector<hipEvent_t>& pre, const OpRef& op, bool per_block);
 int32_t enqueue_in_mapped(kv_pool* p, const std::vector<Move>& mv, const std::vector<hipEvent_t>& pre,
-                          const OpRef& op);
+                          const OpRef& op, int32_t layer_step = 0);
 
 // kv_reuse.cpp: validation, host arena and images, moved-set selection (the reuse map)
 void arena_give(kv_pool* p, const std::vector<Extent>& ext);

@@ -332,11 +332,11 @@ int32_t do_swap_in(kv_pool* p, std::vector<InItem>& items, int32_t* out_n_moved,
     pre_copy.insert(pre_copy.end(), pre_scat.begin(), pre_scat.end());
     return enqueue_direct(p, false, mv, pre_copy, op, direct == 2);
   }
-  if (layer_step > 0) return enqueue_in_layers(p, mv, pre_copy, pre_scat, op, layer_step);
   if (p->mapped_in) {
     pre_copy.insert(pre_copy.end(), pre_scat.begin(), pre_scat.end());
-    return enqueue_in_mapped(p, mv, pre_copy, op);
+    return enqueue_in_mapped(p, mv, pre_copy, op, layer_step);
   }
+  if (layer_step > 0) return enqueue_in_layers(p, mv, pre_copy, pre_scat, op, layer_step);
   return enqueue_in(p, mv, pre_copy, pre_scat, op);
 }
 

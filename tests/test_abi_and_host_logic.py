@@ -255,6 +255,11 @@ def test_layerwise_swap_in_plan(kv):
         p.kv_wait_layer(5, 0)
     assert ei.value.status == kv.KV_ENOENT
     assert p.kv_stats()["bytes_in"] == st3["bytes_in"]
+    # reading the pinned image directly: a step is one kernel launch, there are no copies
+    q = plan_pool(kv, shape, host_blocks=256, flags_extra=kv.KV_FLAG_MAPPED_SWAP_IN)
+    q.swap_out(0, t)
+    assert q.swap_in_layerwise(0, t, 1) == 10
+    assert q.kv_stats()["scatter_launches"] == 2 and q.kv_stats()["h2d_copies"] == 0
 
 
 def test_host_images_grow_by_extents_and_give_everything_back(kv):

@@ -537,7 +537,8 @@ def test_mapped_swap_in_reads_the_host_image_directly(harness, L, H, D, B, e, N)
     assert st["h2d_copies"] == 0 and st["bytes_in"] == h.oracle.bytes_in
 
 
-def test_layerwise_swap_in_lands_layer_by_layer(harness):
+@pytest.mark.parametrize("mapped", [0, 16], ids=["copy_engine", "mapped_reads"])
+def test_layerwise_swap_in_lands_layer_by_layer(harness, mapped):
     """Layer-wise swap-in (the alternative of Section 2.2, Challenge #2): same bytes as swap_in,
     and a stream that waits for layer l sees that layer's K and V complete."""
     import torch
@@ -545,7 +546,7 @@ def test_layerwise_swap_in_lands_layer_by_layer(harness):
     stream = torch.cuda.Stream()
     h = harness(shape, cfg=31, host_bytes=64 * MiB, fill="random", host_slack_blocks=2,
                 staging_in_bytes=1 * MiB, copy_chunk_bytes=256 * 1024,
-                flags=4, compute_stream=stream.cuda_stream)  # KV_FLAG_ORDER_COMPUTE
+                flags=4 | mapped, compute_stream=stream.cuda_stream)  # KV_FLAG_ORDER_COMPUTE [| MAPPED_SWAP_IN]
     rng = synth.rng_for(31)
     view = h.gpu.view(shape.P, shape.n_blocks, shape.C)
     n = 37
