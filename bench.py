@@ -85,6 +85,8 @@ def main() -> int:
     ap.add_argument("--requests", type=int, default=4, help="config 5: 10 GiB requests per run length")
     ap.add_argument("--mapped-swap-in", action="store_true",
                     help="swap-in by a kernel that reads the pinned host image directly (KV_FLAG_MAPPED_SWAP_IN)")
+    ap.add_argument("--mapped-swap-out", action="store_true",
+                    help="config 1: swap-out by a kernel that stores into the pinned image (KV_FLAG_MAPPED_SWAP_OUT)")
     ap.add_argument("--four-streams", action="store_true",
                     help="give kernels and copies of each direction their own streams (KV_FLAG_FOUR_STREAMS)")
     args = ap.parse_args()

@@ -31,7 +31,8 @@ def _rates(recs):
 
 def _flags(args, kv, base=0):
     return (base | (kv.KV_FLAG_FOUR_STREAMS if args.four_streams else 0)
-            | (kv.KV_FLAG_MAPPED_SWAP_IN if args.mapped_swap_in else 0))
+            | (kv.KV_FLAG_MAPPED_SWAP_IN if args.mapped_swap_in else 0)
+            | (kv.KV_FLAG_MAPPED_SWAP_OUT if getattr(args, "mapped_swap_out", False) else 0))
 
 
 def _pool(kv, torch, s, host_bytes, **kw):
@@ -98,7 +99,7 @@ def config1(args):
             "per_request_in_us": {"median": _pct(in_us, 50), "p99": _pct(in_us, 99)},
             "batched_all8_out_in_ms": {"median": _pct(b_ms, 50), "p99": _pct(b_ms, 99)},
             "batched_gbps": round(2 * payload / (np.median(b_ms) * 1e-3) / 1e9, 3),
-            "mapped_swap_in": bool(args.mapped_swap_in)}
+            "mapped_swap_in": bool(args.mapped_swap_in), "mapped_swap_out": bool(args.mapped_swap_out)}
 
 
 def config3(args):

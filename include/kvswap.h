@@ -63,6 +63,11 @@ typedef enum {
 #define KV_FLAG_MAPPED_SWAP_IN  16u /* swap-in reads the pinned host image directly from a small scatter
                                        kernel (no staging, no copy engine): lower latency, and the cost no
                                        longer depends on how fragmented the moved set is */
+#define KV_FLAG_MAPPED_SWAP_OUT 64u /* swap-outs that move at most mapped_out_max_blocks blocks are done by
+                                       one kernel that stores the records straight into the pinned image
+                                       (no staging, no copy): lowest latency for small requests.  Stores to
+                                       host memory slow HBM-bound kernels running beside them, so larger
+                                       swap-outs keep using the copy engines */
 #define KV_FLAG_HOST_EVICT      32u /* when the host arena is full, reclaim the host copies of other requests
                                        (Section 3.3: contamination by higher-priority requests): lowest
                                        priority first, least recently used first, never from a request of
@@ -99,8 +104,9 @@ typedef struct {
   int32_t pack_variant;     /* 0 = one tile per workgroup, 3-D grid, 256 lanes (default); 1 = persistent
                                grid-stride workgroups with the block table in LDS; 2 = same as 0;
                                3 = tile kernel with 1024 lanes */
-  int32_t mapped_in_grid;   /* workgroups of the mapped swap-in kernel; 0 = default 64 */
-  int32_t reserved;
+  int32_t mapped_in_grid;   /* workgroups of the mapped swap-in / swap-out kernels; 0 = default 64 */
+  int32_t mapped_out_max_blocks; /* with KV_FLAG_MAPPED_SWAP_OUT: largest moved set that takes the
+                               mapped path; 0 = every swap-out; < 0 is KV_EINVAL */
 } kv_pool_config_t;
 
 /* Section 3.1 (KV pool + block groups).  Creates the pool object: pinned host arena,
@@ -253,7 +259,7 @@ int32_t kv_stats(kv_pool_t* pool, kv_stats_t* out);
 
 /* Profiling (needs KV_FLAG_PROFILE).  One record per kernel launch / copy, in issue order. */
 typedef struct {
-  int32_t kind;      /* 0 gather, 1 scatter, 2 D2H copy, 3 H2D copy */
+  int32_t kind;      /* 0 gather, 1 scatter, 2 D2H copy, 3 H2D copy, 4 mapped swap-in kernel, 5 mapped swap-out kernel */
   int32_t reserved;
   int64_t bytes;     /* payload bytes of this launch / copy */
   double  ms;        /* device duration */

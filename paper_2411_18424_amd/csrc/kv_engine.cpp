@@ -501,7 +501,7 @@ int32_t enqueue_in_mapped(kv_pool* p, const std::vector<Move>& mv, const std::ve
         if ((rc = get_timing_event(p, &e1))) return rc;
         p->prof.push_back({4, ml * np * p->C, e0, e1});
       }
-      HIP_TRY(kv_launch_mapped_scatter(a, p->mapped_grid, s, e0, e1));
+      HIP_TRY(kv_launch_mapped(false, a, p->mapped_grid, s, e0, e1));
     }
     if (layer_step > 0) {
       hipEvent_t landed;
@@ -513,6 +513,49 @@ int32_t enqueue_in_mapped(kv_pool* p, const std::vector<Move>& mv, const std::ve
   if ((rc = record(p, op->done, s))) return rc;
   p->st.bytes_in += m * p->R;
   p->st.blocks_in += m;
+  return KV_OK;
+}
+
+// Swap-out straight into the pinned image (KV_FLAG_MAPPED_SWAP_OUT, small requests): one
+// launch per 440 blocks reads the pool and stores the records to host memory.  The gather is
+// the transfer, so the request's GPU blocks are reusable exactly when the swap-out is done.
+int32_t enqueue_out_mapped(kv_pool* p, const std::vector<Move>& mv, const std::vector<hipEvent_t>& pre,
+                           const OpRef& op) {
+  int32_t rc;
+  hipStream_t s = p->s_pack;
+  if ((rc = order_after_compute(p, s))) return rc;
+  for (hipEvent_t e : pre)
+    if ((rc = stream_wait(p, s, e))) return rc;
+  const int64_t m = (int64_t)mv.size();
+  for (int64_t i = 0; i < m; i += KV_MAX_MAPPED_BLOCKS) {
+    const int64_t ml = std::min<int64_t>(KV_MAX_MAPPED_BLOCKS, m - i);
+    p->st.gather_launches++;
+    if (p->plan) continue;
+    KvMappedArgs a;
+    a.pool = p->gpu;
+    a.host = p->host_dev;
+    a.plane_stride = p->N * p->C;
+    a.R = p->R;
+    a.C = (uint32_t)p->C;
+    a.P = (uint32_t)p->P;
+    a.m = (uint32_t)ml;
+    a.tiles_per_chunk = a.n_tiles = a.pad = 0;
+    for (int64_t k = 0; k < ml; ++k) {
+      a.phys[k] = mv[(size_t)(i + k)].phys;
+      a.rec[k] = (uint32_t)(mv[(size_t)(i + k)].host_off / p->R);
+    }
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (p->profile) {
+      if ((rc = get_timing_event(p, &e0))) return rc;
+      if ((rc = get_timing_event(p, &e1))) return rc;
+      p->prof.push_back({5, ml * p->R, e0, e1});
+    }
+    HIP_TRY(kv_launch_mapped(true, a, p->mapped_grid, s, e0, e1));
+  }
+  if ((rc = record(p, op->packed, s))) return rc;
+  if ((rc = record(p, op->done, s))) return rc;
+  p->st.bytes_out += m * p->R;
+  p->st.blocks_out += m;
   return KV_OK;
 }
 

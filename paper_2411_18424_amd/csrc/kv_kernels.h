@@ -26,7 +26,7 @@ struct KvPackArgs {
 #define KV_MAX_MAPPED_BLOCKS 440
 struct KvMappedArgs {
   char* pool;            // device: pool[p][b][C]
-  const char* host;      // device-visible address of the pinned arena
+  char* host;            // device-visible address of the pinned arena
   int64_t plane_stride;  // N * C bytes
   int64_t R;             // record bytes = P * C
   uint32_t C;
@@ -39,8 +39,9 @@ struct KvMappedArgs {
   uint32_t rec[KV_MAX_MAPPED_BLOCKS];
 };
 // grid: workgroups (few: the host link, not the CUs, is the limit).
-hipError_t kv_launch_mapped_scatter(const KvMappedArgs& a, int grid, hipStream_t stream,
-                                    hipEvent_t start, hipEvent_t stop);
+// to_host: records go from the pool to the arena (swap-out); else from the arena to the pool.
+hipError_t kv_launch_mapped(bool to_host, const KvMappedArgs& a, int grid, hipStream_t stream,
+                            hipEvent_t start, hipEvent_t stop);
 
 #define KV_PACK_TILE 0        // one tile per workgroup, 3-D grid, 256 lanes (default)
 #define KV_PACK_PERSISTENT 1  // grid-stride loop, block table staged in LDS, 256 lanes

@@ -89,13 +89,17 @@ __global__ __launch_bounds__(WG) void kv_pack_persistent_kernel(const KvPackArgs
   }
 }
 
-// Swap-in without staging: a small persistent grid reads the block records straight from
-// pinned host memory (loads travel over the host link; 8 vectors per lane in flight) and
-// stores them into the pool.  A few dozen workgroups saturate the link, and - unlike a
-// kernel that *stores* to host memory - host reads cost an HBM-bound neighbour only ~2 %.
-// The table (physical id, arena record) of the launch is staged in LDS once per workgroup.
-template <bool FULL>
-__global__ __launch_bounds__(256) void kv_mapped_scatter_kernel(const KvMappedArgs a) {
+// Swap without staging: a small persistent grid moves block records straight between the
+// pool and pinned host memory; the table (physical id, arena record) of the launch is staged
+// in LDS once per workgroup, 8 vectors per lane are in flight.
+// TO_HOST = false (swap-in): loads travel over the host link, stores go to the pool.  A few
+//   dozen workgroups saturate the link and host reads cost an HBM-bound neighbour only ~2 %.
+// TO_HOST = true (swap-out): loads from the pool, stores to host memory.  Lowest latency for
+//   small requests (one launch, no copy), but stores to the host back up the memory fabric:
+//   an HBM-bound kernel beside it loses most of its bandwidth, so large transfers belong on
+//   the copy engines.
+template <bool FULL, bool TO_HOST>
+__global__ __launch_bounds__(256) void kv_mapped_kernel(const KvMappedArgs a) {
   __shared__ int32_t s_phys[KV_MAX_MAPPED_BLOCKS];
   __shared__ uint32_t s_rec[KV_MAX_MAPPED_BLOCKS];
   for (uint32_t i = threadIdx.x; i < a.m; i += 256) {
@@ -114,19 +118,24 @@ __global__ __launch_bounds__(256) void kv_mapped_scatter_kernel(const KvMappedAr
     const uint32_t k = q / P;
     const uint32_t p = q - k * P;
     const uint32_t v0 = t * TILE_VECS;
-    const u32x4* src = reinterpret_cast<const u32x4*>(a.host + (int64_t)s_rec[k] * a.R + (int64_t)p * a.C) + v0;
-    u32x4* dst = reinterpret_cast<u32x4*>(a.pool + (int64_t)p * a.plane_stride + (int64_t)s_phys[k] * a.C) + v0;
+    u32x4* host = reinterpret_cast<u32x4*>(a.host + (int64_t)s_rec[k] * a.R + (int64_t)p * a.C) + v0;
+    u32x4* pool = reinterpret_cast<u32x4*>(a.pool + (int64_t)p * a.plane_stride + (int64_t)s_phys[k] * a.C) + v0;
     const uint32_t rem = chunk_vecs - v0;
     u32x4 r[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const uint32_t i = threadIdx.x + u * 256;
-      if (FULL || i < rem) r[u] = src[i];
+      if (FULL || i < rem) r[u] = TO_HOST ? __builtin_nontemporal_load(pool + i) : host[i];
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const uint32_t i = threadIdx.x + u * 256;
-      if (FULL || i < rem) __builtin_nontemporal_store(r[u], dst + i);
+      if (FULL || i < rem) {
+        if (TO_HOST)
+          host[i] = r[u];
+        else
+          __builtin_nontemporal_store(r[u], pool + i);
+      }
     }
   }
 }
@@ -247,8 +256,8 @@ hipError_t kv_launch_linear_copy(void* dst, const void* src, int64_t bytes, hipS
   return hipGetLastError();
 }
 
-hipError_t kv_launch_mapped_scatter(const KvMappedArgs& a_in, int grid, hipStream_t stream,
-                                    hipEvent_t start, hipEvent_t stop) {
+hipError_t kv_launch_mapped(bool to_host, const KvMappedArgs& a_in, int grid, hipStream_t stream,
+                            hipEvent_t start, hipEvent_t stop) {
   if (a_in.m == 0) return hipSuccess;
   if (a_in.m > KV_MAX_MAPPED_BLOCKS || (a_in.C & 15u) || a_in.C == 0 || a_in.P == 0)
     return hipErrorInvalidValue;
@@ -260,9 +269,15 @@ hipError_t kv_launch_mapped_scatter(const KvMappedArgs& a_in, int grid, hipStrea
   a.n_tiles = (uint32_t)n_tiles;
   if (grid <= 0) grid = 64;
   if ((uint64_t)grid > n_tiles) grid = (int)n_tiles;
-  if (a.C % tile == 0)
-    hipExtLaunchKernelGGL((kv_mapped_scatter_kernel<true>), dim3(grid), dim3(256), 0, stream, start, stop, 0, a);
-  else
-    hipExtLaunchKernelGGL((kv_mapped_scatter_kernel<false>), dim3(grid), dim3(256), 0, stream, start, stop, 0, a);
+  const bool full = a.C % tile == 0;
+#define KV_LAUNCH_MAPPED(FULL, TO_HOST)                                                              \
+  hipExtLaunchKernelGGL((kv_mapped_kernel<FULL, TO_HOST>), dim3(grid), dim3(256), 0, stream, start, \
+                        stop, 0, a)
+  if (to_host) {
+    if (full) KV_LAUNCH_MAPPED(true, true); else KV_LAUNCH_MAPPED(false, true);
+  } else {
+    if (full) KV_LAUNCH_MAPPED(true, false); else KV_LAUNCH_MAPPED(false, false);
+  }
+#undef KV_LAUNCH_MAPPED
   return hipGetLastError();
 }

@@ -135,6 +135,8 @@ struct kv_pool {
   char* host = nullptr;      // pinned arena
   char* host_dev = nullptr;  // the arena as the device addresses it
   bool mapped_in = false;
+  bool mapped_out = false;          // swap-outs of at most mapped_out_max blocks store to the host directly
+  int64_t mapped_out_max = 0;       // 0 = no limit
   bool host_evict = false;
   uint64_t use_clock = 0;
   int mapped_grid = 64;
@@ -188,6 +190,8 @@ int32_t enqueue_in_layers(kv_pool* p, const std::vector<Move>& mv, const std::ve
                           const std::vector<hipEvent_t>& pre_scat, const OpRef& op, int32_t step);
 int32_t enqueue_direct(kv_pool* p, bool to_host, const std::vector<Move>& mv,
                        const std::vector<hipEvent_t>& pre, const OpRef& op, bool per_block);
+int32_t enqueue_out_mapped(kv_pool* p, const std::vector<Move>& mv, const std::vector<hipEvent_t>& pre,
+                           const OpRef& op);
 int32_t enqueue_in_mapped(kv_pool* p, const std::vector<Move>& mv, const std::vector<hipEvent_t>& pre,
                           const OpRef& op, int32_t layer_step = 0);
 

@@ -275,6 +275,8 @@ int32_t do_swap_out(kv_pool* p, std::vector<OutItem>& items, int32_t* out_n_move
   }
   if (out_n_moved) *out_n_moved = (int32_t)total_moved;
   if (direct) return enqueue_direct(p, true, mv, pre, op, direct == 2);
+  if (p->mapped_out && (p->mapped_out_max == 0 || (int64_t)mv.size() <= p->mapped_out_max))
+    return enqueue_out_mapped(p, mv, pre, op);
   return enqueue_out(p, mv, pre, op);
 }
 

@@ -92,6 +92,7 @@ int32_t kv_pool_create(const kv_pool_config_t* cfg, kv_pool_t** out) {
   if (cfg->host_bytes < 0 || cfg->staging_out_bytes < 0 || cfg->staging_in_bytes < 0 ||
       cfg->max_piece_bytes < 0 || cfg->copy_chunk_bytes < 0)
     return fail(KV_EINVAL, "negative size");
+  if (cfg->mapped_out_max_blocks < 0) return fail(KV_EINVAL, "negative mapped_out_max_blocks");
 
   kv_pool* p = new kv_pool();
   p->cfg = *cfg;
@@ -111,6 +112,8 @@ int32_t kv_pool_create(const kv_pool_config_t* cfg, kv_pool_t** out) {
   p->variant = cfg->pack_variant;
   p->mapped_in = (cfg->flags & KV_FLAG_MAPPED_SWAP_IN) != 0;
   p->host_evict = (cfg->flags & KV_FLAG_HOST_EVICT) != 0;
+  p->mapped_out = (cfg->flags & KV_FLAG_MAPPED_SWAP_OUT) != 0;
+  p->mapped_out_max = cfg->mapped_out_max_blocks;
   if (cfg->mapped_in_grid > 0) p->mapped_grid = cfg->mapped_in_grid;
   p->launch_blocks = kv_max_launch_blocks((uint32_t)C, (uint32_t)p->P, p->unroll, p->variant);
   // staging rings: defaults scale with the pool, capped at 4 GiB (out) and 1 GiB (in)

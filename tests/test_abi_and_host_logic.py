@@ -262,6 +262,25 @@ def test_layerwise_swap_in_plan(kv):
     assert q.kv_stats()["scatter_launches"] == 2 and q.kv_stats()["h2d_copies"] == 0
 
 
+def test_mapped_swap_out_takes_small_moved_sets_only(kv):
+    shape = synth.TINY
+    p = plan_pool(kv, shape, host_blocks=256, flags_extra=kv.KV_FLAG_MAPPED_SWAP_OUT, mapped_out_max_blocks=4)
+    t = np.arange(10, dtype=np.int32)
+    p.swap_out(0, t[:4])                     # 4 blocks: one kernel, no copy
+    st = p.kv_stats()
+    assert (st["gather_launches"], st["d2h_copies"], st["bytes_out"]) == (1, 0, 4 * shape.R)
+    p.swap_out(1, t[:5])                     # 5 blocks: staged
+    st = p.kv_stats()
+    assert (st["gather_launches"], st["d2h_copies"]) == (2, 1)
+    dirty = np.array([0, 0, 1, 0, 1], np.uint8)
+    assert p.swap_out_delta(1, t[:5], dirty) == 2   # the moved set counts, not the request
+    st = p.kv_stats()
+    assert (st["gather_launches"], st["d2h_copies"]) == (3, 1)
+    with pytest.raises(kv.KVError) as ei:
+        plan_pool(kv, shape, mapped_out_max_blocks=-1)
+    assert ei.value.status == kv.KV_EINVAL
+
+
 def test_host_images_grow_by_extents_and_give_everything_back(kv):
     """Section 3.3: room behind a new image is reserved for the next turn; when it is used up
     the image continues in a further extent (it is never moved)."""

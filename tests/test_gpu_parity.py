@@ -502,11 +502,13 @@ def test_concurrent_host_threads(harness):
     (3, 3, 40, 16, 2, 96),     # C = 3840: ragged
     (1, 1, 32, 16, 2, 2048),   # many small blocks: more than 440 per swap-in -> several launches
 ])
-def test_mapped_swap_in_reads_the_host_image_directly(harness, L, H, D, B, e, N):
-    """KV_FLAG_MAPPED_SWAP_IN: swap-in by a kernel that reads pinned host memory; same bytes
-    as the staged path, for full, partial and multi-extent images."""
+@pytest.mark.parametrize("out_too", [0, 64], ids=["in", "in_and_out"])
+def test_mapped_swaps_touch_the_host_image_directly(harness, L, H, D, B, e, N, out_too):
+    """KV_FLAG_MAPPED_SWAP_IN (and KV_FLAG_MAPPED_SWAP_OUT): swaps by kernels that read / write
+    pinned host memory; same bytes as the staged path, for full, partial, delta and
+    multi-extent images."""
     shape = synth.KVShape("s", L, H, D, B, e, N, "fp16")
-    h = harness(shape, cfg=18, fill="random", flags=16, host_slack_blocks=2)
+    h = harness(shape, cfg=18, fill="random", flags=16 | out_too, host_slack_blocks=2)
     rng = synth.rng_for(18, stream=N)
     n = min(N // 3, 700)
     t = rng.permutation(N)[:n].astype(np.int32)
@@ -535,6 +537,7 @@ def test_mapped_swap_in_reads_the_host_image_directly(harness, L, H, D, B, e, N)
     h.assert_pool_equal()
     st = h.pool.kv_stats()
     assert st["h2d_copies"] == 0 and st["bytes_in"] == h.oracle.bytes_in
+    assert (st["d2h_copies"] == 0) == bool(out_too) and st["bytes_out"] == h.oracle.bytes_out
 
 
 @pytest.mark.parametrize("mapped", [0, 16], ids=["copy_engine", "mapped_reads"])

@@ -15,7 +15,7 @@ pytestmark = pytest.mark.gpu
 KiB, MiB = 1 << 10, 1 << 20
 SHAPE = synth.KVShape("stream", 2, 2, 64, 16, 2, 512, "fp16")  # C = 4 KiB, R = 16 KiB, 8 MiB pool
 
-ORDER_COMPUTE, FOUR_STREAMS, MAPPED_SWAP_IN = 4, 8, 16
+ORDER_COMPUTE, FOUR_STREAMS, MAPPED_SWAP_IN, MAPPED_SWAP_OUT = 4, 8, 16, 64
 
 
 class Loop:
@@ -203,6 +203,9 @@ CASES = {
     "persistent_pack_kernel": (103, ORDER_COMPUTE, dict(pack_variant=1, staging_out_bytes=2 * MiB,
                                                         staging_in_bytes=2 * MiB, copy_chunk_bytes=64 * KiB)),
     "mapped_swap_in": (104, ORDER_COMPUTE | MAPPED_SWAP_IN, dict(host_slack_blocks=8)),
+    # small swap-outs store to the host from a kernel, larger ones go through staging and copies
+    "mapped_small_swap_outs": (106, ORDER_COMPUTE | MAPPED_SWAP_OUT, dict(mapped_out_max_blocks=12,
+                                                                           host_slack_blocks=4)),
     "tight_host_arena": (105, ORDER_COMPUTE, dict(host_slack_blocks=2)),
 }
 
