@@ -112,6 +112,9 @@ int32_t host_wait_op(kv_pool* p, const OpRef& op) {
 }
 
 // ---------------------------------------------------------------- engine
+// base + off; a plan-only pool has no memory behind its bases (null stays null)
+static inline char* at(char* base, int64_t off) { return base ? base + off : nullptr; }
+
 int32_t stream_wait(kv_pool* p, hipStream_t s, hipEvent_t ev) {
   if (p->plan || !ev) return KV_OK;
   HIP_TRY(hipStreamWaitEvent(s, ev, 0));
@@ -171,8 +174,8 @@ int32_t issue_copies(kv_pool* p, bool to_host, char* slot, const Move* mv, int64
     int64_t j = i;
     while (j + 1 < m && mv[j + 1].host_off == mv[j].host_off + p->R) ++j;
     int64_t bytes = (j - i + 1) * p->R;
-    char* h = p->host + mv[i].host_off;
-    char* d = slot + i * p->R;
+    char* h = at(p->host, mv[i].host_off);
+    char* d = at(slot, i * p->R);
     for (int64_t o = 0; o < bytes; o += p->copy_chunk) {
       int64_t nb = std::min(p->copy_chunk, bytes - o);
       (to_host ? p->st.d2h_copies : p->st.h2d_copies)++;
@@ -258,7 +261,7 @@ int32_t enqueue_out(kv_pool* p, const std::vector<Move>& mv, const std::vector<h
     if ((rc2 = record(p, ready, p->s_pack))) return rc2;
     if ((rc2 = stream_wait(p, p->s_d2h, ready))) return rc2;
     for (const Pending& q : pending) {
-      if ((rc2 = issue_copies(p, true, r.base + q.off, &mv[(size_t)q.first], q.count))) return rc2;
+      if ((rc2 = issue_copies(p, true, at(r.base, q.off), &mv[(size_t)q.first], q.count))) return rc2;
       for (Region& g : r.live)
         if (g.off == q.off && g.op_seq == op->seq && !g.recorded) {
           if ((rc2 = record(p, g.freed, p->s_d2h))) return rc2;
@@ -275,7 +278,7 @@ int32_t enqueue_out(kv_pool* p, const std::vector<Move>& mv, const std::vector<h
     const int64_t off = g->off;
     for (int64_t k = 0; k < mp; k += p->launch_blocks) {
       int64_t ml = std::min<int64_t>(p->launch_blocks, mp - k);
-      if ((rc = launch_pack(p, false, r.base + off + k * p->R, &mv[(size_t)(i + k)], ml))) return rc;
+      if ((rc = launch_pack(p, false, at(r.base, off + k * p->R), &mv[(size_t)(i + k)], ml))) return rc;
     }
     pending.push_back({i, mp, off});
   }
@@ -306,7 +309,7 @@ int32_t enqueue_in(kv_pool* p, const std::vector<Move>& mv, const std::vector<hi
     const int64_t mp = std::min(r.piece_blocks, m - i);
     Region* g;
     if ((rc = ring_claim(p, &r, mp * p->R, op->seq, p->s_h2d, no_flush, &g))) return rc;
-    char* sb = r.base + g->off;
+    char* sb = at(r.base, g->off);
     if ((rc = issue_copies(p, false, sb, &mv[(size_t)i], mp))) return rc;
     hipEvent_t ready;
     if ((rc = get_event(p, &ready))) return rc;
@@ -315,7 +318,7 @@ int32_t enqueue_in(kv_pool* p, const std::vector<Move>& mv, const std::vector<hi
     if ((rc = stream_wait(p, p->s_scat, ready))) return rc;
     for (int64_t k = 0; k < mp; k += p->launch_blocks) {
       int64_t ml = std::min<int64_t>(p->launch_blocks, mp - k);
-      if ((rc = launch_pack(p, true, sb + k * p->R, &mv[(size_t)(i + k)], ml))) return rc;
+      if ((rc = launch_pack(p, true, at(sb, k * p->R), &mv[(size_t)(i + k)], ml))) return rc;
     }
     if ((rc = record(p, g->freed, p->s_scat))) return rc;
     g->recorded = true;
@@ -363,7 +366,7 @@ int32_t enqueue_in_layers(kv_pool* p, const std::vector<Move>& mv, const std::ve
       const int64_t mp = std::min(piece_blocks, m - i);
       Region* g;
       if ((rc = ring_claim(p, &r, mp * slice, op->seq, p->s_h2d, no_flush, &g))) return rc;
-      char* sb = r.base + g->off;
+      char* sb = at(r.base, g->off);
       hipEvent_t e0 = nullptr, e1 = nullptr;
       if (p->profile && !p->plan) {
         if ((rc = get_timing_event(p, &e0))) return rc;
@@ -392,7 +395,7 @@ int32_t enqueue_in_layers(kv_pool* p, const std::vector<Move>& mv, const std::ve
       if ((rc = stream_wait(p, p->s_scat, ready))) return rc;
       for (int64_t k = 0; k < mp; k += p->launch_blocks) {
         int64_t ml = std::min<int64_t>(p->launch_blocks, mp - k);
-        if ((rc = launch_pack(p, true, sb + k * slice, &mv[(size_t)(i + k)], ml, p0, np))) return rc;
+        if ((rc = launch_pack(p, true, at(sb, k * slice), &mv[(size_t)(i + k)], ml, p0, np))) return rc;
       }
       if ((rc = record(p, g->freed, p->s_scat))) return rc;
       g->recorded = true;
@@ -438,8 +441,8 @@ int32_t enqueue_direct(kv_pool* p, bool to_host, const std::vector<Move>& mv,
         ++j;
     const int64_t r = j - i + 1;
     for (int32_t pl = 0; pl < p->P; ++pl) {
-      char* h = p->host + mv[(size_t)i].host_off + (int64_t)pl * p->C;
-      char* d = p->gpu + ((int64_t)pl * p->N + mv[(size_t)i].phys) * p->C;
+      char* h = at(p->host, mv[(size_t)i].host_off + (int64_t)pl * p->C);
+      char* d = at(p->gpu, ((int64_t)pl * p->N + mv[(size_t)i].phys) * p->C);
       (to_host ? p->st.d2h_copies : p->st.h2d_copies)++;
       if (p->plan) continue;
       if (to_host)

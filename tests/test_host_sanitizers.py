@@ -1,0 +1,43 @@
+"""The library's host code under the host sanitizers: tests/host/plan_stress.cpp drives a
+plan-only pool (no HIP call, no GPU) from several threads through the C ABI - swaps, reuse
+map, eviction, both allocators, swap manager - and is built once with AddressSanitizer +
+UndefinedBehaviorSanitizer and once with ThreadSanitizer (host pass only; device code is
+compiled as usual)."""
+
+import os
+import shutil
+import subprocess
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+CSRC = os.path.join(ROOT, "paper_2411_18424_amd", "csrc")
+SOURCES = [os.path.join(ROOT, "tests", "host", "plan_stress.cpp")] + [
+    os.path.join(CSRC, f) for f in ("kv_kernels.hip", "kv_engine.cpp", "kv_reuse.cpp", "kvswap.cpp",
+                                    "kv_probe.cpp", "kv_manager.cpp")]
+FLAGS = ["-O1", "-g", "-std=c++17", "--offload-arch=gfx950", "-pthread",
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
+SANITIZERS = {
+    "address_undefined": ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+                          "-Xarch_host", "-fno-sanitize-recover=undefined"],
+    "thread": ["-Xarch_host", "-fsanitize=thread"],
+}
+
+
+@pytest.mark.parametrize("kind", sorted(SANITIZERS))
+def test_host_logic_is_clean_under(kind, tmp_path):
+    hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+    if not os.path.exists(hipcc):
+        pytest.skip("hipcc not found")
+    exe = str(tmp_path / ("plan_stress_" + kind))
+    build = subprocess.run([hipcc] + FLAGS + SANITIZERS[kind] + SOURCES + ["-o", exe],
+                           stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=600)
+    assert build.returncode == 0, build.stdout[-4000:]
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", TSAN_OPTIONS="halt_on_error=1",
+               UBSAN_OPTIONS="print_stacktrace=1")
+    iters = "20000" if kind == "address_undefined" else "6000"
+    run = subprocess.run([exe, iters], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True,
+                         timeout=300, env=env)
+    assert run.returncode == 0, run.stdout[-4000:]
+    assert "plan_stress: 0 failures" in run.stdout, run.stdout[-2000:]
+    assert "Sanitizer" not in run.stdout, run.stdout[-4000:]
