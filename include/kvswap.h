@@ -103,7 +103,9 @@ typedef struct {
   int32_t tile_unroll;      /* 16-byte vectors per lane per tile (1,2,4,8); 0 = from chunk size */
   int32_t pack_variant;     /* 0 = one tile per workgroup, 3-D grid, 256 lanes (default); 1 = persistent
                                grid-stride workgroups with the block table in LDS; 2 = same as 0;
-                               3 = tile kernel with 1024 lanes */
+                               3 = tile kernel with 1024 lanes; 4..7 = as 0 with the store cache
+                               policy forced (bit 0: gather, bit 1: scatter stores at agent scope),
+                               for comparison */
   int32_t mapped_in_grid;   /* workgroups of the mapped swap-in / swap-out kernels; 0 = default 64 */
   int32_t mapped_out_max_blocks; /* with KV_FLAG_MAPPED_SWAP_OUT: largest moved set that takes the
                                mapped path; 0 = every swap-out; < 0 is KV_EINVAL */

@@ -29,7 +29,26 @@
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-template <int WG, int U, bool FULL, bool SCATTER>
+// Streaming store of one vector to device memory: non-temporal and at agent scope (sc1).
+// Measured on MI355X (read+write TB/s, 4 KiB per workgroup, nt loads; all 8 x 8 combinations of
+// sc0 / sc1 / nt on loads and stores were swept): a plain 2 GiB copy reaches 6.65 with sc1
+// stores against 6.43 with nt-only stores, the scatter (linear reads, writes strided over
+// planes) 6.03 against 5.74, but the gather (strided reads, linear writes) loses: 5.74 against
+// 6.19.  So the scatter and the linear copy store with sc1 nt, the gather with nt only.
+// Loads: nt is what matters (6.1 without), the scope bits make no difference.
+__device__ __forceinline__ void store_stream(u32x4 v, u32x4* p) {
+  asm volatile("global_store_dwordx4 %0, %1, off sc1 nt" : : "v"(p), "v"(v) : "memory");
+}
+
+template <bool SC1>
+__device__ __forceinline__ void store_vec(u32x4 v, u32x4* p) {
+  if (SC1)
+    store_stream(v, p);
+  else
+    __builtin_nontemporal_store(v, p);
+}
+
+template <int WG, int U, bool FULL, bool SCATTER, bool SC1>
 __device__ __forceinline__ void move_tile(u32x4* pool_ptr, u32x4* stag_ptr, uint32_t rem) {
   const u32x4* src = SCATTER ? stag_ptr : pool_ptr;
   u32x4* dst = SCATTER ? pool_ptr : stag_ptr;
@@ -38,7 +57,7 @@ __device__ __forceinline__ void move_tile(u32x4* pool_ptr, u32x4* stag_ptr, uint
 #pragma unroll
     for (int u = 0; u < U; ++u) r[u] = __builtin_nontemporal_load(src + threadIdx.x + u * WG);
 #pragma unroll
-    for (int u = 0; u < U; ++u) __builtin_nontemporal_store(r[u], dst + threadIdx.x + u * WG);
+    for (int u = 0; u < U; ++u) store_vec<SC1>(r[u], dst + threadIdx.x + u * WG);
   } else {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -48,12 +67,12 @@ __device__ __forceinline__ void move_tile(u32x4* pool_ptr, u32x4* stag_ptr, uint
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const uint32_t i = threadIdx.x + u * WG;
-      if (i < rem) __builtin_nontemporal_store(r[u], dst + i);
+      if (i < rem) store_vec<SC1>(r[u], dst + i);
     }
   }
 }
 
-template <int WG, int U, bool FULL, bool SCATTER>
+template <int WG, int U, bool FULL, bool SCATTER, bool SC1>
 __global__ __launch_bounds__(WG) void kv_pack_tile_kernel(const KvPackArgs a) {
   constexpr uint32_t TILE_VECS = WG * U;  // 16-byte vectors per tile
   const uint32_t t = blockIdx.x, p = blockIdx.y, k = blockIdx.z;
@@ -63,10 +82,10 @@ __global__ __launch_bounds__(WG) void kv_pack_tile_kernel(const KvPackArgs a) {
       reinterpret_cast<u32x4*>(a.pool + (int64_t)p * a.plane_stride + b * (int64_t)a.C) + v0;
   u32x4* stag_ptr =
       reinterpret_cast<u32x4*>(a.staging + ((int64_t)k * a.P + p) * (int64_t)a.C) + v0;
-  move_tile<WG, U, FULL, SCATTER>(pool_ptr, stag_ptr, (a.C >> 4) - v0);
+  move_tile<WG, U, FULL, SCATTER, SC1>(pool_ptr, stag_ptr, (a.C >> 4) - v0);
 }
 
-template <int WG, int U, bool FULL, bool SCATTER>
+template <int WG, int U, bool FULL, bool SCATTER, bool SC1>
 __global__ __launch_bounds__(WG) void kv_pack_persistent_kernel(const KvPackArgs a) {
   __shared__ int32_t s_table[KV_MAX_LAUNCH_BLOCKS];
   for (uint32_t i = threadIdx.x; i < a.m; i += WG) s_table[i] = a.table[i];
@@ -85,7 +104,7 @@ __global__ __launch_bounds__(WG) void kv_pack_persistent_kernel(const KvPackArgs
     u32x4* pool_ptr =
         reinterpret_cast<u32x4*>(a.pool + (int64_t)p * a.plane_stride + b * (int64_t)a.C) + v0;
     u32x4* stag_ptr = reinterpret_cast<u32x4*>(a.staging + (int64_t)q * a.C) + v0;
-    move_tile<WG, U, FULL, SCATTER>(pool_ptr, stag_ptr, (a.C >> 4) - v0);
+    move_tile<WG, U, FULL, SCATTER, SC1>(pool_ptr, stag_ptr, (a.C >> 4) - v0);
   }
 }
 
@@ -134,7 +153,7 @@ __global__ __launch_bounds__(256) void kv_mapped_kernel(const KvMappedArgs a) {
         if (TO_HOST)
           host[i] = r[u];
         else
-          __builtin_nontemporal_store(r[u], pool + i);
+          store_stream(r[u], pool + i);
       }
     }
   }
@@ -146,7 +165,7 @@ __global__ __launch_bounds__(KV_WG) void kv_linear_copy_kernel(u32x4* __restrict
                                                                const u32x4* __restrict__ src,
                                                                int64_t n_vecs) {
   const int64_t i = (int64_t)blockIdx.x * KV_WG + threadIdx.x;
-  if (i < n_vecs) __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
+  if (i < n_vecs) store_stream(__builtin_nontemporal_load(src + i), dst + i);
 }
 
 // Workgroup size of the tile kernel: 256 lanes (4 KiB tiles).  Measured on MI355X: alone, the
@@ -155,6 +174,14 @@ __global__ __launch_bounds__(KV_WG) void kv_linear_copy_kernel(u32x4* __restrict
 // and the scatter drops to half the rate of the 256-lane one (0.6 vs 1.2 TB/s), so 256 lanes
 // are the default for both directions.  64-lane workgroups do better still beside a GEMM
 // (gather 3.4 vs 2.2 TB/s) but lose 12 % alone.
+// Store policy of a launch: 1 = sc1 nt, 0 = nt only.  Variants 4 .. 7 exist to compare the
+// four combinations (bit 0: gather stores sc1, bit 1: scatter stores sc1).
+static int store_policy(int variant, bool scatter) {
+  int bits = 2;  // default: gather nt, scatter sc1 nt
+  if (variant >= 4 && variant <= 7) bits = variant - 4;
+  return scatter ? (bits >> 1) & 1 : bits & 1;
+}
+
 static int pick_wg(int variant) { return variant == KV_PACK_TILE_1024 ? 1024 : 256; }
 
 int kv_pick_unroll(uint32_t C, int wg) {
@@ -192,27 +219,27 @@ int64_t kv_max_launch_blocks(uint32_t C, uint32_t P, int unroll, int variant) {
   return (int64_t)(by_grid < KV_MAX_LAUNCH_BLOCKS ? by_grid : KV_MAX_LAUNCH_BLOCKS);
 }
 
-template <int WG, int U, bool FULL, bool SCATTER>
+template <int WG, int U, bool FULL, bool SCATTER, bool SC1>
 static hipError_t launch_one(const KvPackArgs& a, bool persistent, int grid, hipStream_t stream,
                              hipEvent_t start, hipEvent_t stop) {
   if (persistent) {
-    hipExtLaunchKernelGGL((kv_pack_persistent_kernel<WG, U, FULL, SCATTER>), dim3(grid), dim3(WG), 0,
+    hipExtLaunchKernelGGL((kv_pack_persistent_kernel<WG, U, FULL, SCATTER, SC1>), dim3(grid), dim3(WG), 0,
                           stream, start, stop, 0, a);
   } else {
-    hipExtLaunchKernelGGL((kv_pack_tile_kernel<WG, U, FULL, SCATTER>),
+    hipExtLaunchKernelGGL((kv_pack_tile_kernel<WG, U, FULL, SCATTER, SC1>),
                           dim3(a.tiles_per_chunk, a.P, a.m), dim3(WG), 0, stream, start, stop, 0, a);
   }
   return hipGetLastError();
 }
 
-template <int WG, int U>
+template <int WG, int U, bool SC1>
 static hipError_t launch_wu(bool scatter, bool full, const KvPackArgs& a, bool persistent, int grid,
                             hipStream_t stream, hipEvent_t start, hipEvent_t stop) {
   if (scatter)
-    return full ? launch_one<WG, U, true, true>(a, persistent, grid, stream, start, stop)
-                : launch_one<WG, U, false, true>(a, persistent, grid, stream, start, stop);
-  return full ? launch_one<WG, U, true, false>(a, persistent, grid, stream, start, stop)
-              : launch_one<WG, U, false, false>(a, persistent, grid, stream, start, stop);
+    return full ? launch_one<WG, U, true, true, SC1>(a, persistent, grid, stream, start, stop)
+                : launch_one<WG, U, false, true, SC1>(a, persistent, grid, stream, start, stop);
+  return full ? launch_one<WG, U, true, false, SC1>(a, persistent, grid, stream, start, stop)
+              : launch_one<WG, U, false, false, SC1>(a, persistent, grid, stream, start, stop);
 }
 
 hipError_t kv_launch_pack(bool scatter, const KvPackArgs& a_in, int unroll, int variant, int grid,
@@ -231,15 +258,17 @@ hipError_t kv_launch_pack(bool scatter, const KvPackArgs& a_in, int unroll, int 
   if (a.P > 65535u || n_tiles * (uint64_t)s.wg > (1ull << 31)) persistent = true;
   if (grid <= 0) grid = 2048;
   if ((uint64_t)grid > n_tiles) grid = (int)n_tiles;
-#define KV_CASE(WW, UU) \
-  if (s.wg == WW && s.U == UU) return launch_wu<WW, UU>(scatter, s.full, a, persistent, grid, stream, start, stop);
+  const int policy = store_policy(variant, scatter);
+#define KV_CASE(WW, UU)                                                                             \
+  if (s.wg == WW && s.U == UU)                                                                      \
+    return policy ? launch_wu<WW, UU, true>(scatter, s.full, a, persistent, grid, stream, start, stop) \
+                  : launch_wu<WW, UU, false>(scatter, s.full, a, persistent, grid, stream, start, stop);
   KV_CASE(256, 1)
   KV_CASE(256, 2)
   KV_CASE(256, 4)
   KV_CASE(256, 8)
   KV_CASE(1024, 1)
   KV_CASE(1024, 2)
-
 #undef KV_CASE
   return hipErrorInvalidValue;
 }

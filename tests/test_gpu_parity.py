@@ -105,7 +105,7 @@ def test_shapes_and_ragged_chunks(harness, L, H, D, B, e, N):
     h.assert_pool_equal()
 
 
-@pytest.mark.parametrize("variant", [0, 1, 2, 3])
+@pytest.mark.parametrize("variant", [0, 1, 2, 3, 4, 7])
 @pytest.mark.parametrize("unroll", [0, 1, 2, 4, 8])
 def test_every_tile_width_and_kernel_variant(harness, unroll, variant):
     shape = synth.KVShape("s", 2, 6, 80, 16, 2, 80, "bf16")  # C = 30720: full for U<=2, ragged for 4, 8
