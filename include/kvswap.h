@@ -121,18 +121,18 @@ int32_t kv_pool_destroy(kv_pool_t* pool);
 /* Section 3.1, Dynamic Block Group allocation.  Returns n_blocks physical ids in
  * out_blocks[n_blocks] (caller-allocated), in as few maximal contiguous runs as the free
  * lists allow; runs shorter than min_run are used only when nothing longer is free.
- * *out_n_runs (may be NULL) receives the number of maximal runs.  Blocks still being read
- * by an unfinished gather are never handed out (Section 3.2, KV cache conflict): if they
- * are needed the call waits for exactly that gather.  KV_ENOMEM_GPU if fewer than
+ * *out_n_runs (may be NULL) receives the number of maximal runs.  Freed blocks that an
+ * unfinished gather still reads or an unfinished scatter still writes are never handed out
+ * (Section 3.2, KV cache conflict): if they are needed the call waits for exactly that work.  KV_ENOMEM_GPU if fewer than
  * n_blocks are free; nothing is allocated then. */
 int32_t alloc_block_group(kv_pool_t* pool, int64_t req, int32_t n_blocks, int32_t min_run,
                           int32_t* out_blocks, int32_t* out_n_runs);
 /* Returns blocks to the free lists (adjacent free runs merge).  Blocks named by a swap_out
- * whose gather has not finished stay unavailable until it has.  Blocks a swap_in is still
- * writing are the caller's to order: free them after kv_wait, or after kv_stream_wait has put
- * the stream that touches them next behind the swap-in (the library's own later swaps into
- * them are ordered by it).  KV_EINVAL if any block is out of range, repeated, or not
- * currently allocated (then nothing is freed). */
+ * whose gather, or by a swap_in whose scatter, has not finished stay unavailable until it
+ * has: the allocator never hands out a block that work of this library still reads or
+ * writes.  (Accesses from the caller's own streams are the caller's to order, with
+ * kv_stream_wait and KV_FLAG_ORDER_COMPUTE.)  KV_EINVAL if any block is out of range,
+ * repeated, or not currently allocated (then nothing is freed). */
 int32_t free_block_group(kv_pool_t* pool, int64_t req, const int32_t* blocks, int32_t n_blocks);
 /* Number of blocks currently free (including those waiting for a gather to finish). */
 int32_t kv_free_blocks(kv_pool_t* pool, int64_t* out_free, int64_t* out_largest_run);

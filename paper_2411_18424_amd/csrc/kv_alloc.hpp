@@ -185,27 +185,30 @@ class BlockGroupAllocator {
     return true;
   }
 
-  // Frees ids.  Ids whose reader sequence number (reader_seq[b]) is beyond done_seq are still
-  // being read by a gather: they are parked and released by reap() once it has finished.
-  void free_ids(const int32_t* ids, int32_t n, const std::vector<uint64_t>& reader_seq,
-                uint64_t done_seq) {
+  // Frees ids.  A block that an unfinished gather still reads (reader_seq[b] > out_done) or an
+  // unfinished scatter still writes (writer_seq[b] > in_done) is parked, and released by
+  // reap() once both have finished; it is never handed out before.
+  void free_ids(const int32_t* ids, int32_t n, const std::vector<uint64_t>& reader_seq, uint64_t out_done,
+                const std::vector<uint64_t>& writer_seq, uint64_t in_done) {
     std::vector<int32_t> v(ids, ids + n);
     std::sort(v.begin(), v.end());
+    auto busy = [&](int32_t b) {
+      return reader_seq[(size_t)b] > out_done || writer_seq[(size_t)b] > in_done;
+    };
     size_t i = 0;
     while (i < v.size()) {
       size_t j = i;
-      uint64_t seq = reader_seq[(size_t)v[i]];
-      bool parked = seq > done_seq;
-      uint64_t max_seq = seq;
-      while (j + 1 < v.size() && v[j + 1] == v[j] + 1 &&
-             ((reader_seq[(size_t)v[j + 1]] > done_seq) == parked)) {
+      const bool parked = busy(v[i]);
+      uint64_t max_out = reader_seq[(size_t)v[i]], max_in = writer_seq[(size_t)v[i]];
+      while (j + 1 < v.size() && v[j + 1] == v[j] + 1 && busy(v[j + 1]) == parked) {
         ++j;
-        max_seq = std::max(max_seq, reader_seq[(size_t)v[j]]);
+        max_out = std::max(max_out, reader_seq[(size_t)v[j]]);
+        max_in = std::max(max_in, writer_seq[(size_t)v[j]]);
       }
       int64_t start = v[i], len = (int64_t)(j - i + 1);
       if (parked) {
         for (int64_t k = 0; k < len; ++k) state_[(size_t)(start + k)] = DRAINING;
-        draining_.push_back({max_seq, start, len});
+        draining_.push_back({max_out, max_in, start, len});
         n_draining_ += len;
       } else {
         for (int64_t k = 0; k < len; ++k) state_[(size_t)(start + k)] = FREE;
@@ -215,12 +218,13 @@ class BlockGroupAllocator {
     }
   }
 
-  // Releases parked runs whose gather (sequence <= done_seq) has finished.
-  void reap(uint64_t done_seq) {
+  // Releases parked runs whose gather (sequence <= out_done) and scatter (<= in_done) have
+  // both finished.
+  void reap(uint64_t out_done, uint64_t in_done) {
     size_t w = 0;
     for (size_t i = 0; i < draining_.size(); ++i) {
       Parked& d = draining_[i];
-      if (d.seq <= done_seq) {
+      if (d.out_seq <= out_done && d.in_seq <= in_done) {
         for (int64_t k = 0; k < d.len; ++k) state_[(size_t)(d.start + k)] = FREE;
         free_.insert(d.start, d.len);
         n_draining_ -= d.len;
@@ -231,25 +235,31 @@ class BlockGroupAllocator {
     draining_.resize(w);
   }
 
-  // Smallest sequence number whose completion would release at least `need` parked blocks
-  // (0 if even all parked blocks are not enough).
-  uint64_t seq_to_release(int64_t need) const {
-    std::vector<std::pair<uint64_t, int64_t>> v;
-    for (const Parked& d : draining_) v.push_back({d.seq, d.len});
-    std::sort(v.begin(), v.end());
+  // The gather and the scatter whose completion would release at least `need` parked blocks,
+  // oldest work first (*out_seq / *in_seq: wait for ops up to these; 0 = none of that kind).
+  // False if even all parked blocks are not enough.
+  bool seqs_to_release(int64_t need, uint64_t* out_seq, uint64_t* in_seq) const {
+    std::vector<const Parked*> v;
+    for (const Parked& d : draining_) v.push_back(&d);
+    std::sort(v.begin(), v.end(), [](const Parked* a, const Parked* b) {
+      return a->out_seq + a->in_seq < b->out_seq + b->in_seq;
+    });
+    *out_seq = *in_seq = 0;
     int64_t got = 0;
-    for (auto& e : v) {
-      got += e.second;
-      if (got >= need) return e.first;
+    for (const Parked* d : v) {
+      *out_seq = std::max(*out_seq, d->out_seq);
+      *in_seq = std::max(*in_seq, d->in_seq);
+      got += d->len;
+      if (got >= need) return true;
     }
-    return 0;
+    return false;
   }
 
   uint8_t state(int64_t b) const { return state_[(size_t)b]; }
 
  private:
   struct Parked {
-    uint64_t seq;
+    uint64_t out_seq, in_seq;  // last gather reading / last scatter writing the run
     int64_t start, len;
   };
   static int32_t count_runs(const std::vector<int32_t>& ids) {

@@ -53,7 +53,7 @@ void reap(kv_pool* p) {
     p->ops_in.clear();
     p->ring_out.live.clear();
     p->ring_in.live.clear();
-    p->alloc.reap(p->pack_done_seq);
+    p->alloc.reap(p->pack_done_seq, p->scat_done_seq);
     return;
   }
   for (auto& o : p->ops_out) {
@@ -94,7 +94,7 @@ void reap(kv_pool* p) {
       r->live.pop_front();
     }
   }
-  p->alloc.reap(p->pack_done_seq);
+  p->alloc.reap(p->pack_done_seq, p->scat_done_seq);
 }
 
 Op* find_op(std::deque<OpRef>& dq, uint64_t seq) {

@@ -215,6 +215,34 @@ int32_t kv_pool_destroy(kv_pool_t* p) {
   return KV_OK;
 }
 
+// Waits (fine-grained, Section 3.2 conflict handling) for exactly the gathers / scatters that
+// still use parked blocks until `need` blocks are free or nothing more can be released.
+static int32_t make_free(kv_pool* p, int64_t need) {
+  reap(p);
+  while (p->alloc.n_free() < need && p->alloc.n_draining() > 0) {
+    uint64_t so = 0, si = 0;
+    p->alloc.seqs_to_release(std::min(need - p->alloc.n_free(), p->alloc.n_draining()), &so, &si);
+    bool waited = false;
+    if (!p->plan) {
+      Op* o = so ? find_op(p->ops_out, so) : nullptr;
+      if (o && o->packed && !o->packed_done) {
+        HIP_TRY(hipEventSynchronize(o->packed));
+        waited = true;
+      }
+      Op* w = si ? find_op(p->ops_in, si) : nullptr;
+      if (w && w->done && !w->all_done) {
+        HIP_TRY(hipEventSynchronize(w->done));
+        waited = true;
+      }
+    }
+    if (waited) p->st.conflict_waits++;
+    int64_t before = p->alloc.n_draining();
+    reap(p);
+    if (p->alloc.n_draining() == before) break;
+  }
+  return KV_OK;
+}
+
 int32_t alloc_block_group(kv_pool_t* p, int64_t req, int32_t n_blocks, int32_t min_run,
                           int32_t* out_blocks, int32_t* out_n_runs) {
   (void)req;
@@ -222,18 +250,12 @@ int32_t alloc_block_group(kv_pool_t* p, int64_t req, int32_t n_blocks, int32_t m
   std::lock_guard<std::mutex> g(p->mu);
   reap(p);
   if (p->alloc.n_free() < n_blocks) {
-    // blocks parked behind an unfinished gather may cover the shortfall: wait for exactly
-    // the gather that releases enough of them (fine-grained conflict synchronisation)
+    // blocks parked behind unfinished work may cover the shortfall: wait for exactly that work
     if (p->alloc.n_free() + p->alloc.n_draining() < n_blocks)
       return fail(KV_ENOMEM_GPU, "need %d blocks, %lld free", n_blocks,
                   (long long)(p->alloc.n_free() + p->alloc.n_draining()));
-    uint64_t seq = p->alloc.seq_to_release(n_blocks - p->alloc.n_free());
-    Op* o = find_op(p->ops_out, seq);
-    if (o && o->packed && !o->packed_done && !p->plan) {
-      HIP_TRY(hipEventSynchronize(o->packed));
-      p->st.conflict_waits++;
-    }
-    reap(p);
+    int32_t rc = make_free(p, n_blocks);
+    if (rc) return rc;
     if (p->alloc.n_free() < n_blocks) return fail(KV_ENOMEM_GPU, "need %d blocks, %lld free", n_blocks, (long long)p->alloc.n_free());
   }
   std::vector<int32_t> ids;
@@ -252,24 +274,7 @@ int32_t free_block_group(kv_pool_t* p, int64_t req, const int32_t* blocks, int32
   reap(p);
   if (!p->alloc.can_free(blocks, n_blocks, &p->free_stamp, &p->free_epoch))
     return fail(KV_EINVAL, "free of a block that is out of range, repeated, or not allocated");
-  p->alloc.free_ids(blocks, n_blocks, p->reader_seq, p->pack_done_seq);
-  return KV_OK;
-}
-
-// Waits (fine-grained) for gathers that still read parked blocks until `need` blocks are free.
-static int32_t make_free(kv_pool* p, int64_t need) {
-  reap(p);
-  while (p->alloc.n_free() < need && p->alloc.n_draining() > 0) {
-    uint64_t seq = p->alloc.seq_to_release(std::min(need - p->alloc.n_free(), p->alloc.n_draining()));
-    Op* o = find_op(p->ops_out, seq);
-    if (o && o->packed && !o->packed_done && !p->plan) {
-      HIP_TRY(hipEventSynchronize(o->packed));
-      p->st.conflict_waits++;
-    }
-    int64_t before = p->alloc.n_draining();
-    reap(p);
-    if (p->alloc.n_draining() == before) break;
-  }
+  p->alloc.free_ids(blocks, n_blocks, p->reader_seq, p->pack_done_seq, p->writer_seq, p->scat_done_seq);
   return KV_OK;
 }
 
@@ -317,7 +322,7 @@ int32_t kv_bg_close(kv_pool_t* p, int64_t req) {
   std::vector<int32_t> ids;
   p->groups.all_blocks(req, &ids);
   p->groups.forget(req);
-  p->alloc.free_ids(ids.data(), (int32_t)ids.size(), p->reader_seq, p->pack_done_seq);
+  p->alloc.free_ids(ids.data(), (int32_t)ids.size(), p->reader_seq, p->pack_done_seq, p->writer_seq, p->scat_done_seq);
   return KV_OK;
 }
 

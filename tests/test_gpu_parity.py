@@ -287,6 +287,37 @@ def test_allocator_driven_flow(harness):
     assert free + chk.n_used() == shape.n_blocks
 
 
+def test_blocks_freed_during_a_swap_in_are_held_back(harness):
+    """A request is resumed and its blocks are given up at once (it is preempted again before
+    anything ran, or it ends): the allocator must not hand them out while the scatter still
+    writes them, or the next owner's KV would be overwritten."""
+    import torch
+    shape = synth.KVShape("s", 8, 8, 128, 16, 2, 1024, "bf16")  # R = 512 KiB, 512 MiB pool
+    h = harness(shape, cfg=33, host_bytes=512 * MiB, fill="random")
+    ids, _ = h.pool.alloc_block_group(0, 600, 8)
+    h.pool.swap_out(0, ids)
+    h.oracle.swap_out(0, ids)
+    h.pool.kv_wait(0)
+    h.pool.free_block_group(0, ids)
+    stream = torch.cuda.Stream()
+    view = h.gpu.view(shape.P, shape.n_blocks, shape.C)
+    for rep in range(3):
+        ids, _ = h.pool.alloc_block_group(0, 600, 8)
+        h.pool.swap_in(0, ids)                 # 300 MiB over the link: several milliseconds
+        h.pool.free_block_group(0, ids)        # ... and the blocks are given up at once
+        other, _ = h.pool.alloc_block_group(1, 900, 8)   # needs most of them back
+        idx = torch.from_numpy(other.astype(np.int64)).to(h.dev)
+        with torch.cuda.stream(stream):
+            view[:, idx, :] = 0x30 + rep       # the next owner writes its KV right away
+        stream.synchronize()
+        h.oracle.swap_in(0, ids)
+        h.oracle.G[:, other.astype(np.int64), :] = 0x30 + rep
+        h.pool.kv_wait_all()
+        h.assert_pool_equal()
+        h.pool.free_block_group(1, other)
+    assert h.pool.kv_stats()["conflict_waits"] >= 3
+
+
 def test_empty_request_and_queries(harness):
     h = harness(synth.TINY, cfg=11)
     h.pool.swap_out(0, np.zeros(0, np.int32))

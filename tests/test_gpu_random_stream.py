@@ -14,6 +14,8 @@ pytestmark = pytest.mark.gpu
 
 KiB, MiB = 1 << 10, 1 << 20
 SHAPE = synth.KVShape("stream", 2, 2, 64, 16, 2, 512, "fp16")  # C = 4 KiB, R = 16 KiB, 8 MiB pool
+# transfers that take milliseconds, so calls really overlap: C = 32 KiB, R = 512 KiB, 2 GiB pool
+BIG = synth.KVShape("stream_big", 8, 8, 128, 16, 2, 4096, "bf16")
 
 ORDER_COMPUTE, FOUR_STREAMS, MAPPED_SWAP_IN, MAPPED_SWAP_OUT = 4, 8, 16, 64
 
@@ -21,10 +23,12 @@ ORDER_COMPUTE, FOUR_STREAMS, MAPPED_SWAP_IN, MAPPED_SWAP_OUT = 4, 8, 16, 64
 class Loop:
     """The serving loop's own state: which requests run (and where), which are swapped out."""
 
-    def __init__(self, h, stream, rng, n_req):
+    def __init__(self, h, stream, rng, n_req, max_blocks=40):
         self.h, self.stream, self.rng = h, stream, rng
-        self.chk = AllocChecker(SHAPE.n_blocks)
-        self.view = h.gpu.view(SHAPE.P, SHAPE.n_blocks, SHAPE.C)
+        self.shape = h.shape
+        self.max_blocks = max_blocks
+        self.chk = AllocChecker(self.shape.n_blocks)
+        self.view = h.gpu.view(self.shape.P, self.shape.n_blocks, self.shape.C)
         self.table = {}      # running request -> physical table
         self.tokens = {}     # every live request -> tokens so far
         self.dirty = {}      # running request -> blocks written since its last swap-out
@@ -34,18 +38,36 @@ class Loop:
         self.next_id = n_req
         self.tight = False   # host arena smaller than the swapped set can get
         self.refused = 0
+        # The oracle replays the calls later, at the checkpoint: nothing slow may sit between
+        # two library calls, or each would have finished before the next one is made.
+        self.pending = []
+        self.log = []        # (request, what) in program order, for failure reports
+        # new KV comes from a resident base of 256 random blocks (same bytes on both sides)
+        torch = h.torch
+        self.base_host = rng.integers(0, 256, size=(self.shape.P, 256, self.shape.C), dtype=np.uint8)
+        self.base_dev = torch.from_numpy(self.base_host).to(h.dev)
+        torch.cuda.synchronize()
+
+    def payload(self, n):
+        """New KV of n blocks: which base blocks they copy."""
+        return self.rng.integers(0, 256, size=n)
 
     # -- both sides get the same bytes; the GPU write goes on the compute stream, unsynchronised
-    def write(self, blocks, payload):
+    def write(self, blocks, sel):
         torch = self.h.torch
         blocks = np.asarray(blocks, dtype=np.int64)
         if blocks.size == 0:
             return
-        planes = np.ascontiguousarray(payload.transpose(1, 0, 2))
-        self.h.oracle.G[:, blocks, :] = planes
+        sel = np.asarray(sel, dtype=np.int64)
+        G, base = self.h.oracle.G, self.base_host
+
+        def on_oracle():
+            G[:, blocks, :] = base[:, sel, :]
+        self.pending.append(on_oracle)
         with torch.cuda.stream(self.stream):
-            idx = torch.from_numpy(blocks).to(self.h.dev, non_blocking=False)
-            self.view[:, idx, :] = torch.from_numpy(planes).to(self.h.dev)
+            idx = torch.from_numpy(blocks).to(self.h.dev)
+            src = torch.from_numpy(sel).to(self.h.dev)
+            self.view[:, idx, :] = self.base_dev[:, src, :]
 
     def alloc(self, req, n):
         free, _ = self.h.pool.kv_free_blocks()
@@ -63,19 +85,20 @@ class Loop:
     def start(self):
         if not self.free_ids:
             return
-        n = int(self.rng.integers(1, 41))
+        n = int(self.rng.integers(1, self.max_blocks + 1))
         req = self.free_ids[-1]
         ids = self.alloc(req, n)
         if ids is None:
             return
         self.free_ids.pop()
         self.table[req] = ids
-        self.tokens[req] = n * SHAPE.block_size - int(self.rng.integers(0, SHAPE.block_size))
+        self.tokens[req] = n * self.shape.block_size - int(self.rng.integers(0, self.shape.block_size))
         self.dirty[req] = np.ones(n, np.uint8)
-        self.write(ids, synth.fresh_tokens(self.rng, SHAPE, n))
+        self.write(ids, self.payload(n))
+        self.note(req, "start %d blocks %s.." % (n, ids[:4].tolist()))
 
     def grow(self, req):
-        B = SHAPE.block_size
+        B = self.shape.block_size
         new_tokens = int(self.rng.integers(1, 6 * B))
         n_old = len(self.table[req])
         mask = synth.turn_dirty_mask(n_old, self.tokens[req], new_tokens, B)
@@ -88,10 +111,11 @@ class Loop:
             self.h.pool.kv_stream_wait(req, self.stream.cuda_stream)
         table = np.concatenate([self.table[req], ids]).astype(np.int32)
         touched = np.flatnonzero(mask)
-        self.write(table[touched], synth.fresh_tokens(self.rng, SHAPE, len(touched)))
+        self.write(table[touched], self.payload(len(touched)))
         self.table[req] = table
         self.tokens[req] += new_tokens
         self.dirty[req] = np.concatenate([self.dirty[req], np.zeros(extra, np.uint8)]) | mask
+        self.note(req, "grow +%d blocks, touched %s" % (extra, table[touched].tolist()[:6]))
 
     def preempt(self, req):
         table, dirty = self.table[req], self.dirty[req]
@@ -107,10 +131,15 @@ class Loop:
             assert self.tight and err.status == self.h.kv.KV_ENOMEM_HOST, err
             self.refused += 1
             return
+        oracle = self.h.oracle
         if delta:
-            assert moved == len(self.h.oracle.swap_out_delta(req, table, dirty))
+            def on_oracle(moved=moved, table=table.copy(), dirty=dirty.copy()):
+                assert moved == len(oracle.swap_out_delta(req, table, dirty))
         else:
-            self.h.oracle.swap_out(req, table)
+            def on_oracle(table=table.copy()):
+                oracle.swap_out(req, table)
+        self.pending.append(on_oracle)
+        self.note(req, "preempt %s n=%d" % ("delta" if delta else "full", len(table)))
         del self.table[req], self.dirty[req]
         self.has_image.add(req)
         self.swapped.add(req)
@@ -122,7 +151,8 @@ class Loop:
         if ids is None:
             return
         self.h.pool.swap_in(req, ids)
-        self.h.oracle.swap_in(req, ids)
+        self.pending.append(lambda ids=ids.copy(): self.h.oracle.swap_in(req, ids))
+        self.note(req, "resume into %s.." % ids[:4].tolist())
         self.swapped.discard(req)
         self.table[req] = ids
         self.dirty[req] = np.zeros(n, np.uint8)
@@ -131,7 +161,8 @@ class Loop:
         n, _ = self.h.pool.kv_host_len(req)
         mask = synth.random_mask(self.rng, n, 0.3)
         self.h.pool.kv_host_invalidate(req, mask)
-        self.h.oracle.host_invalidate(req, mask)
+        self.pending.append(lambda: self.h.oracle.host_invalidate(req, mask))
+        self.note(req, "contaminate %d" % int(mask.sum()))
 
     def finish(self, req):
         """A request ends: its blocks and its host copy go back."""
@@ -142,19 +173,24 @@ class Loop:
             self.dirty.pop(req)
         if req in self.has_image:
             self.h.pool.kv_host_release(req)
-            self.h.oracle.host_release(req)
+            self.pending.append(lambda: self.h.oracle.host_release(req))
             self.has_image.discard(req)
         self.swapped.discard(req)
         del self.tokens[req]
+        self.note(req, "finish")
         self.free_ids.append(self.next_id)  # a fresh id: nothing of the old request may linger
         self.next_id += 1
 
     def drop_host_copy(self, req):
         """A running request loses its whole host copy (memory pressure): next swap-out is full."""
         self.h.pool.kv_host_release(req)
-        self.h.oracle.host_release(req)
+        self.pending.append(lambda: self.h.oracle.host_release(req))
         self.has_image.discard(req)
         self.dirty[req][:] = 1
+        self.note(req, "drop host copy")
+
+    def note(self, req, what):
+        self.log.append((req, what))
 
     def step(self):
         r = self.rng.random()
@@ -182,17 +218,48 @@ class Loop:
         else:
             self.start()
 
+    def diagnose(self):
+        """Who owns the blocks that differ, what was done to them, and what they hold instead."""
+        got, want = self.h.gpu_pool(), self.h.oracle.G
+        bad = np.flatnonzero((got != want).any(axis=(0, 2)))
+        owner = {int(b): q for q, t in self.table.items() for b in t}
+        lines = ["%d blocks differ: %s" % (bad.size, bad[:24].tolist())]
+        owners = sorted({owner.get(int(b), -1) for b in bad})
+        lines.append("owners (-1 = free): %s" % owners)
+        for q in owners:
+            if q >= 0:
+                lines.append("request %d table %s" % (q, self.table[q].tolist()))
+                lines.append("  history: " + "; ".join(w for r, w in self.log if r == q))
+        b = int(bad[0])
+        planes_bad = np.flatnonzero((got[:, b] != want[:, b]).any(axis=1))
+        lines.append("block %d: planes that differ %s" % (b, planes_bad.tolist()[:16]))
+        p0 = int(planes_bad[0])
+        holds = [s for s in range(256) if np.array_equal(got[p0, b], self.base_host[p0, s])]
+        lines.append("  GPU holds base block(s) %s of that plane" % holds)
+        wants = [s for s in range(256) if np.array_equal(want[p0, b], self.base_host[p0, s])]
+        lines.append("  oracle holds base block(s) %s" % wants)
+        same_as = [int(x) for x in range(want.shape[1]) if np.array_equal(got[p0, b], want[p0, x])][:8]
+        lines.append("  GPU bytes equal the oracle's block(s) %s of that plane" % same_as)
+        lines.append("last 30 calls: " + "; ".join("%d %s" % rw for rw in self.log[-30:]))
+        return "\n".join(lines)
+
     def checkpoint(self):
+        for fn in self.pending:  # the oracle catches up, in program order
+            fn()
+        self.pending.clear()
         self.h.pool.kv_wait_all()
         self.stream.synchronize()
-        self.h.assert_pool_equal()
+        try:
+            self.h.assert_pool_equal()
+        except AssertionError as err:
+            raise AssertionError(str(err) + "\n" + self.diagnose()) from None
         for req in sorted(self.has_image):
             self.h.assert_image_equal(req)
         st = self.h.pool.kv_stats()
         assert st["bytes_out"] == self.h.oracle.bytes_out
         assert st["bytes_in"] == self.h.oracle.bytes_in
         free, _ = self.h.pool.kv_free_blocks()
-        assert free + self.chk.n_used() == SHAPE.n_blocks
+        assert free + self.chk.n_used() == self.shape.n_blocks
 
 
 CASES = {
@@ -230,5 +297,36 @@ def test_random_serving_loop_matches_oracle(case):
         loop.checkpoint()
         assert h.oracle.bytes_out > 50 * SHAPE.R and h.oracle.bytes_in > 50 * SHAPE.R
         assert (loop.refused > 0) == loop.tight
+    finally:
+        h.close()
+
+
+BIG_CASES = {
+    # rings smaller than most requests: pieces wrap, gathers interleave with copies
+    "small_rings": (201, ORDER_COMPUTE, dict(staging_out_bytes=48 * MiB, staging_in_bytes=24 * MiB,
+                                            max_piece_bytes=8 * MiB, copy_chunk_bytes=4 * MiB)),
+    "four_streams": (202, ORDER_COMPUTE | FOUR_STREAMS, dict(staging_out_bytes=256 * MiB, staging_in_bytes=64 * MiB)),
+    "mapped_both_ways": (203, ORDER_COMPUTE | MAPPED_SWAP_IN | MAPPED_SWAP_OUT, dict(mapped_out_max_blocks=64)),
+}
+
+
+@pytest.mark.parametrize("case", sorted(BIG_CASES))
+def test_random_serving_loop_with_millisecond_transfers(case):
+    """The same loop with requests of up to 100 MiB: swaps take milliseconds, so unsynchronised
+    calls overlap on the device for real and ordering mistakes would show in the bytes."""
+    import torch
+    from gpu_util import Harness
+    seed, flags, kw = BIG_CASES[case]
+    stream = torch.cuda.Stream()
+    h = Harness(BIG, seed, 3 * 1024 * MiB, fill="random", flags=flags, compute_stream=stream.cuda_stream,
+                host_slack_blocks=8, **kw)
+    try:
+        loop = Loop(h, stream, synth.rng_for(seed), n_req=12, max_blocks=200)
+        for i in range(240):
+            loop.step()
+            if i % 80 == 79:
+                loop.checkpoint()
+        assert h.oracle.bytes_out > 2000 * BIG.R and h.oracle.bytes_in > 1000 * BIG.R
+        assert h.pool.kv_stats()["conflict_waits"] > 0
     finally:
         h.close()
