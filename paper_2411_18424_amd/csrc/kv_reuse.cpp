@@ -307,13 +307,14 @@ int32_t do_swap_in(kv_pool* p, std::vector<InItem>& items, int32_t* out_n_moved,
   if ((rc = new_op(p, false, &op))) return rc;
   std::vector<Move> mv;
   std::vector<hipEvent_t> pre_copy, pre_scat;
-  uint64_t max_reader = 0;
+  uint64_t max_reader = 0, max_writer = 0;
   for (InItem& it : items) {
     Req& q = p->reqs[it.req];
     for (int32_t j = 0; j < it.n; ++j) {
       if (it.resident && it.resident[j]) continue;
       int32_t b = it.table[j];
       mv.push_back({q.img.rec[(size_t)j] * p->R, b});
+      max_writer = std::max(max_writer, p->writer_seq[(size_t)b]);
       p->writer_seq[(size_t)b] = op->seq;
       max_reader = std::max(max_reader, p->reader_seq[(size_t)b]);
     }
@@ -328,6 +329,12 @@ int32_t do_swap_in(kv_pool* p, std::vector<InItem>& items, int32_t* out_n_moved,
         p->st.conflict_waits++;
       }
     }
+  }
+  if (max_writer > p->scat_done_seq) {
+    // an earlier swap-in into these blocks is still in flight: write after it, whatever
+    // stream it runs on (the paths of this library use more than one)
+    if (Op* w = find_op(p->ops_in, max_writer))
+      if (w->done) pre_scat.push_back(w->done);
   }
   if (out_n_moved) *out_n_moved = (int32_t)mv.size();
   if (direct) {

@@ -318,6 +318,31 @@ def test_blocks_freed_during_a_swap_in_are_held_back(harness):
     assert h.pool.kv_stats()["conflict_waits"] >= 3
 
 
+@pytest.mark.parametrize("flags", [0, 8], ids=["two_streams", "four_streams"])
+def test_swap_ins_into_the_same_blocks_land_in_call_order(harness, flags):
+    """Raw tables, no allocator in between: two requests are swapped in to the same blocks by
+    different paths (staged scatter, then 2-D copies on the copy stream); the later call wins."""
+    shape = synth.KVShape("s", 8, 8, 128, 16, 2, 512, "bf16")  # R = 512 KiB
+    h = harness(shape, cfg=34, host_bytes=512 * MiB, fill="random", flags=flags)
+    rng = synth.rng_for(34)
+    ta, tb, target = (rng.permutation(512)[:200].astype(np.int32) for _ in range(3))
+    for r, t in ((0, ta), (1, tb)):
+        h.pool.swap_out(r, t)
+        h.oracle.swap_out(r, t)
+    h.pool.kv_wait_all()
+    for rep in range(3):
+        h.pool.swap_in(0, target)
+        h.pool.swap_in_direct(1, target[::-1].copy())
+        h.pool.swap_in(0, target)
+        h.pool.swap_in_direct(1, target)
+        h.oracle.swap_in(0, target)
+        h.oracle.swap_in(1, target[::-1].copy())
+        h.oracle.swap_in(0, target)
+        h.oracle.swap_in(1, target)
+        h.pool.kv_wait_all()
+        h.assert_pool_equal()
+
+
 def test_empty_request_and_queries(harness):
     h = harness(synth.TINY, cfg=11)
     h.pool.swap_out(0, np.zeros(0, np.int32))
