@@ -33,6 +33,7 @@ class Loop:
         self.tokens = {}     # every live request -> tokens so far
         self.dirty = {}      # running request -> blocks written since its last swap-out
         self.swapped = set()
+        self.kept = {}       # swapped-out request -> its blocks that stayed on the GPU
         self.has_image = set()
         self.free_ids = list(range(n_req))
         self.next_id = n_req
@@ -143,16 +144,36 @@ class Loop:
         del self.table[req], self.dirty[req]
         self.has_image.add(req)
         self.swapped.add(req)
-        self.free(req, table)  # right away: the allocator holds them back until the gather is done
+        # sometimes the first blocks stay on the GPU (a partly resident request); the rest is
+        # freed right away: the allocator holds them back until the gather is done
+        keep = int(self.rng.integers(0, len(table))) if self.rng.random() < 0.3 else 0
+        self.kept[req] = table[:keep]
+        self.free(req, table[keep:])
 
     def resume(self, req):
         n, _ = self.h.pool.kv_host_len(req)
-        ids = self.alloc(req, n)
-        if ids is None:
+        kept = self.kept[req]
+        rest = self.alloc(req, n - len(kept)) if n > len(kept) else np.zeros(0, np.int32)
+        if rest is None:
             return
-        self.h.pool.swap_in(req, ids)
-        self.pending.append(lambda ids=ids.copy(): self.h.oracle.swap_in(req, ids))
-        self.note(req, "resume into %s.." % ids[:4].tolist())
+        del self.kept[req]
+        ids = np.concatenate([kept, rest]).astype(np.int32)
+        resident = np.zeros(n, np.uint8)
+        resident[:len(kept)] = 1
+        how = int(self.rng.integers(0, 3))
+        if len(kept):
+            moved = self.h.pool.swap_in_delta(req, ids, resident)
+        elif how == 0:
+            moved = self.h.pool.swap_in_layerwise(req, ids, int(self.rng.integers(1, self.shape.n_layers + 1)))
+        else:
+            self.h.pool.swap_in(req, ids)
+            moved = n
+        oracle = self.h.oracle
+
+        def on_oracle(ids=ids.copy(), moved=moved):
+            assert moved == len(oracle.swap_in(req, ids, resident=resident))
+        self.pending.append(on_oracle)
+        self.note(req, "resume (%d kept) into %s.." % (len(kept), ids[:4].tolist()))
         self.swapped.discard(req)
         self.table[req] = ids
         self.dirty[req] = np.zeros(n, np.uint8)
@@ -176,6 +197,8 @@ class Loop:
             self.pending.append(lambda: self.h.oracle.host_release(req))
             self.has_image.discard(req)
         self.swapped.discard(req)
+        if req in self.kept:
+            self.free(req, self.kept.pop(req))
         del self.tokens[req]
         self.note(req, "finish")
         self.free_ids.append(self.next_id)  # a fresh id: nothing of the old request may linger
