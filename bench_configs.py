@@ -305,6 +305,31 @@ def config5(args):
                                    "out_gbps": round(payload / (t1 - t0) / 1e9, 2),
                                    "in_gbps": round(payload / (t2 - t1) / 1e9, 2)}
         out["run_%d" % run] = res
+    # the paper's argument in one table: rate of per-group copies against the length of the
+    # groups (20 blocks is the average granularity the paper reports for its block groups);
+    # the packed path is flat across all of them
+    sweep = {}
+    for run in (4, 20, 64, 256, 2048):
+        rng = synth.rng_for(5, stream=1000 + run)
+        ta, tb = synth.deal_tables(rng, s.n_blocks, [2048, 2048], run=run)
+        t0 = time.perf_counter()
+        pool.swap_out_direct(98, ta, False)
+        pool.kv_wait(98)
+        t1 = time.perf_counter()
+        pool.swap_in_direct(98, tb, False)
+        pool.kv_wait(98)
+        t2 = time.perf_counter()
+        pool.kv_host_release(98)
+        t3 = time.perf_counter()
+        pool.swap_out(97, ta)
+        pool.kv_wait(97)
+        t4 = time.perf_counter()
+        pool.kv_host_release(97)
+        sweep["run_%d" % run] = {"copy_KiB": run * s.C // 1024,
+                                 "direct_out_gbps": round(payload / (t1 - t0) / 1e9, 2),
+                                 "direct_in_gbps": round(payload / (t2 - t1) / 1e9, 2),
+                                 "packed_out_gbps": round(payload / (t4 - t3) / 1e9, 2)}
+    out["direct_by_group_length"] = sweep
     pool.kv_pool_destroy()
     out["value"] = round(2 * payload / ((out["run_16"]["out_ms"] + out["run_16"]["in_ms"]) * 1e-3) / 1e9, 3)
     return out
