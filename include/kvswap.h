@@ -101,8 +101,10 @@ typedef struct {
                                increment (Section 3.3 adjacent preallocation); <0 = default 32 */
   int32_t gather_grid;      /* workgroups per launch of the persistent pack variant; 0 = default */
   int32_t tile_unroll;      /* 16-byte vectors per lane per tile (1,2,4,8); 0 = from chunk size */
-  int32_t pack_variant;     /* 0 = one tile per workgroup, 3-D grid, 256 lanes (default); 1 = persistent
-                               grid-stride workgroups with the block table in LDS; 2 = same as 0;
+  int32_t pack_variant;     /* 0 = one tile per workgroup, 256 lanes, tiles in XCD-aware order for
+                               launches of 64 blocks or more (default); 2 = the same kernel always
+                               in plain 3-D grid order; 1 = persistent
+                               grid-stride workgroups with the block table in LDS;
                                3 = tile kernel with 1024 lanes; 4..7 = as 0 with the store cache
                                policy forced (bit 0: gather, bit 1: scatter stores at agent scope),
                                for comparison */

@@ -43,9 +43,11 @@ struct KvMappedArgs {
 hipError_t kv_launch_mapped(bool to_host, const KvMappedArgs& a, int grid, hipStream_t stream,
                             hipEvent_t start, hipEvent_t stop);
 
-#define KV_PACK_TILE 0        // one tile per workgroup, 3-D grid, 256 lanes (default)
+#define KV_PACK_TILE 0        // one tile per workgroup, 256 lanes; XCD-aware order for launches of
+                              // KV_XCD_MIN_BLOCKS blocks or more, 3-D grid below (default)
 #define KV_PACK_PERSISTENT 1  // grid-stride loop, block table staged in LDS, 256 lanes
-#define KV_PACK_TILE_256 2    // tile kernel, 256 lanes
+#define KV_PACK_TILE_256 2    // tile kernel, 256 lanes, always the plain 3-D grid
+#define KV_XCD_MIN_BLOCKS 64  // smaller launches would leave XCDs without work in that order
 #define KV_PACK_TILE_1024 3   // tile kernel, 1024 lanes
 
 // unroll: 16-byte vectors per lane per tile (1, 2, 4 or 8); 0 picks from the chunk size.

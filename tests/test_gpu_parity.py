@@ -122,6 +122,26 @@ def test_every_tile_width_and_kernel_variant(harness, unroll, variant):
     h.assert_pool_equal()
 
 
+@pytest.mark.parametrize("m", [64, 65, 79, 80, 111])
+@pytest.mark.parametrize("L,H,D", [(2, 4, 64), (3, 3, 40), (1, 40, 128)])  # C = 8 KiB, 3840 B, 160 KiB
+def test_xcd_aware_order_with_short_last_groups(harness, L, H, D, m):
+    """Launches of 64 blocks or more walk the tiles in XCD-aware order (groups of 16 blocks);
+    block counts that are not a multiple of 16 leave the last group short."""
+    shape = synth.KVShape("s", L, H, D, 16, 2, 160, "fp16")
+    for variant in (0, 2):  # XCD-aware order, plain 3-D grid
+        h = harness(shape, cfg=35, fill="random", pack_variant=variant, host_bytes=128 * MiB)
+        rng = synth.rng_for(35, stream=m)
+        t = rng.permutation(160)[:m].astype(np.int32)
+        t2 = rng.permutation(160)[:m].astype(np.int32)
+        h.pool.swap_out(0, t)
+        h.oracle.swap_out(0, t)
+        h.assert_image_equal(0)
+        h.pool.swap_in(0, t2)
+        h.oracle.swap_in(0, t2)
+        h.pool.kv_wait_all()
+        h.assert_pool_equal()
+
+
 def test_ring_wraps_when_request_exceeds_staging(harness):
     shape = synth.TINY
     # rings of 7 block records, pieces of 3: a 16-block request wraps the ring twice and
