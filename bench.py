@@ -306,7 +306,7 @@ def main() -> int:
         },
         "roofline": {
             "bound": "hbm",
-            "kernel": "kv_pack_kernel (gather)",
+            "kernel": "kv_pack_xcd_kernel, gather direction (kv_pack_tile_kernel below 64 blocks per launch)",
             "achieved": round(gather_gbps, 1),
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
