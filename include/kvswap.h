@@ -228,7 +228,8 @@ int32_t kv_wait_packed(kv_pool_t* pool, int64_t req);         /* until the last 
                                                                  finished: GPU blocks reusable */
 int32_t kv_stream_wait(kv_pool_t* pool, int64_t req, void* stream); /* make a hipStream_t wait (on the
                                                                  device) for req's last op */
-int32_t kv_wait_all(kv_pool_t* pool);
+int32_t kv_wait_all(kv_pool_t* pool);  /* until everything enqueued before the call is done; other
+                                          threads may keep calling meanwhile */
 
 /* Reuse map (Section 3.3). */
 /* The image of a request is a list of extents of the pinned arena: one extent (with slack

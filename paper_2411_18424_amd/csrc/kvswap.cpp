@@ -541,9 +541,16 @@ int32_t kv_wait_layer(kv_pool_t* p, int64_t req, int32_t layer) {
 
 int32_t kv_wait_all(kv_pool_t* p) {
   if (!p) return fail(KV_EINVAL, "null pool");
-  std::lock_guard<std::mutex> g(p->mu);
+  std::unique_lock<std::mutex> lk(p->mu);
   if (!p->plan) {
-    for (hipStream_t s : {p->s_pack, p->s_d2h, p->s_h2d, p->s_scat}) HIP_TRY(hipStreamSynchronize(s));
+    // wait without the lock: other threads may keep enqueueing (their work is not waited for)
+    const hipStream_t streams[4] = {p->s_pack, p->s_d2h, p->s_h2d, p->s_scat};
+    lk.unlock();
+    hipError_t e = hipSuccess;
+    for (hipStream_t s : streams)
+      if (e == hipSuccess) e = hipStreamSynchronize(s);
+    lk.lock();
+    if (e != hipSuccess) return fail(KV_EHIP, "hipStreamSynchronize: %s", hipGetErrorString(e));
   }
   reap(p);
   return KV_OK;
