@@ -178,6 +178,45 @@ class Loop:
         self.table[req] = ids
         self.dirty[req] = np.zeros(n, np.uint8)
 
+    def preempt_batch(self, reqs):
+        """Several victims leave in one call (full swap-outs; all or none on a full arena)."""
+        tables = [self.table[q] for q in reqs]
+        try:
+            self.h.pool.swap_out_batch(reqs, tables)
+        except self.h.kv.KVError as err:
+            assert self.tight and err.status == self.h.kv.KV_ENOMEM_HOST, err
+            self.refused += 1
+            return
+        oracle = self.h.oracle
+        for q, t in zip(reqs, tables):
+            self.pending.append(lambda q=q, t=t.copy(): oracle.swap_out(q, t))
+            self.note(q, "preempt in a batch n=%d" % len(t))
+            del self.table[q], self.dirty[q]
+            self.has_image.add(q)
+            self.swapped.add(q)
+            self.kept[q] = t[:0]
+            self.free(q, t)
+
+    def resume_batch(self, reqs):
+        tables = []
+        for q in reqs:
+            n, _ = self.h.pool.kv_host_len(q)
+            ids = self.alloc(q, n)
+            if ids is None:
+                for q2, t2 in zip(reqs, tables):
+                    self.free(q2, t2)
+                return
+            tables.append(ids)
+        self.h.pool.swap_in_batch(reqs, tables)
+        oracle = self.h.oracle
+        for q, t in zip(reqs, tables):
+            self.pending.append(lambda q=q, t=t.copy(): oracle.swap_in(q, t))
+            self.note(q, "resume in a batch into %s.." % t[:4].tolist())
+            del self.kept[q]
+            self.swapped.discard(q)
+            self.table[q] = t
+            self.dirty[q] = np.zeros(len(t), np.uint8)
+
     def contaminate(self, req):
         n, _ = self.h.pool.kv_host_len(req)
         mask = synth.random_mask(self.rng, n, 0.3)
@@ -224,10 +263,17 @@ class Loop:
             self.start()
         elif r < 0.35 and running:
             self.grow(pick(running))
-        elif r < 0.60 and running:
+        elif r < 0.55 and running:
             self.preempt(pick(running))
-        elif r < 0.85 and swapped:
+        elif r < 0.60 and len(running) >= 3:
+            k = int(self.rng.integers(2, 4))
+            self.preempt_batch([int(q) for q in self.rng.choice(running, size=k, replace=False)])
+        elif r < 0.80 and swapped:
             self.resume(pick(swapped))
+        elif r < 0.85 and swapped:
+            whole = [q for q in swapped if len(self.kept[q]) == 0]   # nothing of them stayed on the GPU
+            if len(whole) >= 2:
+                self.resume_batch([int(q) for q in self.rng.choice(whole, size=2, replace=False)])
         elif r < 0.93 and running:
             # only a request that is back on the GPU can lose host blocks (Section 3.3): part of
             # the copy (contamination) or all of it
