@@ -240,7 +240,8 @@ int32_t kv_wait_all(kv_pool_t* pool);  /* until everything enqueued before the c
  * [P][C] of logical block j, i.e. its bytes start at *arena_base + record_index[j]*R
  * (-1: the block has no record because its space was reclaimed; its host_valid bit is 0).
  * Consecutive logical blocks are adjacent inside an extent.  Valid until the image is
- * released or rebuilt by a full swap_out; wait for the request before reading the bytes. */
+ * released or rebuilt by a full swap_out; wait for the request before reading the bytes.
+ * In a KV_FLAG_PLAN_ONLY pool *arena_base is NULL (there are no bytes), the indices are real. */
 int32_t kv_host_len(kv_pool_t* pool, int64_t req, int32_t* n_blocks, int32_t* n_extents);
 int32_t kv_host_blocks(kv_pool_t* pool, int64_t req, const void** arena_base, int64_t* record_index,
                        int32_t n);

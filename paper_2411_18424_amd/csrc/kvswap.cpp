@@ -569,12 +569,11 @@ int32_t kv_host_len(kv_pool_t* p, int64_t req, int32_t* n_blocks, int32_t* n_ext
 int32_t kv_host_blocks(kv_pool_t* p, int64_t req, const void** arena_base, int64_t* record_index, int32_t n) {
   if (!p || (n > 0 && !record_index)) return fail(KV_EINVAL, "null argument");
   std::lock_guard<std::mutex> g(p->mu);
-  if (p->plan) return fail(KV_ENODEV, "plan-only pool holds no bytes");
   auto f = p->reqs.find(req);
   if (f == p->reqs.end() || !f->second.has_image) return fail(KV_ENOENT, "request %lld has no host copy", (long long)req);
   const Image& im = f->second.img;
   if (n != im.n) return fail(KV_EINVAL, "asked for %d blocks, host image has %d", n, im.n);
-  if (arena_base) *arena_base = p->host;
+  if (arena_base) *arena_base = p->host;  // null in a plan-only pool: the records exist as bookkeeping only
   for (int32_t j = 0; j < n; ++j) record_index[j] = im.rec[(size_t)j];
   return KV_OK;
 }

@@ -365,6 +365,8 @@ class KVPool:
         """uint8 [n][P][C] over the host image: a zero-copy view of the pinned arena when the
         image is one extent, else a gathered copy (reading aid for tests and tools)."""
         base, idx = self.kv_host_blocks(req)
+        if base is None:
+            raise KVError(KV_ENODEV, "plan-only pool holds no bytes")
         n = idx.size
         if n == 0:
             return np.zeros((0, self.P, self.C), dtype=np.uint8)

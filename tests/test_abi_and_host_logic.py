@@ -534,6 +534,54 @@ def test_host_eviction_by_priority_and_recency(kv):
         assert p.swap_in_delta(2, t[120:128], res) == 8 - lost2
 
 
+def test_host_records_never_overlap_under_growth_and_eviction(kv):
+    """Arena invariants over a random multi-request history with growth, release and eviction:
+    every record belongs to at most one logical block of one image, lies inside the arena, and
+    a block has a record exactly while it can be valid."""
+    shape = synth.KVShape("s", 1, 1, 8, 1, 2, 4096, "fp16")
+    arena = 600
+    p = plan_pool(kv, shape, host_blocks=arena, flags_extra=kv.KV_FLAG_HOST_EVICT, host_slack_blocks=5)
+    rng = synth.rng_for(41)
+    live = {}
+    for step in range(600):
+        r = int(rng.integers(0, 12))
+        kind = int(rng.integers(0, 6))
+        try:
+            if r not in live or kind == 0:
+                n = int(rng.integers(1, 90))
+                p.kv_host_set_priority(r, int(rng.integers(0, 3))) if r in live else None
+                p.swap_out(r, rng.permutation(4096)[:n].astype(np.int32))
+                live[r] = n
+            elif kind in (1, 2, 3):
+                n = live[r] + int(rng.integers(0, 25))
+                p.swap_out_delta(r, rng.permutation(4096)[:n].astype(np.int32), synth.random_mask(rng, n, 0.2))
+                live[r] = n
+            elif kind == 4:
+                p.kv_host_release(r)
+                del live[r]
+            else:
+                p.kv_host_set_priority(r, int(rng.integers(0, 3)))
+        except kv.KVError as err:
+            assert err.status == kv.KV_ENOMEM_HOST, err      # refused calls change nothing
+        seen = {}
+        for q, n in live.items():
+            base, rec = p.kv_host_blocks(q)
+            assert base is None and rec.size == n == p.kv_host_len(q)[0]
+            valid = p.kv_host_valid(q, n).astype(bool)
+            assert not valid[rec < 0].any(), "a block without a record cannot be valid"
+            for j in np.flatnonzero(rec >= 0):
+                x = int(rec[j])
+                assert 0 <= x < arena, x
+                assert x not in seen, "record %d holds block %d of request %d and %s" % (x, j, q, seen[x])
+                seen[x] = (q, int(j))
+        st = p.kv_stats()
+        assert len(seen) * shape.R <= st["host_arena_used"] <= arena * shape.R
+    assert p.kv_stats()["host_evicted_blocks"] > 0
+    for q in list(live):
+        p.kv_host_release(q)
+    assert p.kv_stats()["host_arena_used"] == 0
+
+
 def test_reuse_cuts_swap_out_volume_and_small_host_memory_erodes_it():
     """Direction of the paper's microbenchmark (Section 5.3.3): with reuse far fewer blocks are
     swapped out than when the whole context leaves every time; a smaller host arena means more
