@@ -39,6 +39,8 @@ def _pool(kv, torch, s, host_bytes, **kw):
     import os
     if "KVSWAP_PACK_VARIANT" in os.environ:  # development aid: force a kernel variant
         kw["pack_variant"] = int(os.environ["KVSWAP_PACK_VARIANT"])
+    if "KVSWAP_MAPPED_GRID" in os.environ:  # development aid: workgroups of the mapped kernels
+        kw["mapped_in_grid"] = int(os.environ["KVSWAP_MAPPED_GRID"])
     gpu = torch.empty(s.R * s.n_blocks, dtype=torch.uint8, device="cuda:0")
     pool = kv.KVPool(n_layers=s.n_layers, n_kv_heads=s.n_kv_heads, head_dim=s.head_dim,
                      block_size=s.block_size, elt_bytes=s.elt_bytes, n_gpu_blocks=s.n_blocks,
@@ -100,6 +102,50 @@ def config1(args):
             "batched_all8_out_in_ms": {"median": _pct(b_ms, 50), "p99": _pct(b_ms, 99)},
             "batched_gbps": round(2 * payload / (np.median(b_ms) * 1e-3) / 1e9, 3),
             "mapped_swap_in": bool(args.mapped_swap_in), "mapped_swap_out": bool(args.mapped_swap_out)}
+
+
+def _copy_fairness(kv, torch, s, gpu):
+    """Section 3.2, order of dispatches: how long a small copy of the inference stream (a 4 KiB
+    result going to the host, a 4 KiB input coming in) takes while a 3 GiB swap uses the link in
+    the same direction, with the swap's copies cut at copy_chunk_bytes or issued whole."""
+    comp = torch.cuda.Stream()
+    dev = torch.zeros(4096, dtype=torch.uint8, device="cuda:0")
+    host = torch.zeros(4096, dtype=torch.uint8).pin_memory()
+
+    def one(to_host):
+        t0 = time.perf_counter()
+        with torch.cuda.stream(comp):
+            (host if to_host else dev).copy_(dev if to_host else host, non_blocking=True)
+        comp.synchronize()
+        return (time.perf_counter() - t0) * 1e6
+
+    def stats(xs):
+        return {"n": len(xs), "median": _pct(xs, 50), "p99": _pct(xs, 99), "max": _pct(xs, 100)}
+
+    for _ in range(50):
+        one(True), one(False)
+    out = {"what": "4 KiB pinned copy on another stream, call -> synchronised, host clock; alone and while a "
+                   "256-block (3.1 GiB) swap moves in the same direction",
+           "alone_d2h": stats([one(True) for _ in range(300)]),
+           "alone_h2d": stats([one(False) for _ in range(300)])}
+    ids = np.arange(256, dtype=np.int32)
+    for name, chunk in (("chunks_of_8_MiB", 8 * MiB), ("chunks_of_64_MiB_default", 0), ("whole_copies", 1 << 40)):
+        pool = kv.KVPool(n_layers=s.n_layers, n_kv_heads=s.n_kv_heads, head_dim=s.head_dim,
+                         block_size=s.block_size, elt_bytes=s.elt_bytes, n_gpu_blocks=s.n_blocks,
+                         gpu_base=gpu.data_ptr(), host_bytes=(256 + 40) * s.R, copy_chunk_bytes=chunk)
+        pool.swap_out(0, ids)
+        pool.kv_wait(0)
+        d2h, h2d = [], []
+        for _ in range(4):
+            pool.swap_out(0, ids)
+            while not pool.kv_query(0):
+                d2h.append(one(True))
+            pool.swap_in(0, ids)
+            while not pool.kv_query(0):
+                h2d.append(one(False))
+        pool.kv_pool_destroy()
+        out[name] = {"d2h_beside_swap_out": stats(d2h), "h2d_beside_swap_in": stats(h2d)}
+    return out
 
 
 def config3(args):
@@ -166,6 +212,7 @@ def config3(args):
     rates = _rates(pool.kv_profile_read())
     st = pool.kv_stats()
     pool.kv_pool_destroy()
+    fairness = _copy_fairness(kv, torch, s, gpu)
     return {"metric": "KV swap GB/s (out+in), 1 MI355X", "unit": "GB/s",
             "value": round(moved / total_s / 1e9, 3),
             "config": {"workload": "config 3: Llama-2-13B-shaped MHA KV (40 layers, 40 KV heads, head_dim 128, fp16), "
@@ -180,7 +227,8 @@ def config3(args):
                                   "alone": round(alone_ms, 4), "beside_swaps": round(busy_ms, 4),
                                   "slowdown": round(busy_ms / alone_ms, 4)},
             "streams": 4 if args.four_streams else 2, "mapped_swap_in": bool(args.mapped_swap_in),
-            "conflict_waits": st["conflict_waits"], "host_arena_bytes": st["host_arena_bytes"]}
+            "conflict_waits": st["conflict_waits"], "host_arena_bytes": st["host_arena_bytes"],
+            "small_copy_latency_us": fairness}
 
 
 def config4(args):
