@@ -37,6 +37,36 @@ def percentile(xs, q):
     return round(float(np.percentile(np.asarray(xs, dtype=np.float64), q)), 3)
 
 
+def device_state():
+    """Clocks and power state of the GPU as the kernel driver reports them (best effort)."""
+    import glob
+    out = {}
+    try:
+        import torch
+        out["name"] = torch.cuda.get_device_name(0)
+    except Exception:
+        pass
+    for dev in sorted(glob.glob("/sys/class/drm/card*/device")):
+        try:
+            if open(os.path.join(dev, "vendor")).read().strip() != "0x1002":
+                continue
+        except OSError:
+            continue
+        for key, fname in (("sclk", "pp_dpm_sclk"), ("mclk", "pp_dpm_mclk"), ("fclk", "pp_dpm_fclk"),
+                           ("performance_level", "power_dpm_force_performance_level")):
+            try:
+                text = open(os.path.join(dev, fname)).read().strip()
+            except OSError:
+                continue
+            lines = text.splitlines()
+            cur = [l for l in lines if l.rstrip().endswith("*")]
+            out[key] = (cur[0].split(":", 1)[-1].strip(" *") if cur else lines[0]) if lines else ""
+            if key != "performance_level" and lines:
+                out[key + "_max"] = lines[-1].split(":", 1)[-1].strip(" *")
+        break
+    return out
+
+
 def cpu_baseline(work, budget_s=12.0):
     """The CPU oracle, as it stands, on the same victims: swap all out, then in through the
     resume tables, repeated until about budget_s seconds of work.  One thread."""
@@ -148,6 +178,7 @@ def main() -> int:
     for _ in range(args.warmup):
         step()
     n_warm = len(pool.kv_profile_read())  # also waits for the warm-up to finish
+    dev_state = device_state()  # right after the warm-up steps, before the timed region
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -356,6 +387,7 @@ def main() -> int:
             "manager_dispatcher_avg": (round(mgr_stats["dispatch_us_sum"] / max(1, mgr_stats["dispatched"]), 2)
                                        if mgr_stats else None),
         },
+        "device_state": dev_state,
         "streams": 4 if args.four_streams else 2,
         "swap_in_path": "mapped host reads" if args.mapped_swap_in else "staged copies + scatter",
         "verified_samples_ok": ok,
