@@ -117,6 +117,8 @@ def main() -> int:
                     help="swap-in by a kernel that reads the pinned host image directly (KV_FLAG_MAPPED_SWAP_IN)")
     ap.add_argument("--mapped-swap-out", action="store_true",
                     help="config 1: swap-out by a kernel that stores into the pinned image (KV_FLAG_MAPPED_SWAP_OUT)")
+    ap.add_argument("--copy-chunk-mib", type=int, default=0,
+                    help="config 2: cut host-link copies at this many MiB (0 = the library's default)")
     ap.add_argument("--four-streams", action="store_true",
                     help="give kernels and copies of each direction their own streams (KV_FLAG_FOUR_STREAMS)")
     args = ap.parse_args()
@@ -163,7 +165,8 @@ def main() -> int:
                      gpu_base=gpu.data_ptr(), host_bytes=payload + 64 * len(victims) * s.R,
                      flags=kv.KV_FLAG_PROFILE | (kv.KV_FLAG_FOUR_STREAMS if args.four_streams else 0)
                      | (kv.KV_FLAG_MAPPED_SWAP_IN if args.mapped_swap_in else 0),
-                     pack_variant=int(os.environ.get("KVSWAP_PACK_VARIANT", "0")))
+                     pack_variant=int(os.environ.get("KVSWAP_PACK_VARIANT", "0")),
+                     copy_chunk_bytes=args.copy_chunk_mib << 20)
     cur = [work.tables[v] for v in victims]
     nxt = list(work.resume_tables)
 

@@ -129,7 +129,7 @@ def _copy_fairness(kv, torch, s, gpu):
            "alone_d2h": stats([one(True) for _ in range(300)]),
            "alone_h2d": stats([one(False) for _ in range(300)])}
     ids = np.arange(256, dtype=np.int32)
-    for name, chunk in (("chunks_of_8_MiB", 8 * MiB), ("chunks_of_64_MiB_default", 0), ("whole_copies", 1 << 40)):
+    for name, chunk in (("chunks_of_8_MiB", 8 * MiB), ("chunks_of_64_MiB", 64 * MiB), ("chunks_of_256_MiB_default", 0), ("whole_copies", 1 << 40)):
         pool = kv.KVPool(n_layers=s.n_layers, n_kv_heads=s.n_kv_heads, head_dim=s.head_dim,
                          block_size=s.block_size, elt_bytes=s.elt_bytes, n_gpu_blocks=s.n_blocks,
                          gpu_base=gpu.data_ptr(), host_bytes=(256 + 40) * s.R, copy_chunk_bytes=chunk)

@@ -94,7 +94,7 @@ typedef struct {
                                0 = default.  Always <= half a ring and >= one block record */
   int64_t copy_chunk_bytes; /* a host<->device copy is issued in pieces of at most this many
                                bytes so other streams' copies can interleave (Section 3.2,
-                               dispatch-order control); 0 = default 64 MiB */
+                               dispatch-order control); 0 = default 256 MiB */
   void*   compute_stream;   /* hipStream_t of the caller's inference work (used with
                                KV_FLAG_ORDER_COMPUTE) */
   int32_t host_slack_blocks;/* room reserved after each new host image for the next turn's

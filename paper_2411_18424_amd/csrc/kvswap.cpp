@@ -106,7 +106,7 @@ int32_t kv_pool_create(const kv_pool_config_t* cfg, kv_pool_t** out) {
   p->gpu = (char*)cfg->gpu_base;
   p->compute = (hipStream_t)cfg->compute_stream;
   p->slack = cfg->host_slack_blocks < 0 ? 32 : cfg->host_slack_blocks;
-  p->copy_chunk = cfg->copy_chunk_bytes > 0 ? cfg->copy_chunk_bytes : (64ll << 20);
+  p->copy_chunk = cfg->copy_chunk_bytes > 0 ? cfg->copy_chunk_bytes : (256ll << 20);
   p->grid = cfg->gather_grid;
   p->unroll = cfg->tile_unroll;  // 0 = pick from the chunk size
   p->variant = cfg->pack_variant;
