@@ -170,12 +170,19 @@ def main() -> int:
     cur = [work.tables[v] for v in victims]
     nxt = list(work.resume_tables)
 
+    phase_s = [0.0, 0.0]  # time in the swap-out and the swap-in half of the steps (host clock)
+
     def step():
         nonlocal cur, nxt
+        t_a = time.perf_counter()
         pool.swap_out_batch(victims, cur)
         pool.kv_wait_all()
+        t_b = time.perf_counter()
         pool.swap_in_batch(victims, nxt)
         pool.kv_wait_all()
+        t_c = time.perf_counter()
+        phase_s[0] += t_b - t_a
+        phase_s[1] += t_c - t_b
         cur, nxt = nxt, cur
 
     for _ in range(args.warmup):
@@ -183,6 +190,7 @@ def main() -> int:
     n_warm = len(pool.kv_profile_read())  # also waits for the warm-up to finish
     dev_state = device_state()  # right after the warm-up steps, before the timed region
     torch.cuda.synchronize()
+    phase_s[0] = phase_s[1] = 0.0
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
@@ -338,6 +346,8 @@ def main() -> int:
             "payload_bytes_each_way": payload,
             "victim_blocks": nb,
         },
+        "out_gbps": round(payload * args.steps / phase_s[0] / 1e9, 3),
+        "in_gbps": round(payload * args.steps / phase_s[1] / 1e9, 3),
         "roofline": {
             "bound": "hbm",
             "kernel": "kv_pack_xcd_kernel, gather direction (kv_pack_tile_kernel below 64 blocks per launch)",
