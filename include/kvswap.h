@@ -17,7 +17,9 @@
  * Conventions
  *  - Every function returns 0 (KV_OK) or a negative kv_status_t.  No function
  *    throws or aborts.  All argument validation happens before anything is
- *    enqueued: a call that returns an error has had no effect.
+ *    enqueued: a call that returns an error has had no effect.  (KV_EHIP is the
+ *    exception: a HIP runtime call that fails in the middle of a call can leave it
+ *    half enqueued; destroy the pool then.)
  *  - All pointers are HOST pointers unless a comment says "device pointer".
  *  - The caller owns every array it passes; the library has consumed it when
  *    the call returns.  The library owns the pool object, the pinned host
