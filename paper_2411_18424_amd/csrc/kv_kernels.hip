@@ -19,7 +19,7 @@
 //
 //  TILE, XCD-aware order (default for launches of 64 blocks or more): the same tiles through a
 //    1-D grid.  Workgroups are dealt round-robin to the 8 XCDs (each with its own L2), so
-//    workgroup w runs on XCD w % 8; the mapping gives every XCD two blocks of the launch at a
+//    workgroup w runs on XCD w % 8 (confirmed by reading XCC_ID in a probe kernel); the mapping gives every XCD two blocks of the launch at a
 //    time and lets it walk them chunk by chunk, alternating between the two (plane 0 of block
 //    A, plane 0 of block B, plane 1 of A ...), instead of spreading every chunk's tiles over
 //    all XCDs.  Measured on MI355X on the Llama-3-8B shape (896-block launches, read+write):
