@@ -3,7 +3,7 @@
  *
  * The library moves a preempted request's paged KV cache from GPU HBM to
  * pinned host memory and back (FastSwitch, arXiv 2411.18424: Section 2.1
- * "preemption by swapping", Section 3.1 block groups, Section 3.2 asynchronous
+ * preemption by swapping, Section 3.1 block groups, Section 3.2 asynchronous
  * swapping, Section 3.3 reuse of the CPU copy).  The data path is
  *
  *   swap-out: gather kernel (scattered pool chunks -> contiguous device
