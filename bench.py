@@ -327,7 +327,7 @@ def main() -> int:
                     traffic = int(line.split(":")[1].split()[0])
 
     result = {
-        "metric": "KV swap GB/s (out+in), 1 MI355X",
+        "metric": "KV swap GB/s (out+in) and per-preemption switch latency, 1 MI355X",
         "value": round(2 * payload * args.steps / dt / 1e9, 3),
         "unit": "GB/s",
         "n_gpus": 1,

@@ -92,7 +92,7 @@ def config1(args):
             b_ms.append((time.perf_counter() - t0) * 1e3)
         tables, tables2 = tables2, tables
     pool.kv_pool_destroy()
-    return {"metric": "KV swap GB/s (out+in), 1 MI355X", "unit": "GB/s",
+    return {"metric": "KV swap GB/s (out+in) and per-preemption switch latency, 1 MI355X", "unit": "GB/s",
             "value": round(2 * payload / (np.median(all_ms) * 1e-3) / 1e9, 3),
             "config": {"workload": "config 1: tiny pool (2 layers, 4 KV heads, head_dim 64, fp16, 256 blocks), "
                                    "8 requests of 1..16 blocks, one call per request, each waited for"},
@@ -213,7 +213,7 @@ def config3(args):
     st = pool.kv_stats()
     pool.kv_pool_destroy()
     fairness = _copy_fairness(kv, torch, s, gpu)
-    return {"metric": "KV swap GB/s (out+in), 1 MI355X", "unit": "GB/s",
+    return {"metric": "KV swap GB/s (out+in) and per-preemption switch latency, 1 MI355X", "unit": "GB/s",
             "value": round(moved / total_s / 1e9, 3),
             "config": {"workload": "config 3: Llama-2-13B-shaped MHA KV (40 layers, 40 KV heads, head_dim 128, fp16), "
                                    "pool %d blocks = %.1f GB, %d preemptions of 512..4096 tokens, one out while one in, "
@@ -288,7 +288,7 @@ def config4(args):
     st = pool.kv_stats()
     pool_recs = pool.kv_profile_read()
     pool.kv_pool_destroy()
-    return {"metric": "KV swap GB/s (out+in), 1 MI355X", "unit": "GB/s",
+    return {"metric": "KV swap GB/s (out+in) and per-preemption switch latency, 1 MI355X", "unit": "GB/s",
             "value": round(delta_bytes / (sum(delta_ms) * 1e-3) / 1e9, 3),
             "value_is": "payload rate of the delta swap-outs alone",
             "config": {"workload": "config 4: Llama-3-8B shape, %d conversations (capped from 128 by pinned memory: %.1f GiB "
@@ -312,7 +312,7 @@ def config5(args):
     from paper_2411_18424_amd import kvswap as kv, synth
     s = synth.QWEN2_72B
     n_req = args.requests
-    out = {"metric": "KV swap GB/s (out+in), 1 MI355X", "unit": "GB/s",
+    out = {"metric": "KV swap GB/s (out+in) and per-preemption switch latency, 1 MI355X", "unit": "GB/s",
            "config": {"workload": "config 5: Qwen2-72B-shaped GQA KV (80 layers, 8 KV heads, head_dim 128, bf16), pool %d blocks "
                                   "= %.1f GB, %d requests of 2048 blocks (10 GiB) per run length, one at a time"
                                   % (s.n_blocks, s.n_blocks * s.R / 1e9, n_req)}}
