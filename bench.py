@@ -119,6 +119,8 @@ def main() -> int:
                     help="config 1: swap-out by a kernel that stores into the pinned image (KV_FLAG_MAPPED_SWAP_OUT)")
     ap.add_argument("--copy-chunk-mib", type=int, default=0,
                     help="config 2: cut host-link copies at this many MiB (0 = the library's default)")
+    ap.add_argument("--scatter-stream", action="store_true",
+                    help="three streams: scatter kernels on a stream of their own (KV_FLAG_SCATTER_STREAM)")
     ap.add_argument("--four-streams", action="store_true",
                     help="give kernels and copies of each direction their own streams (KV_FLAG_FOUR_STREAMS)")
     args = ap.parse_args()
@@ -164,6 +166,7 @@ def main() -> int:
                      block_size=s.block_size, elt_bytes=s.elt_bytes, n_gpu_blocks=s.n_blocks,
                      gpu_base=gpu.data_ptr(), host_bytes=payload + 64 * len(victims) * s.R,
                      flags=kv.KV_FLAG_PROFILE | (kv.KV_FLAG_FOUR_STREAMS if args.four_streams else 0)
+                     | (kv.KV_FLAG_SCATTER_STREAM if args.scatter_stream else 0)
                      | (kv.KV_FLAG_MAPPED_SWAP_IN if args.mapped_swap_in else 0),
                      pack_variant=int(os.environ.get("KVSWAP_PACK_VARIANT", "0")),
                      copy_chunk_bytes=args.copy_chunk_mib << 20)
@@ -401,7 +404,7 @@ def main() -> int:
                                        if mgr_stats else None),
         },
         "device_state": dev_state,
-        "streams": 4 if args.four_streams else 2,
+        "streams": 4 if args.four_streams else 3 if args.scatter_stream else 2,
         "swap_in_path": "mapped host reads" if args.mapped_swap_in else "staged copies + scatter",
         "verified_samples_ok": ok,
         "stats": {k: stats[k] for k in ("gather_launches", "scatter_launches", "d2h_copies", "h2d_copies")},

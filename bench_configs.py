@@ -31,6 +31,7 @@ def _rates(recs):
 
 def _flags(args, kv, base=0):
     return (base | (kv.KV_FLAG_FOUR_STREAMS if args.four_streams else 0)
+            | (kv.KV_FLAG_SCATTER_STREAM if getattr(args, "scatter_stream", False) else 0)
             | (kv.KV_FLAG_MAPPED_SWAP_IN if args.mapped_swap_in else 0)
             | (kv.KV_FLAG_MAPPED_SWAP_OUT if getattr(args, "mapped_swap_out", False) else 0))
 
@@ -226,7 +227,7 @@ def config3(args):
             "compute_matmul_ms": {"what": "8192^3 bf16 matmul on the compute stream, %d per iteration" % per_iter,
                                   "alone": round(alone_ms, 4), "beside_swaps": round(busy_ms, 4),
                                   "slowdown": round(busy_ms / alone_ms, 4)},
-            "streams": 4 if args.four_streams else 2, "mapped_swap_in": bool(args.mapped_swap_in),
+            "streams": 4 if args.four_streams else 3 if args.scatter_stream else 2, "mapped_swap_in": bool(args.mapped_swap_in),
             "conflict_waits": st["conflict_waits"], "host_arena_bytes": st["host_arena_bytes"],
             "small_copy_latency_us": fairness}
 

@@ -81,6 +81,8 @@ typedef enum {
                                        where the process has hardware queues to spare (HIP's default is 4
                                        per process, GPU_MAX_HW_QUEUES): streams that share a queue with the
                                        application's compute stream wait behind its kernels */
+#define KV_FLAG_SCATTER_STREAM 128u /* three streams: the scatter kernels get a stream of their own, so the
+                                       scatter of a piece runs under the next piece's host-to-device copy */
 
 typedef struct kv_pool kv_pool_t;
 

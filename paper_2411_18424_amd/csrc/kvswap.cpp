@@ -59,7 +59,8 @@ void destroy_pool(kv_pool* p) {
       (void)hipEventDestroy(r.stop);
     }
     if (p->ev_compute) (void)hipEventDestroy(p->ev_compute);
-    if (!p->four_streams) p->s_d2h = p->s_scat = nullptr;  // aliases of the other two
+    if (p->s_d2h == p->s_pack) p->s_d2h = nullptr;  // aliases of the other two
+    if (p->s_scat == p->s_h2d) p->s_scat = nullptr;
     for (hipStream_t s : {p->s_pack, p->s_d2h, p->s_h2d, p->s_scat})
       if (s) (void)hipStreamDestroy(s);
     if (p->own_staging && p->staging) (void)hipFree(p->staging);
@@ -186,6 +187,7 @@ int32_t kv_pool_create(const kv_pool_config_t* cfg, kv_pool_t** out) {
     } else {
       p->s_d2h = p->s_pack;
       p->s_scat = p->s_h2d;
+      if (cfg->flags & KV_FLAG_SCATTER_STREAM) TRY_OR_BAIL(hipStreamCreateWithFlags(&p->s_scat, hipStreamNonBlocking));
     }
     TRY_OR_BAIL(hipEventCreateWithFlags(&p->ev_compute, hipEventDisableTiming));
     if (p->arena_blocks > 0) {

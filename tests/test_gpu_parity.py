@@ -338,7 +338,7 @@ def test_blocks_freed_during_a_swap_in_are_held_back(harness):
     assert h.pool.kv_stats()["conflict_waits"] >= 3
 
 
-@pytest.mark.parametrize("flags", [0, 8], ids=["two_streams", "four_streams"])
+@pytest.mark.parametrize("flags", [0, 8, 128], ids=["two_streams", "four_streams", "three_streams"])
 def test_swap_ins_into_the_same_blocks_land_in_call_order(harness, flags):
     """Raw tables, no allocator in between: two requests are swapped in to the same blocks by
     different paths (staged scatter, then 2-D copies on the copy stream); the later call wins."""

@@ -17,7 +17,7 @@ SHAPE = synth.KVShape("stream", 2, 2, 64, 16, 2, 512, "fp16")  # C = 4 KiB, R = 
 # transfers that take milliseconds, so calls really overlap: C = 32 KiB, R = 512 KiB, 2 GiB pool
 BIG = synth.KVShape("stream_big", 8, 8, 128, 16, 2, 4096, "bf16")
 
-ORDER_COMPUTE, FOUR_STREAMS, MAPPED_SWAP_IN, MAPPED_SWAP_OUT = 4, 8, 16, 64
+ORDER_COMPUTE, FOUR_STREAMS, MAPPED_SWAP_IN, MAPPED_SWAP_OUT, SCATTER_STREAM = 4, 8, 16, 64, 128
 
 
 class Loop:
@@ -336,6 +336,8 @@ CASES = {
     "two_streams_small_rings": (101, ORDER_COMPUTE, dict(staging_out_bytes=1 * MiB, staging_in_bytes=512 * KiB,
                                                          max_piece_bytes=128 * KiB, host_slack_blocks=4)),
     "four_streams_default_rings": (102, ORDER_COMPUTE | FOUR_STREAMS, dict(host_slack_blocks=0)),
+    "three_streams_small_rings": (107, ORDER_COMPUTE | SCATTER_STREAM, dict(staging_out_bytes=1 * MiB, staging_in_bytes=512 * KiB,
+                                                                         max_piece_bytes=64 * KiB)),
     "persistent_pack_kernel": (103, ORDER_COMPUTE, dict(pack_variant=1, staging_out_bytes=2 * MiB,
                                                         staging_in_bytes=2 * MiB, copy_chunk_bytes=64 * KiB)),
     "mapped_swap_in": (104, ORDER_COMPUTE | MAPPED_SWAP_IN, dict(host_slack_blocks=8)),
@@ -375,6 +377,8 @@ BIG_CASES = {
     "small_rings": (201, ORDER_COMPUTE, dict(staging_out_bytes=48 * MiB, staging_in_bytes=24 * MiB,
                                             max_piece_bytes=8 * MiB, copy_chunk_bytes=4 * MiB)),
     "four_streams": (202, ORDER_COMPUTE | FOUR_STREAMS, dict(staging_out_bytes=256 * MiB, staging_in_bytes=64 * MiB)),
+    "three_streams": (204, ORDER_COMPUTE | SCATTER_STREAM, dict(staging_out_bytes=128 * MiB, staging_in_bytes=32 * MiB,
+                                                             max_piece_bytes=8 * MiB)),
     "mapped_both_ways": (203, ORDER_COMPUTE | MAPPED_SWAP_IN | MAPPED_SWAP_OUT, dict(mapped_out_max_blocks=64)),
 }
 
