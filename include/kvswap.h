@@ -276,6 +276,7 @@ typedef struct {
   int32_t reserved;
   int64_t bytes;     /* payload bytes of this launch / copy */
   double  ms;        /* device duration */
+  double  start_ms;  /* when it began, relative to the first record's beginning */
 } kv_prof_record_t;
 /* Waits for all work, then writes up to cap records; *out_n = number available. */
 int32_t kv_profile_read(kv_pool_t* pool, kv_prof_record_t* out, int32_t cap, int32_t* out_n);

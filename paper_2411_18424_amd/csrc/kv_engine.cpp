@@ -202,9 +202,12 @@ int32_t order_after_compute(kv_pool* p, hipStream_t s) {
 // overlaps (and every older one) must have been released by its consumer first: the
 // producer stream is made to wait for it on the device.  `flush` is called before waiting
 // on a region of the same op whose consumer work has not been issued yet.
+// An event another stream has just been told to wait for is not recycled at once: it goes to
+// the claiming op's list (`retired`) and back to the pool when that op is done, so nothing can
+// record it again while the wait is still queued.
 template <class Flush>
 int32_t ring_claim(kv_pool* p, ByteRing* r, int64_t len, uint64_t op_seq, hipStream_t producer,
-                   Flush&& flush, Region** out) {
+                   Flush&& flush, std::vector<hipEvent_t>* retired, Region** out) {
   int32_t rc;
   auto evict = [&](int64_t lo, int64_t hi) -> int32_t {
     int last = -1;
@@ -218,7 +221,7 @@ int32_t ring_claim(kv_pool* p, ByteRing* r, int64_t len, uint64_t op_seq, hipStr
       Region f = r->live.front();
       r->live.pop_front();
       if ((rc = stream_wait(p, producer, f.freed))) return rc;
-      put_event(p, f.freed);
+      if (f.freed) retired->push_back(f.freed);
     }
     return KV_OK;
   };
@@ -274,7 +277,7 @@ int32_t enqueue_out(kv_pool* p, const std::vector<Move>& mv, const std::vector<h
   for (int64_t i = 0; i < m; i += r.piece_blocks) {
     const int64_t mp = std::min(r.piece_blocks, m - i);
     Region* g;
-    if ((rc = ring_claim(p, &r, mp * p->R, op->seq, p->s_pack, flush, &g))) return rc;
+    if ((rc = ring_claim(p, &r, mp * p->R, op->seq, p->s_pack, flush, &op->aux, &g))) return rc;
     const int64_t off = g->off;
     for (int64_t k = 0; k < mp; k += p->launch_blocks) {
       int64_t ml = std::min<int64_t>(p->launch_blocks, mp - k);
@@ -308,7 +311,7 @@ int32_t enqueue_in(kv_pool* p, const std::vector<Move>& mv, const std::vector<hi
   for (int64_t i = 0; i < m; i += r.piece_blocks) {
     const int64_t mp = std::min(r.piece_blocks, m - i);
     Region* g;
-    if ((rc = ring_claim(p, &r, mp * p->R, op->seq, p->s_h2d, no_flush, &g))) return rc;
+    if ((rc = ring_claim(p, &r, mp * p->R, op->seq, p->s_h2d, no_flush, &op->aux, &g))) return rc;
     char* sb = at(r.base, g->off);
     if ((rc = issue_copies(p, false, sb, &mv[(size_t)i], mp))) return rc;
     hipEvent_t ready;
@@ -365,7 +368,7 @@ int32_t enqueue_in_layers(kv_pool* p, const std::vector<Move>& mv, const std::ve
     for (int64_t i = 0; i < m; i += piece_blocks) {
       const int64_t mp = std::min(piece_blocks, m - i);
       Region* g;
-      if ((rc = ring_claim(p, &r, mp * slice, op->seq, p->s_h2d, no_flush, &g))) return rc;
+      if ((rc = ring_claim(p, &r, mp * slice, op->seq, p->s_h2d, no_flush, &op->aux, &g))) return rc;
       char* sb = at(r.base, g->off);
       hipEvent_t e0 = nullptr, e1 = nullptr;
       if (p->profile && !p->plan) {

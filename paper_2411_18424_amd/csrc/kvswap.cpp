@@ -648,6 +648,9 @@ int32_t kv_profile_read(kv_pool_t* p, kv_prof_record_t* out, int32_t cap, int32_
     out[i].reserved = 0;
     out[i].bytes = p->prof[(size_t)i].bytes;
     out[i].ms = ms;
+    float t0 = 0.f;
+    if (i > 0) HIP_TRY(hipEventElapsedTime(&t0, p->prof[0].start, p->prof[(size_t)i].start));
+    out[i].start_ms = t0;
   }
   return KV_OK;
 }

@@ -70,7 +70,8 @@ class kv_manager_stats_t(C.Structure):
 
 
 class kv_prof_record_t(C.Structure):
-    _fields_ = [("kind", C.c_int32), ("reserved", C.c_int32), ("bytes", C.c_int64), ("ms", C.c_double)]
+    _fields_ = [("kind", C.c_int32), ("reserved", C.c_int32), ("bytes", C.c_int64), ("ms", C.c_double),
+                ("start_ms", C.c_double)]
 
 
 def _load() -> C.CDLL:
@@ -413,6 +414,14 @@ class KVPool:
         recs = (kv_prof_record_t * max(1, n.value))()
         _check(lib.kv_profile_read(self._h, recs, n.value, C.byref(n)))
         return [(recs[i].kind, recs[i].bytes, recs[i].ms) for i in range(n.value)]
+
+    def kv_profile_timeline(self):
+        """(kind, bytes, start_ms, ms) of every launch and copy, in issue order."""
+        n = C.c_int32()
+        _check(lib.kv_profile_read(self._h, None, 0, C.byref(n)))
+        recs = (kv_prof_record_t * max(1, n.value))()
+        _check(lib.kv_profile_read(self._h, recs, n.value, C.byref(n)))
+        return [(recs[i].kind, recs[i].bytes, recs[i].start_ms, recs[i].ms) for i in range(n.value)]
 
     def kv_profile_reset(self):
         _check(lib.kv_profile_reset(self._h))

@@ -454,6 +454,11 @@ def test_profile_records(harness):
     assert kinds == [0, 1, 2, 3]
     for k, nbytes, ms in recs:
         assert nbytes == 16 * h.shape.R and ms > 0
+    tl = h.pool.kv_profile_timeline()
+    assert [(k, b) for k, b, _, _ in tl] == [(k, b) for k, b, _ in recs]
+    starts = {k: t0 for k, _, t0, _ in tl}
+    assert tl[0][2] == 0 and all(t0 >= 0 for t0 in starts.values())
+    assert starts[0] <= starts[2] <= starts[3] <= starts[1]   # gather, its copy, copy back, scatter
     h.pool.kv_profile_reset()
     assert h.pool.kv_profile_read() == []
 
