@@ -182,7 +182,9 @@ int32_t swap_out(kv_pool_t* pool, int64_t req, const int32_t* block_table, int32
 int32_t swap_out_delta(kv_pool_t* pool, int64_t req, const int32_t* block_table, int32_t n_blocks,
                        const uint8_t* dirty_mask, int32_t* out_n_moved);
 /* Section 3.2 swap-in path.  Copies the host image into new_block_table's blocks.  The
- * image is kept (Section 3.3).  KV_ENOENT: no image, or a needed block's host copy is not
+ * image is kept (Section 3.3).  When one scheduling step both resumes and preempts, issue the
+ * swap-in the scheduler will wait for before the swap-out: calls reach the copy engines in
+ * call order.  KV_ENOENT: no image, or a needed block's host copy is not
  * valid.  KV_EINVAL: n_blocks differs from the image, bad ids. */
 int32_t swap_in(kv_pool_t* pool, int64_t req, const int32_t* new_block_table, int32_t n_blocks);
 /* As swap_in, but logical blocks with resident_mask[j] != 0 are already on the GPU and are
