@@ -202,6 +202,30 @@ int32_t kv_pool_create(const kv_pool_config_t* cfg, kv_pool_t** out) {
       if (e != hipSuccess) return bail(fail(KV_ENOMEM_GPU, "hipMalloc(staging %lld): %s", (long long)(out_cap + in_cap), hipGetErrorString(e)));
       p->own_staging = true;
     }
+    // The first copies of a process in each direction block the host for milliseconds while
+    // the runtime sets its copy paths up: take that here, not inside the first swap.
+    if (p->host) {
+      const size_t n = (size_t)std::min<int64_t>({1ll << 20, p->arena_blocks * p->R, out_cap + in_cap});
+      TRY_OR_BAIL(hipMemcpyAsync(p->staging, p->host, n, hipMemcpyHostToDevice, p->s_h2d));
+      TRY_OR_BAIL(hipStreamSynchronize(p->s_h2d));
+      TRY_OR_BAIL(hipMemcpyAsync(p->host, p->staging, n, hipMemcpyDeviceToHost, p->s_pack));
+      TRY_OR_BAIL(hipStreamSynchronize(p->s_pack));
+    }
+    // ... and the first kernel launch loads the code object: gather block 0 into staging once
+    // (reads the pool, writes only staging).
+    {
+      KvPackArgs a;
+      a.pool = p->gpu;
+      a.staging = p->staging;
+      a.plane_stride = p->N * p->C;
+      a.C = (uint32_t)p->C;
+      a.P = (uint32_t)p->P;
+      a.m = 1;
+      a.tiles_per_chunk = a.n_tiles = a.pad = 0;
+      a.table[0] = 0;
+      TRY_OR_BAIL(kv_launch_pack(false, a, p->unroll, p->variant, p->grid, p->s_pack, nullptr, nullptr));
+      TRY_OR_BAIL(hipStreamSynchronize(p->s_pack));
+    }
   }
   p->ring_out.base = p->staging;
   p->ring_in.base = p->staging ? p->staging + out_cap : nullptr;
