@@ -224,9 +224,8 @@ def main() -> int:
     origin = [work.tables[v] for v in victims]
     ok = True
     for i in rng.integers(0, len(victims), size=8):
-        img = pool.kv_host_view(victims[i])
-        j = int(rng.integers(0, img.shape[0]))
-        ok &= bool(np.array_equal(img[j], content.block(int(origin[i][j]))))
+        j = int(rng.integers(0, len(origin[i])))
+        ok &= bool(np.array_equal(pool.kv_host_read(victims[i], j, 1)[0], content.block(int(origin[i][j]))))
     pool.swap_in_batch(victims, cur)
     pool.kv_wait_all()
 

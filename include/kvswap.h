@@ -124,12 +124,18 @@ typedef struct {
  * staging rings, side streams, event pool, allocator with all N blocks free.
  * *out is written only on success. */
 int32_t kv_pool_create(const kv_pool_config_t* cfg, kv_pool_t** out);
-/* Waits for all in-flight work, then frees everything the library owns. */
+/* Waits for the library's own in-flight work (its streams, not the caller's), then frees
+ * everything the library owns. */
 int32_t kv_pool_destroy(kv_pool_t* pool);
 
 /* Section 3.1, Dynamic Block Group allocation.  Returns n_blocks physical ids in
  * out_blocks[n_blocks] (caller-allocated), in as few maximal contiguous runs as the free
- * lists allow; runs shorter than min_run are used only when nothing longer is free.
+ * lists allow: the best-fitting free run when one holds the whole request, else the longest
+ * free runs first.  min_run (>= 0; 0 and 1 mean no preference) is the block-group size the
+ * caller is aiming for: the last piece of a request that had to be split is carved from the
+ * best-fitting free run of at least min_run blocks when there is one, so free runs shorter
+ * than min_run are touched only when every longer run is used up.  req is a label for the
+ * caller's bookkeeping (ownership is not tracked per request).
  * *out_n_runs (may be NULL) receives the number of maximal runs.  Freed blocks that an
  * unfinished gather still reads or an unfinished scatter still writes are never handed out
  * (Section 3.2, KV cache conflict): if they are needed the call waits for exactly that work.  KV_ENOMEM_GPU if fewer than
@@ -254,6 +260,19 @@ int32_t kv_wait_all(kv_pool_t* pool);  /* until everything enqueued before the c
 int32_t kv_host_len(kv_pool_t* pool, int64_t req, int32_t* n_blocks, int32_t* n_extents);
 int32_t kv_host_blocks(kv_pool_t* pool, int64_t req, const void** arena_base, int64_t* record_index,
                        int32_t n);
+/* Section 3.3: the CPU copy itself, in the layout of the contract.  kv_host_read copies logical
+ * blocks [first_block, first_block + n_blocks) of req's image into dst (host memory,
+ * n_blocks * R bytes, caller-owned) as dst[j - first_block][p][C], whatever extents the
+ * records sit in; a block whose record was reclaimed reads as zeros (its host_valid bit is 0).
+ * It waits for the request's last op first, and holds the pool's lock while it copies (a
+ * reading aid for tests, tools and checkpointing, not a hot-path call).  KV_ENODEV in a
+ * plan-only pool.
+ * kv_host_view is the zero-copy form: *bytes = n * R, and *ptr = the image's first byte when
+ * all its records are consecutive in the arena (one extent, nothing reclaimed), NULL
+ * otherwise (then use kv_host_read).  Valid until the image grows, is released or rebuilt;
+ * it does not wait - use kv_wait before reading through it. */
+int32_t kv_host_read(kv_pool_t* pool, int64_t req, int32_t first_block, int32_t n_blocks, void* dst);
+int32_t kv_host_view(kv_pool_t* pool, int64_t req, const void** ptr, int64_t* bytes);
 int32_t kv_host_valid(kv_pool_t* pool, int64_t req, uint8_t* out_mask, int32_t n); /* 1 = valid */
 int32_t kv_host_invalidate(kv_pool_t* pool, int64_t req, const uint8_t* mask, int32_t n); /* contaminate */
 int32_t kv_host_release(kv_pool_t* pool, int64_t req);        /* drop the image (waits for its ops) */

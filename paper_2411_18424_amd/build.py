@@ -40,7 +40,32 @@ def build_lib(verbose: bool = True) -> str:
     if verbose and out:
         print(out, flush=True)
     os.replace(tmp, LIB)
+    build_host_tests(hipcc, verbose)
     return LIB
+
+
+# C / C++ callers of the ABI that the GPU tests run as programs of their own (tests/host/*.cpp):
+# built here, next to the library, so that nothing is compiled on the GPU machine.
+HOST_TESTS = ["host_read_check"]
+
+
+def build_host_tests(hipcc: str, verbose: bool = True) -> None:
+    root = os.path.dirname(HERE)
+    tdir = os.path.join(root, "tests", "host")
+    for name in HOST_TESTS:
+        src = os.path.join(tdir, name + ".cpp")
+        if not os.path.exists(src):
+            continue
+        exe = os.path.join(tdir, name + ".bin")
+        cmd = [hipcc, "-O1", "-std=c++17", "--offload-arch=gfx950", "-Wall", "-Wno-unused-command-line-argument",
+               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+               src, "-L" + HERE, "-lkvswap", "-Wl,-rpath," + HERE, "-Wl,-rpath,$ORIGIN/../../paper_2411_18424_amd",
+               "-o", exe]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        if res.returncode != 0:
+            raise RuntimeError("hipcc failed on %s:\n%s" % (name, res.stdout))
 
 
 if __name__ == "__main__":

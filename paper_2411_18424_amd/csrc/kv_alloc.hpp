@@ -60,6 +60,15 @@ class RunSet {
     return true;
   }
 
+  // As take_best_fit(n), but only among runs of at least min_len blocks.
+  bool take_best_fit_at_least(int64_t n, int64_t min_len, int64_t* start) {
+    auto it = by_size_.lower_bound({std::max(n, min_len), INT64_MIN});
+    if (it == by_size_.end()) return false;
+    carve(it->second, it->first, n);
+    *start = last_start_;
+    return true;
+  }
+
   // Takes the low end (up to n) of the largest run; returns the length taken.
   int64_t take_from_largest(int64_t n, int64_t* start) {
     if (by_size_.empty()) return 0;
@@ -133,17 +142,25 @@ class BlockGroupAllocator {
   int64_t largest_run() const { return free_.largest(); }
 
   // Allocates n ids into out (which must be empty), fewest runs first: the best-fitting free
-  // run if one holds the rest, else the largest run, repeatedly - so runs shorter than any
-  // wanted minimum are used only when nothing longer is free.  Caller has checked
+  // run if one holds the rest, else the largest run, repeatedly.  A request that has to be
+  // split therefore uses the longest free runs first; its last piece (the remainder, which may
+  // be short) is carved from the best-fitting run of at least min_run blocks when there is
+  // one, so that free runs shorter than min_run are touched only when every longer run is used
+  // up - the short fragments stay for requests that are short themselves.  A request that fits
+  // one free run takes the best-fitting one whatever min_run says.  Caller has checked
   // n <= n_free().  Returns the number of maximal runs of consecutive ids in out.
-  int32_t alloc(int64_t n, std::vector<int32_t>* out) {
+  int32_t alloc(int64_t n, std::vector<int32_t>* out, int64_t min_run = 1) {
     int64_t start;
+    bool split = false;
     while (n > 0) {
       int64_t got;
-      if (free_.take_best_fit(n, &start)) {
+      if (split && n < min_run && free_.take_best_fit_at_least(n, min_run, &start)) {
+        got = n;
+      } else if (free_.take_best_fit(n, &start)) {
         got = n;
       } else {
         got = free_.take_from_largest(n, &start);
+        split = true;
       }
       for (int64_t i = 0; i < got; ++i) {
         state_[(size_t)(start + i)] = USED;

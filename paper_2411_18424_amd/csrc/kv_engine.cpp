@@ -42,15 +42,23 @@ void put_event(kv_pool* p, hipEvent_t ev) {
 }
 
 // Polls completion of the oldest ops; recycles their events.  Ops of one direction finish
-// in issue order (their kernels share one stream), so polling stops at the first unfinished.
+// in issue order (their completion events are recorded on one stream per direction), so polling
+// stops at the first unfinished one - and at an op that is still being enqueued (its events
+// have not been recorded yet, and an unrecorded event reads as complete).
 void reap(kv_pool* p) {
-  if (p->plan) {
-    for (auto& o : p->ops_out) o->packed_done = o->all_done = true;
-    for (auto& o : p->ops_in) o->all_done = true;
-    p->pack_done_seq = p->out_seq;
-    p->scat_done_seq = p->in_seq;
-    p->ops_out.clear();
-    p->ops_in.clear();
+  if (p->plan) {  // nothing runs: whatever has been enqueued is done
+    while (!p->ops_out.empty() && p->ops_out.front()->issued) {
+      Op& o = *p->ops_out.front();
+      o.packed_done = o.all_done = true;
+      p->pack_done_seq = o.seq;
+      p->ops_out.pop_front();
+    }
+    while (!p->ops_in.empty() && p->ops_in.front()->issued) {
+      Op& o = *p->ops_in.front();
+      o.all_done = true;
+      p->scat_done_seq = o.seq;
+      p->ops_in.pop_front();
+    }
     p->ring_out.live.clear();
     p->ring_in.live.clear();
     p->alloc.reap(p->pack_done_seq, p->scat_done_seq);
@@ -58,13 +66,13 @@ void reap(kv_pool* p) {
   }
   for (auto& o : p->ops_out) {
     if (o->packed_done) continue;
-    if (hipEventQuery(o->packed) != hipSuccess) break;
+    if (!o->issued || p->event_query(o->packed) != hipSuccess) break;
     o->packed_done = true;
     p->pack_done_seq = o->seq;
   }
   while (!p->ops_out.empty()) {
     Op& o = *p->ops_out.front();
-    if (!o.packed_done || hipEventQuery(o.done) != hipSuccess) break;
+    if (!o.issued || !o.packed_done || p->event_query(o.done) != hipSuccess) break;
     o.all_done = true;
     put_event(p, o.packed);
     put_event(p, o.done);
@@ -75,7 +83,7 @@ void reap(kv_pool* p) {
   }
   while (!p->ops_in.empty()) {
     Op& o = *p->ops_in.front();
-    if (hipEventQuery(o.done) != hipSuccess) break;
+    if (!o.issued || p->event_query(o.done) != hipSuccess) break;
     o.all_done = true;
     p->scat_done_seq = o.seq;
     put_event(p, o.done);
@@ -89,7 +97,7 @@ void reap(kv_pool* p) {
   for (ByteRing* r : {&p->ring_out, &p->ring_in}) {
     while (!r->live.empty()) {
       Region& f = r->live.front();
-      if (!f.recorded || hipEventQuery(f.freed) != hipSuccess) break;
+      if (!f.recorded || p->event_query(f.freed) != hipSuccess) break;
       put_event(p, f.freed);
       r->live.pop_front();
     }
@@ -188,6 +196,24 @@ int32_t issue_copies(kv_pool* p, bool to_host, char* slot, const Move* mv, int64
     i = j + 1;
   }
   if (e1) HIP_TRY(hipEventRecord(e1, s));
+  return KV_OK;
+}
+
+// Records `ev` so that it fires when the work enqueued so far on `from` is done, but ON stream
+// `on`: completion events of one direction are all recorded on one stream (packed: s_pack,
+// swap-out done: s_d2h, swap-in done: s_scat), whatever stream a path did its work on, so they
+// fire in issue order and waiting for the newest op of a set covers the older ones.
+int32_t record_via(kv_pool* p, hipEvent_t ev, hipStream_t from, hipStream_t on, const OpRef& op) {
+  if (p->plan || !ev) return KV_OK;
+  if (from != on) {
+    int32_t rc;
+    hipEvent_t hop;
+    if ((rc = get_event(p, &hop))) return rc;
+    op->aux.push_back(hop);
+    HIP_TRY(hipEventRecord(hop, from));
+    HIP_TRY(hipStreamWaitEvent(on, hop, 0));
+  }
+  HIP_TRY(hipEventRecord(ev, on));
   return KV_OK;
 }
 
@@ -458,8 +484,12 @@ int32_t enqueue_direct(kv_pool* p, bool to_host, const std::vector<Move>& mv,
     i = j + 1;
   }
   if (e1) HIP_TRY(hipEventRecord(e1, s));
-  if (to_host && (rc = record(p, op->packed, s))) return rc;
-  if ((rc = record(p, op->done, s))) return rc;
+  if (to_host) {
+    if ((rc = record_via(p, op->packed, s, p->s_pack, op))) return rc;
+    if ((rc = record(p, op->done, s))) return rc;
+  } else {
+    if ((rc = record_via(p, op->done, s, p->s_scat, op))) return rc;
+  }
   (to_host ? p->st.bytes_out : p->st.bytes_in) += m * p->R;
   (to_host ? p->st.blocks_out : p->st.blocks_in) += m;
   return KV_OK;
@@ -559,7 +589,7 @@ int32_t enqueue_out_mapped(kv_pool* p, const std::vector<Move>& mv, const std::v
     HIP_TRY(kv_launch_mapped(true, a, p->mapped_grid, s, e0, e1));
   }
   if ((rc = record(p, op->packed, s))) return rc;
-  if ((rc = record(p, op->done, s))) return rc;
+  if ((rc = record_via(p, op->done, s, p->s_d2h, op))) return rc;
   p->st.bytes_out += m * p->R;
   p->st.blocks_out += m;
   return KV_OK;

@@ -38,6 +38,9 @@ struct Op {
   hipEvent_t packed = nullptr;  // swap-out only: recorded after the last gather
   hipEvent_t done = nullptr;    // recorded after the last copy (out) / scatter (in)
   bool packed_done = false, all_done = false;
+  bool issued = false;          // every event of the op has been recorded (or the enqueue has failed);
+                                // until then completion polling must not look at them: a query of an
+                                // event that was never recorded, or was recycled, reports success
   std::vector<hipEvent_t> aux;  // hand-off events of this op, recycled when it is done
   std::vector<hipEvent_t> layer_ev;  // layer-wise swap-in: one per step of layer_step layers (null
                                      // entries in a plan-only pool); recycled when the op is done
@@ -145,6 +148,7 @@ struct kv_pool {
   char* staging = nullptr;
   kvi::ByteRing ring_out, ring_in;
   hipStream_t s_pack = nullptr, s_d2h = nullptr, s_h2d = nullptr, s_scat = nullptr;
+  hipStream_t s_d2h2 = nullptr;  // second device-to-host copy stream (small copies alternate), or null
   hipStream_t compute = nullptr;
   hipEvent_t ev_compute = nullptr;
   int unroll = 0, grid = 0, variant = 0;
@@ -170,6 +174,8 @@ struct kv_pool {
   std::vector<hipEvent_t> timing_pool;  // timing enabled
   std::vector<kvi::ProfRec> prof;
   kv_stats_t st{};
+  // completion test of an event (hipEventQuery); a host-only unit test substitutes its own
+  hipError_t (*event_query)(hipEvent_t) = hipEventQuery;
 };
 
 namespace kvi {

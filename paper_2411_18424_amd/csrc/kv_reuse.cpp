@@ -204,7 +204,19 @@ int32_t do_swap_out(kv_pool* p, std::vector<OutItem>& items, int32_t* out_n_move
                   (long long)need, (long long)p->arena.total(), (long long)p->arena.largest());
     }
   }
-  // 3. commit: images, reuse map, move list
+  // 3. an image that is rebuilt gives its old extents back to the arena; an unfinished op of
+  //    the request may still read or write them.  Wait for it now, before this call's op
+  //    exists: completion polling must never meet an op whose events are not recorded yet.
+  for (OutItem& it : items) {
+    if (!it.fresh) continue;
+    auto f = p->reqs.find(it.req);
+    if (f == p->reqs.end() || !f->second.has_image) continue;
+    if ((rc = host_wait_op(p, f->second.last))) {
+      undo(items.size());
+      return rc;
+    }
+  }
+  // 4. commit: images, reuse map, move list
   std::vector<Move> mv;
   std::vector<hipEvent_t> pre;
   uint64_t max_writer = 0;
@@ -218,11 +230,7 @@ int32_t do_swap_out(kv_pool* p, std::vector<OutItem>& items, int32_t* out_n_move
     Req& q = p->reqs[it.req];
     Image& im = q.img;
     if (it.fresh) {
-      if (q.has_image) {
-        // the old extents may still be read or written by an unfinished op of this request
-        if ((rc = host_wait_op(p, q.last))) return rc;
-        arena_give(p, im.ext);
-      }
+      if (q.has_image) arena_give(p, im.ext);  // its last op has finished (step 3)
       im.ext = it.new_ext;
       im.n = im.mapped = 0;
       im.valid.clear();
@@ -274,10 +282,14 @@ int32_t do_swap_out(kv_pool* p, std::vector<OutItem>& items, int32_t* out_n_move
     }
   }
   if (out_n_moved) *out_n_moved = (int32_t)total_moved;
-  if (direct) return enqueue_direct(p, true, mv, pre, op, direct == 2);
-  if (p->mapped_out && (p->mapped_out_max == 0 || (int64_t)mv.size() <= p->mapped_out_max))
-    return enqueue_out_mapped(p, mv, pre, op);
-  return enqueue_out(p, mv, pre, op);
+  if (direct)
+    rc = enqueue_direct(p, true, mv, pre, op, direct == 2);
+  else if (p->mapped_out && (p->mapped_out_max == 0 || (int64_t)mv.size() <= p->mapped_out_max))
+    rc = enqueue_out_mapped(p, mv, pre, op);
+  else
+    rc = enqueue_out(p, mv, pre, op);
+  op->issued = true;  // also after a failed enqueue, so that polling does not stop here for ever
+  return rc;
 }
 
 
@@ -339,14 +351,17 @@ int32_t do_swap_in(kv_pool* p, std::vector<InItem>& items, int32_t* out_n_moved,
   if (out_n_moved) *out_n_moved = (int32_t)mv.size();
   if (direct) {
     pre_copy.insert(pre_copy.end(), pre_scat.begin(), pre_scat.end());
-    return enqueue_direct(p, false, mv, pre_copy, op, direct == 2);
-  }
-  if (p->mapped_in) {
+    rc = enqueue_direct(p, false, mv, pre_copy, op, direct == 2);
+  } else if (p->mapped_in) {
     pre_copy.insert(pre_copy.end(), pre_scat.begin(), pre_scat.end());
-    return enqueue_in_mapped(p, mv, pre_copy, op, layer_step);
+    rc = enqueue_in_mapped(p, mv, pre_copy, op, layer_step);
+  } else if (layer_step > 0) {
+    rc = enqueue_in_layers(p, mv, pre_copy, pre_scat, op, layer_step);
+  } else {
+    rc = enqueue_in(p, mv, pre_copy, pre_scat, op);
   }
-  if (layer_step > 0) return enqueue_in_layers(p, mv, pre_copy, pre_scat, op, layer_step);
-  return enqueue_in(p, mv, pre_copy, pre_scat, op);
+  op->issued = true;
+  return rc;
 }
 
 }  // namespace kvi

@@ -42,7 +42,9 @@ namespace {
 
 void destroy_pool(kv_pool* p) {
   if (!p->plan) {
-    (void)hipDeviceSynchronize();
+    // wait for the library's own streams only: the caller's streams are none of its business
+    for (hipStream_t s : {p->s_pack, p->s_d2h, p->s_h2d, p->s_scat, p->s_d2h2})
+      if (s) (void)hipStreamSynchronize(s);
     for (ByteRing* r : {&p->ring_out, &p->ring_in})
       for (Region& g : r->live)
         if (g.freed) (void)hipEventDestroy(g.freed);
@@ -51,6 +53,8 @@ void destroy_pool(kv_pool* p) {
         if (o->packed) (void)hipEventDestroy(o->packed);
         if (o->done) (void)hipEventDestroy(o->done);
         for (hipEvent_t e : o->aux) (void)hipEventDestroy(e);
+        for (hipEvent_t e : o->layer_ev)
+          if (e) (void)hipEventDestroy(e);
       }
     for (hipEvent_t e : p->event_pool) (void)hipEventDestroy(e);
     for (hipEvent_t e : p->timing_pool) (void)hipEventDestroy(e);
@@ -61,7 +65,7 @@ void destroy_pool(kv_pool* p) {
     if (p->ev_compute) (void)hipEventDestroy(p->ev_compute);
     if (p->s_d2h == p->s_pack) p->s_d2h = nullptr;  // aliases of the other two
     if (p->s_scat == p->s_h2d) p->s_scat = nullptr;
-    for (hipStream_t s : {p->s_pack, p->s_d2h, p->s_h2d, p->s_scat})
+    for (hipStream_t s : {p->s_pack, p->s_d2h, p->s_h2d, p->s_scat, p->s_d2h2})
       if (s) (void)hipStreamDestroy(s);
     if (p->own_staging && p->staging) (void)hipFree(p->staging);
     if (p->host) (void)hipHostFree(p->host);
@@ -271,8 +275,8 @@ static int32_t make_free(kv_pool* p, int64_t need) {
 
 int32_t alloc_block_group(kv_pool_t* p, int64_t req, int32_t n_blocks, int32_t min_run,
                           int32_t* out_blocks, int32_t* out_n_runs) {
-  (void)req;
-  if (!p || n_blocks < 0 || (n_blocks > 0 && !out_blocks)) return fail(KV_EINVAL, "bad argument");
+  (void)req;  // a label for the caller's bookkeeping; ownership is not tracked per request
+  if (!p || n_blocks < 0 || min_run < 0 || (n_blocks > 0 && !out_blocks)) return fail(KV_EINVAL, "bad argument");
   std::lock_guard<std::mutex> g(p->mu);
   reap(p);
   if (p->alloc.n_free() < n_blocks) {
@@ -286,8 +290,7 @@ int32_t alloc_block_group(kv_pool_t* p, int64_t req, int32_t n_blocks, int32_t m
   }
   std::vector<int32_t> ids;
   ids.reserve((size_t)n_blocks);
-  (void)min_run;  // largest-first allocation already honours it (see BlockGroupAllocator::alloc)
-  int32_t runs = p->alloc.alloc(n_blocks, &ids);
+  int32_t runs = p->alloc.alloc(n_blocks, &ids, min_run);
   if (n_blocks > 0) memcpy(out_blocks, ids.data(), sizeof(int32_t) * (size_t)n_blocks);
   if (out_n_runs) *out_n_runs = runs;
   return KV_OK;
@@ -601,6 +604,62 @@ int32_t kv_host_blocks(kv_pool_t* p, int64_t req, const void** arena_base, int64
   if (n != im.n) return fail(KV_EINVAL, "asked for %d blocks, host image has %d", n, im.n);
   if (arena_base) *arena_base = p->host;  // null in a plan-only pool: the records exist as bookkeeping only
   for (int32_t j = 0; j < n; ++j) record_index[j] = im.rec[(size_t)j];
+  return KV_OK;
+}
+
+int32_t kv_host_read(kv_pool_t* p, int64_t req, int32_t first_block, int32_t n_blocks, void* dst) {
+  if (!p || first_block < 0 || n_blocks < 0 || (n_blocks > 0 && !dst)) return fail(KV_EINVAL, "bad argument");
+  std::unique_lock<std::mutex> lk(p->mu);
+  auto f = p->reqs.find(req);
+  if (f == p->reqs.end() || !f->second.has_image) return fail(KV_ENOENT, "request %lld has no host copy", (long long)req);
+  if ((int64_t)first_block + n_blocks > f->second.img.n)
+    return fail(KV_EINVAL, "blocks [%d, %d) outside the host image of %d blocks", first_block,
+                first_block + n_blocks, f->second.img.n);
+  if (p->plan) return fail(KV_ENODEV, "a plan-only pool holds no bytes");
+  OpRef op = f->second.last;
+  if (op && !op->all_done) {
+    int32_t rc = wait_event_unlocked(p, lk, op->done);
+    if (rc) return rc;
+    f = p->reqs.find(req);  // the lock was dropped meanwhile
+    if (f == p->reqs.end() || !f->second.has_image || (int64_t)first_block + n_blocks > f->second.img.n)
+      return fail(KV_ENOENT, "request %lld lost its host copy during the wait", (long long)req);
+  }
+  // records of consecutive logical blocks are adjacent inside an extent: copy run by run
+  const Image& im = f->second.img;
+  char* out = (char*)dst;
+  int32_t j = first_block;
+  const int32_t end = first_block + n_blocks;
+  while (j < end) {
+    int32_t k = j;
+    const int64_t r0 = im.rec[(size_t)j];
+    if (r0 < 0) {
+      while (k + 1 < end && im.rec[(size_t)k + 1] < 0) ++k;
+      memset(out, 0, (size_t)(k - j + 1) * (size_t)p->R);
+    } else {
+      while (k + 1 < end && im.rec[(size_t)k + 1] == r0 + (k + 1 - j)) ++k;
+      memcpy(out, p->host + r0 * p->R, (size_t)(k - j + 1) * (size_t)p->R);
+    }
+    out += (int64_t)(k - j + 1) * p->R;
+    j = k + 1;
+  }
+  return KV_OK;
+}
+
+int32_t kv_host_view(kv_pool_t* p, int64_t req, const void** ptr, int64_t* bytes) {
+  if (!p || !ptr || !bytes) return fail(KV_EINVAL, "null argument");
+  std::lock_guard<std::mutex> g(p->mu);
+  auto f = p->reqs.find(req);
+  if (f == p->reqs.end() || !f->second.has_image) return fail(KV_ENOENT, "request %lld has no host copy", (long long)req);
+  if (p->plan) return fail(KV_ENODEV, "a plan-only pool holds no bytes");
+  const Image& im = f->second.img;
+  *bytes = (int64_t)im.n * p->R;
+  *ptr = nullptr;
+  if (im.n == 0) return KV_OK;
+  const int64_t r0 = im.rec[0];
+  if (r0 < 0) return KV_OK;
+  for (int32_t j = 1; j < im.n; ++j)
+    if (im.rec[(size_t)j] != r0 + j) return KV_OK;  // several extents, or records lost: use kv_host_read
+  *ptr = p->host + r0 * p->R;
   return KV_OK;
 }
 

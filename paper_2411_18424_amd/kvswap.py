@@ -2,7 +2,8 @@
 
 Every function of include/kvswap.h is exposed under its own name on ``lib``;
 ``KVPool`` is a thin convenience object around a ``kv_pool_t*`` with methods of the
-same names.  Nothing here moves or computes a byte: if the shared library is missing
+same names.  Nothing here moves, gathers or computes a byte (host images are read through
+kv_host_read / kv_host_view of the library): if the shared library is missing
 the import fails loudly (build it with ``python -m paper_2411_18424_amd.build``).
 """
 
@@ -112,6 +113,8 @@ def _load() -> C.CDLL:
         "kv_wait_all": (C.c_int32, [pool_p]),
         "kv_host_len": (C.c_int32, [pool_p, C.c_int64, i32p, i32p]),
         "kv_host_blocks": (C.c_int32, [pool_p, C.c_int64, P(C.c_void_p), i64p, C.c_int32]),
+        "kv_host_read": (C.c_int32, [pool_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p]),
+        "kv_host_view": (C.c_int32, [pool_p, C.c_int64, P(C.c_void_p), i64p]),
         "kv_host_valid": (C.c_int32, [pool_p, C.c_int64, u8p, C.c_int32]),
         "kv_host_invalidate": (C.c_int32, [pool_p, C.c_int64, u8p, C.c_int32]),
         "kv_host_release": (C.c_int32, [pool_p, C.c_int64]),
@@ -362,30 +365,26 @@ class KVPool:
         _check(lib.kv_host_blocks(self._h, req, C.byref(base), idx.ctypes.data_as(C.POINTER(C.c_int64)), n))
         return base.value, idx
 
-    def kv_host_view(self, req: int) -> np.ndarray:
-        """uint8 [n][P][C] over the host image: a zero-copy view of the pinned arena when the
-        image is one extent, else a gathered copy (reading aid for tests and tools)."""
-        base, idx = self.kv_host_blocks(req)
-        if base is None:
-            raise KVError(KV_ENODEV, "plan-only pool holds no bytes")
-        n = idx.size
-        if n == 0:
+    def kv_host_read(self, req: int, first_block: int = 0, n_blocks: int | None = None) -> np.ndarray:
+        """uint8 [n_blocks][P][C]: a copy of those logical blocks of the host image, made by the
+        library (it waits for the request first)."""
+        if n_blocks is None:
+            n_blocks = self.kv_host_len(req)[0] - first_block
+        out = np.empty((max(0, n_blocks), self.P, self.C), dtype=np.uint8)
+        _check(lib.kv_host_read(self._h, req, first_block, n_blocks, out.ctypes.data_as(C.c_void_p)))
+        return out
+
+    def kv_host_view(self, req: int):
+        """The library's zero-copy view of the image as uint8 [n][P][C], or None when the image
+        is not one run of consecutive arena records (use kv_host_read then)."""
+        ptr, nbytes = C.c_void_p(), C.c_int64()
+        _check(lib.kv_host_view(self._h, req, C.byref(ptr), C.byref(nbytes)))
+        if nbytes.value == 0:
             return np.zeros((0, self.P, self.C), dtype=np.uint8)
-        if (idx < 0).any():  # some blocks lost their record: they read as zeros
-            out = np.zeros((n, self.P, self.C), dtype=np.uint8)
-            have = np.flatnonzero(idx >= 0)
-            if have.size:
-                lo, hi = int(idx[have].min()), int(idx[have].max())
-                buf = (C.c_uint8 * ((hi - lo + 1) * self.R)).from_address(base + lo * self.R)
-                span = np.frombuffer(buf, dtype=np.uint8).reshape(hi - lo + 1, self.P, self.C)
-                out[have] = span[idx[have] - lo]
-            return out
-        lo, hi = int(idx.min()), int(idx.max())
-        buf = (C.c_uint8 * ((hi - lo + 1) * self.R)).from_address(base + lo * self.R)
-        span = np.frombuffer(buf, dtype=np.uint8).reshape(hi - lo + 1, self.P, self.C)
-        if np.array_equal(idx, np.arange(lo, lo + n)):
-            return span
-        return span[idx - lo]
+        if not ptr.value:
+            return None
+        buf = (C.c_uint8 * nbytes.value).from_address(ptr.value)
+        return np.frombuffer(buf, dtype=np.uint8).reshape(-1, self.P, self.C)
 
     def kv_host_valid(self, req: int, n: int) -> np.ndarray:
         out = np.zeros(n, dtype=np.uint8)

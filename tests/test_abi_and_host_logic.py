@@ -86,6 +86,12 @@ def test_validation_errors_and_no_effect(kv):
     with pytest.raises(kv.KVError) as ei:
         p.kv_host_view(0)
     assert ei.value.status == kv.KV_ENODEV
+    with pytest.raises(kv.KVError) as ei:
+        p.kv_host_read(0)
+    assert ei.value.status == kv.KV_ENODEV
+    with pytest.raises(kv.KVError) as ei:
+        p.kv_host_read(0, 8, 3)  # past the end of the 10-block image
+    assert ei.value.status == kv.KV_EINVAL
     with pytest.raises(kv.KVError):
         p.kv_wait(12345)
     assert p.kv_stats() == st0
@@ -196,6 +202,36 @@ def test_fragmented_pool_yields_few_long_runs(kv):
     assert runs == 3
     ids2, runs2 = p.alloc_block_group(2, 3, 1)
     assert AllocChecker.run_lengths(ids2) == [3] and ids2[0] == 64
+
+
+def test_min_run_keeps_short_fragments_out_of_a_split_request(kv):
+    """alloc_block_group's min_run: when a request has to be split, its remainder is carved from
+    a free run of at least min_run blocks while one exists; without the preference it takes the
+    best fit, which is a short fragment here."""
+    shape = synth.TINY
+    for min_run, want_tail_start in ((8, 100), (1, 64), (0, 64)):
+        p = plan_pool(kv, shape)
+        p.alloc_block_group(0, 256, 1)
+        for start, ln in ((0, 40), (64, 5), (100, 30), (200, 5)):
+            p.free_block_group(0, np.arange(start, start + ln, dtype=np.int32))
+        ids, runs = p.alloc_block_group(1, 45, min_run)
+        assert AllocChecker.run_lengths(ids) == [40, 5] and runs == 2
+        assert ids[0] == 0 and ids[40] == want_tail_start, (min_run, ids[40])
+        # a request that fits one run takes the best fit whatever min_run says
+        ids2, runs2 = p.alloc_block_group(2, 5, min_run)
+        assert runs2 == 1 and ids2[0] == (64 if want_tail_start == 100 else 200)
+        p.close()
+    # every longer run used up: the short fragments are the fallback
+    p = plan_pool(kv, shape)
+    p.alloc_block_group(0, 256, 1)
+    for start, ln in ((0, 40), (64, 5), (200, 5)):
+        p.free_block_group(0, np.arange(start, start + ln, dtype=np.int32))
+    ids, runs = p.alloc_block_group(1, 44, 8)
+    assert AllocChecker.run_lengths(ids) == [40, 4] and ids[40] == 64
+    with pytest.raises(kv.KVError) as ei:
+        p.alloc_block_group(2, 1, -1)
+    assert ei.value.status == kv.KV_EINVAL
+    p.close()
 
 
 def test_plan_counts_copies_and_launches(kv):

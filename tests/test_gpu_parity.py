@@ -363,13 +363,86 @@ def test_swap_ins_into_the_same_blocks_land_in_call_order(harness, flags):
         h.assert_pool_equal()
 
 
+@pytest.mark.parametrize("flags", [0, 8, 128], ids=["two_streams", "four_streams", "three_streams"])
+def test_older_writer_on_another_stream_is_waited_for(harness, flags):
+    """Three swap-ins, no host wait between them: a slow one by per-block copies on the copy
+    stream into blocks Ta, a small staged one into Tb, then one over Ta and Tb together.  The
+    last call's scatter must land after BOTH earlier writers although conflict detection waits
+    for the newest of them only: completion events of a direction fire in issue order."""
+    shape = synth.KVShape("s", 8, 8, 128, 16, 2, 512, "bf16")  # R = 512 KiB
+    h = harness(shape, cfg=35, host_bytes=512 * MiB, fill="random", flags=flags)
+    rng = synth.rng_for(35)
+    perm = rng.permutation(512).astype(np.int32)
+    src_a, src_b, src_c = perm[:200], perm[200:204], perm[204:408]
+    ta, tb = perm[408:508][:96], perm[508:512]
+    ta = np.concatenate([ta, perm[:104]])          # 200 blocks for request 0
+    for r, t in ((0, src_a), (1, src_b), (2, src_c)):
+        h.pool.swap_out(r, t)
+        h.oracle.swap_out(r, t)
+    h.pool.kv_wait_all()
+    for rep in range(2):
+        h.pool.swap_in_direct(0, ta, per_block=True)   # 3200 small copies: slow
+        h.pool.swap_in(1, tb)
+        h.pool.swap_in(2, np.concatenate([ta, tb]))
+        h.oracle.swap_in(0, ta)
+        h.oracle.swap_in(1, tb)
+        h.oracle.swap_in(2, np.concatenate([ta, tb]))
+        h.pool.kv_wait(2)
+        h.assert_pool_equal()
+        ta = ta[::-1].copy()
+
+
+def test_full_swap_out_of_a_grown_request_while_its_swap_in_is_in_flight(harness):
+    """A request is swapped in and, before that has finished, swapped out in full with a table
+    that no longer fits its old host image: the old image must not be given back under the
+    running swap-in, and the new op must not be reported done before it has run."""
+    shape = synth.KVShape("s", 8, 8, 128, 16, 2, 1024, "bf16")  # R = 512 KiB
+    h = harness(shape, cfg=36, host_bytes=600 * MiB, fill="random")
+    rng = synth.rng_for(36)
+    perm = rng.permutation(1024).astype(np.int32)
+    t1, t2, extra = perm[:300], perm[300:600], perm[600:700]
+    h.pool.swap_out(7, t1)
+    h.oracle.swap_out(7, t1)
+    h.pool.kv_wait(7)
+    for rep in range(2):
+        grown = np.concatenate([t2, extra])   # 400 blocks > 300 + 32 of slack: the image is rebuilt
+        h.pool.swap_in(7, t2)                 # 150 MiB, about 3 ms on the link
+        h.pool.swap_out(7, grown)             # 200 MiB, issued at once
+        done_at_once = h.pool.kv_query(7)
+        h.oracle.swap_in(7, t2)
+        h.oracle.swap_out(7, grown)
+        assert not done_at_once, "a 200 MiB swap-out cannot be complete microseconds after the call"
+        h.pool.kv_wait_packed(7)
+        h.assert_image_equal(7)
+        h.assert_pool_equal()
+        # back to 300 blocks through a different table for the second round
+        h.pool.kv_host_release(7)
+        h.oracle.host_release(7)
+        h.pool.swap_out(7, t1)
+        h.oracle.swap_out(7, t1)
+        h.pool.kv_wait(7)
+        t2 = perm[700:1000]
+
+
+def test_a_c_caller_reads_host_images_in_the_contract_layout():
+    """tests/host/host_read_check.cpp (built by paper_2411_18424_amd.build): kv_host_read and
+    kv_host_view from a C++ program, including an image that continues in a second extent."""
+    import os
+    import subprocess
+    exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "host", "host_read_check.bin")
+    if not os.path.exists(exe):
+        pytest.skip("tests/host/host_read_check.bin is not built (python -m paper_2411_18424_amd.build)")
+    run = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=120)
+    assert run.returncode == 0 and "host_read_check: 0 failures" in run.stdout, run.stdout[-3000:]
+
+
 def test_empty_request_and_queries(harness):
     h = harness(synth.TINY, cfg=11)
     h.pool.swap_out(0, np.zeros(0, np.int32))
     h.oracle.swap_out(0, [])
     h.pool.kv_wait(0)
     assert h.pool.kv_query(0)
-    assert h.pool.kv_host_view(0).shape[0] == 0
+    assert h.pool.kv_host_view(0).shape[0] == 0 and h.pool.kv_host_read(0).shape[0] == 0
     h.pool.swap_in(0, np.zeros(0, np.int32))
     h.pool.kv_wait(0)
     h.assert_pool_equal()

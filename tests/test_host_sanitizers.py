@@ -41,3 +41,19 @@ def test_host_logic_is_clean_under(kind, tmp_path):
     assert run.returncode == 0, run.stdout[-4000:]
     assert "plan_stress: 0 failures" in run.stdout, run.stdout[-2000:]
     assert "Sanitizer" not in run.stdout, run.stdout[-4000:]
+
+
+def test_polling_never_harvests_an_op_that_is_still_being_enqueued(tmp_path):
+    """tests/host/reap_unissued.cpp: the engine's completion polling against an op whose events
+    are not recorded yet (the runtime reports such events as complete).  Host only."""
+    hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+    if not os.path.exists(hipcc):
+        pytest.skip("hipcc not found")
+    exe = str(tmp_path / "reap_unissued")
+    srcs = [os.path.join(ROOT, "tests", "host", "reap_unissued.cpp")] + SOURCES[1:]
+    build = subprocess.run([hipcc] + FLAGS + SANITIZERS["address_undefined"] + srcs + ["-o", exe],
+                           stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=600)
+    assert build.returncode == 0, build.stdout[-4000:]
+    run = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=60,
+                         env=dict(os.environ, ASAN_OPTIONS="detect_leaks=0"))
+    assert run.returncode == 0 and "reap_unissued: 0 failures" in run.stdout, run.stdout[-4000:]
