@@ -187,6 +187,25 @@ int32_t swap_out(kv_pool_t* pool, int64_t req, const int32_t* block_table, int32
  * is KV_EINVAL.  out_n_moved may be NULL. */
 int32_t swap_out_delta(kv_pool_t* pool, int64_t req, const int32_t* block_table, int32_t n_blocks,
                        const uint8_t* dirty_mask, int32_t* out_n_moved);
+/* For callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  A variant of swap_out that allocates nothing, on the device or
+ * through any library, and keeps no state: the gather kernel packs the listed blocks into a
+ * staging array that is part of the library's code object (KV_STATIC_STAGING_BYTES = 64 MiB,
+ * held by every GPU the library runs on until the process ends; its address on the pool's
+ * device is looked up once, in kv_pool_create), and one copy takes them from there to
+ * host_dst, both enqueued on `stream`.  host_dst: caller-owned host memory, pinned for the
+ * copy to be asynchronous, n_blocks * R bytes, layout dst[j][p][C] (the host-image layout).
+ * stream: the caller's hipStream_t; NULL = a stream of the library, and the call then
+ * returns when the bytes have arrived.  No request, no host image, no reuse map and no
+ * conflict tracking are involved: ordering against other work on the blocks is the
+ * caller's, by stream order.
+ * Limits: n_blocks <= 896 and n_blocks * R <= 64 MiB, else KV_EINVAL (nothing is enqueued).
+ * KV_EINVAL also for ids out of range or repeated; KV_ENODEV in a plan-only pool.
+ * All calls on one GPU share the one staging array, which keeps the last call's bytes: calls
+ * whose device work overlaps on one GPU (different streams, or several pools) race. */
+int32_t swap_out_static(kv_pool_t* pool, const int32_t* block_table, int32_t n_blocks, void* host_dst,
+                        void* stream);
+
 /* Section 3.2 swap-in path.  Copies the host image into new_block_table's blocks.  The
  * image is kept (Section 3.3).  When one scheduling step both resumes and preempts, issue the
  * swap-in the scheduler will wait for before the swap-out: calls reach the copy engines in

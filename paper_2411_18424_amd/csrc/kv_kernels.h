@@ -61,3 +61,9 @@ int64_t kv_max_launch_blocks(uint32_t C, uint32_t P, int unroll, int variant);
 hipError_t kv_launch_linear_copy(void* dst, const void* src, int64_t bytes, hipStream_t stream,
                                  hipEvent_t start, hipEvent_t stop);
 int kv_pick_unroll(uint32_t C, int wg);
+
+// Staging for callers that may not allocate: a file-scope device array that every GPU the
+// library runs on holds until the process ends.  kv_static_staging() returns its address on
+// the CURRENT device (looked up once per device; null + an error code if that fails).
+#define KV_STATIC_STAGING_BYTES (64ll << 20)
+hipError_t kv_static_staging(char** ptr);

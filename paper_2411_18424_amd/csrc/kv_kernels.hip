@@ -36,6 +36,7 @@
 #include <hip/hip_ext.h>
 
 #include <algorithm>
+#include <mutex>
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
@@ -319,6 +320,30 @@ hipError_t kv_launch_pack(bool scatter, const KvPackArgs& a_in, int unroll, int 
   KV_CASE(1024, 2)
 #undef KV_CASE
   return hipErrorInvalidValue;
+}
+
+// Staging of the entry point that allocates nothing.  In host code this name is only a handle
+// for hipGetSymbolAddress; kernels and copies get the address that call returns.
+static __device__ __align__(256) unsigned char scratch[KV_STATIC_STAGING_BYTES];
+
+hipError_t kv_static_staging(char** ptr) {
+  constexpr int MAX_DEV = 64;
+  static char* addr[MAX_DEV];  // per device: each GPU holds its own copy of the array
+  static std::mutex mu;
+  *ptr = nullptr;
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= MAX_DEV) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> g(mu);
+  if (!addr[dev]) {
+    void* a = nullptr;
+    e = hipGetSymbolAddress(&a, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    addr[dev] = (char*)a;
+  }
+  *ptr = addr[dev];
+  return hipSuccess;
 }
 
 hipError_t kv_launch_linear_copy(void* dst, const void* src, int64_t bytes, hipStream_t stream,

@@ -146,6 +146,7 @@ struct kv_pool {
   int64_t arena_blocks = 0;
   bool own_staging = false;
   char* staging = nullptr;
+  char* static_staging = nullptr;  // this device's address of the library's file-scope staging array
   kvi::ByteRing ring_out, ring_in;
   hipStream_t s_pack = nullptr, s_d2h = nullptr, s_h2d = nullptr, s_scat = nullptr;
   hipStream_t s_d2h2 = nullptr;  // second device-to-host copy stream (small copies alternate), or null

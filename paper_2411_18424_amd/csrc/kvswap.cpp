@@ -206,6 +206,8 @@ int32_t kv_pool_create(const kv_pool_config_t* cfg, kv_pool_t** out) {
       if (e != hipSuccess) return bail(fail(KV_ENOMEM_GPU, "hipMalloc(staging %lld): %s", (long long)(out_cap + in_cap), hipGetErrorString(e)));
       p->own_staging = true;
     }
+    // address of the static staging array on this device (swap_out_static)
+    TRY_OR_BAIL(kv_static_staging(&p->static_staging));
     // The first copies of a process in each direction block the host for milliseconds while
     // the runtime sets its copy paths up: take that here, not inside the first swap.
     if (p->host) {
@@ -396,6 +398,42 @@ int32_t swap_out_delta(kv_pool_t* p, int64_t req, const int32_t* block_table, in
   std::vector<OutItem> items(1);
   items[0] = OutItem{req, block_table, n_blocks, dirty_mask ? dirty_mask : &none};
   return do_swap_out(p, items, out_n_moved);
+}
+
+int32_t swap_out_static(kv_pool_t* p, const int32_t* block_table, int32_t n_blocks, void* host_dst,
+                        void* stream) {
+  if (!p || n_blocks < 0 || (n_blocks > 0 && (!block_table || !host_dst))) return fail(KV_EINVAL, "bad argument");
+  if (p->plan) return fail(KV_ENODEV, "a plan-only pool moves no bytes");
+  if (n_blocks > KV_MAX_LAUNCH_BLOCKS || (int64_t)n_blocks * p->R > KV_STATIC_STAGING_BYTES)
+    return fail(KV_EINVAL, "%d blocks (%lld bytes) exceed the static staging: at most %d blocks and %lld bytes per call",
+                n_blocks, (long long)((int64_t)n_blocks * p->R), KV_MAX_LAUNCH_BLOCKS,
+                (long long)KV_STATIC_STAGING_BYTES);
+  if (!p->static_staging) return fail(KV_EHIP, "static staging has no address on this device");
+  {
+    std::lock_guard<std::mutex> g(p->mu);  // the duplicate stamps are shared with the other entry points
+    ++p->epoch;
+    for (int32_t i = 0; i < n_blocks; ++i) {
+      const int64_t b = block_table[i];
+      if (b < 0 || b >= p->N) return fail(KV_EINVAL, "block id %lld out of range [0,%lld)", (long long)b, (long long)p->N);
+      if (p->stamp[(size_t)b] == p->epoch) return fail(KV_EINVAL, "block id %lld named twice", (long long)b);
+      p->stamp[(size_t)b] = p->epoch;
+    }
+  }
+  if (n_blocks == 0) return KV_OK;
+  hipStream_t s = stream ? (hipStream_t)stream : p->s_pack;
+  KvPackArgs a;  // on the stack: the block table travels in the kernel arguments
+  a.pool = p->gpu;
+  a.staging = p->static_staging;
+  a.plane_stride = p->N * p->C;
+  a.C = (uint32_t)p->C;
+  a.P = (uint32_t)p->P;
+  a.m = (uint32_t)n_blocks;
+  a.tiles_per_chunk = a.n_tiles = a.pad = 0;
+  for (int32_t i = 0; i < n_blocks; ++i) a.table[i] = block_table[i];
+  HIP_TRY(kv_launch_pack(false, a, p->unroll, p->variant, p->grid, s, nullptr, nullptr));
+  HIP_TRY(hipMemcpyAsync(host_dst, p->static_staging, (size_t)n_blocks * (size_t)p->R, hipMemcpyDeviceToHost, s));
+  if (!stream) HIP_TRY(hipStreamSynchronize(s));
+  return KV_OK;
 }
 
 int32_t swap_in(kv_pool_t* p, int64_t req, const int32_t* new_block_table, int32_t n_blocks) {

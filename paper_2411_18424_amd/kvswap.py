@@ -97,6 +97,7 @@ def _load() -> C.CDLL:
         "kv_bg_stats": (C.c_int32, [pool_p, P(kv_bg_stats_t)]),
         "swap_out": (C.c_int32, [pool_p, C.c_int64, i32p, C.c_int32]),
         "swap_out_delta": (C.c_int32, [pool_p, C.c_int64, i32p, C.c_int32, u8p, i32p]),
+        "swap_out_static": (C.c_int32, [pool_p, i32p, C.c_int32, C.c_void_p, C.c_void_p]),
         "swap_in": (C.c_int32, [pool_p, C.c_int64, i32p, C.c_int32]),
         "swap_in_delta": (C.c_int32, [pool_p, C.c_int64, i32p, C.c_int32, u8p, i32p]),
         "swap_out_direct": (C.c_int32, [pool_p, C.c_int64, i32p, C.c_int32, C.c_int32]),
@@ -280,6 +281,11 @@ class KVPool:
         n = C.c_int32()
         _check(lib.swap_out_delta(self._h, req, p, a.size, mp, C.byref(n)))
         return n.value
+
+    def swap_out_static(self, block_table, host_dst: int, stream: int = 0):
+        """host_dst: address of caller-owned (pinned) host memory of len(block_table) * R bytes."""
+        a, p = _i32(block_table)
+        _check(lib.swap_out_static(self._h, p, a.size, host_dst or None, stream or None))
 
     def swap_in(self, req: int, new_block_table):
         a, p = _i32(new_block_table)

@@ -1,0 +1,52 @@
+"""swap_out_static, the entry point that allocates nothing, against swap_out (and the oracle):
+two calls in a row, the second with a smaller input, through the C ABI."""
+
+import numpy as np
+import pytest
+
+from paper_2411_18424_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+MiB = 1 << 20
+
+
+def test_swap_out_static_matches_swap_out():
+    import torch
+    from gpu_util import Harness
+    shape = synth.KVShape("s", 8, 8, 128, 16, 2, 512, "bf16")  # C = 32 KiB, R = 512 KiB
+    h = Harness(shape, 71, 256 * MiB, fill="random")
+    try:
+        kv, pool = h.kv, h.pool
+        rng = synth.rng_for(71)
+        dst = torch.empty(128 * shape.R, dtype=torch.uint8).pin_memory()
+        dst.fill_(0xEE)
+        side = torch.cuda.Stream()
+        for call, (req, n) in enumerate(((0, 128), (1, 37))):   # 64 MiB (the limit), then 18.5 MiB
+            table = rng.permutation(shape.n_blocks)[:n].astype(np.int32)
+            # the existing entry point and the definition
+            pool.swap_out(req, table)
+            h.oracle.swap_out(req, table)
+            want = pool.kv_host_read(req)
+            assert np.array_equal(want, h.oracle.host[req].Hq)
+            # the allocation-free variant: on the caller's stream, then on the library's
+            for stream in (side.cuda_stream, 0):
+                dst.fill_(0xEE)
+                pool.swap_out_static(table, dst.data_ptr(), stream)
+                if stream:
+                    side.synchronize()
+                got = dst.numpy()[:n * shape.R].reshape(n, shape.P, shape.C)
+                assert np.array_equal(got, want), "call %d differs from swap_out" % call
+                assert (dst.numpy()[n * shape.R:] == 0xEE).all(), "wrote past n_blocks * R"
+        h.assert_pool_equal()  # a swap-out changes nothing on the GPU
+        # limits and validation: nothing is enqueued
+        dst.fill_(0x11)
+        for bad in (np.arange(129, dtype=np.int32), np.array([3, 3], np.int32), np.array([512], np.int32)):
+            with pytest.raises(kv.KVError) as ei:
+                pool.swap_out_static(bad, dst.data_ptr(), 0)
+            assert ei.value.status == kv.KV_EINVAL
+        pool.swap_out_static(np.zeros(0, np.int32), dst.data_ptr(), 0)
+        torch.cuda.synchronize()
+        assert (dst.numpy() == 0x11).all()
+    finally:
+        h.close()
