@@ -84,6 +84,9 @@ typedef enum {
 #define KV_FLAG_SCATTER_STREAM 128u /* three streams: the scatter kernels get a stream of their own, so the
                                        scatter of a piece runs under the next piece's host-to-device copy */
 
+#define KV_FLAG_NO_STRIDED_COPIES 256u /* one copy per run of adjacent host records, never a 2-D copy over
+                                       several equal runs a constant stride apart (for comparison) */
+
 typedef struct kv_pool kv_pool_t;
 
 typedef struct {
@@ -307,6 +310,7 @@ typedef struct {
   int64_t host_new_extents;             /* image growths that had to open a new arena extent */
   int64_t host_evicted_blocks;          /* logical blocks whose host copy was reclaimed (KV_FLAG_HOST_EVICT) */
   int64_t host_arena_used, host_arena_bytes;
+  int64_t strided_copies;               /* of d2h_copies + h2d_copies: 2-D copies that carry several runs */
 } kv_stats_t;
 int32_t kv_stats(kv_pool_t* pool, kv_stats_t* out);
 

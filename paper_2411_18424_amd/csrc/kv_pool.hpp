@@ -155,6 +155,7 @@ struct kv_pool {
   int unroll = 0, grid = 0, variant = 0;
   int64_t launch_blocks = KV_MAX_LAUNCH_BLOCKS;  // most blocks one pack launch carries
   int64_t copy_chunk = 0;
+  bool strided_copies = true;  // equal runs a constant stride apart go out as rows of one 2-D copy
   int64_t slack = 32;
 
   std::mutex mu;
@@ -189,6 +190,7 @@ void reap(kv_pool* p);
 Op* find_op(std::deque<OpRef>& dq, uint64_t seq);
 int32_t host_wait_op(kv_pool* p, const OpRef& op);
 int32_t new_op(kv_pool* p, bool is_out, OpRef* out);
+void order_for_strided_copies(kv_pool* p, std::vector<Move>& mv);
 int32_t enqueue_out(kv_pool* p, const std::vector<Move>& mv, const std::vector<hipEvent_t>& pre,
                     const OpRef& op);
 int32_t enqueue_in(kv_pool* p, const std::vector<Move>& mv, const std::vector<hipEvent_t>& pre_copy,

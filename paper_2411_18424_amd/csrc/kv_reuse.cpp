@@ -286,8 +286,10 @@ int32_t do_swap_out(kv_pool* p, std::vector<OutItem>& items, int32_t* out_n_move
     rc = enqueue_direct(p, true, mv, pre, op, direct == 2);
   else if (p->mapped_out && (p->mapped_out_max == 0 || (int64_t)mv.size() <= p->mapped_out_max))
     rc = enqueue_out_mapped(p, mv, pre, op);
-  else
+  else {
+    order_for_strided_copies(p, mv);
     rc = enqueue_out(p, mv, pre, op);
+  }
   op->issued = true;  // also after a failed enqueue, so that polling does not stop here for ever
   return rc;
 }
@@ -358,6 +360,7 @@ int32_t do_swap_in(kv_pool* p, std::vector<InItem>& items, int32_t* out_n_moved,
   } else if (layer_step > 0) {
     rc = enqueue_in_layers(p, mv, pre_copy, pre_scat, op, layer_step);
   } else {
+    order_for_strided_copies(p, mv);
     rc = enqueue_in(p, mv, pre_copy, pre_scat, op);
   }
   op->issued = true;

@@ -119,6 +119,7 @@ int32_t kv_pool_create(const kv_pool_config_t* cfg, kv_pool_t** out) {
   p->host_evict = (cfg->flags & KV_FLAG_HOST_EVICT) != 0;
   p->mapped_out = (cfg->flags & KV_FLAG_MAPPED_SWAP_OUT) != 0;
   p->mapped_out_max = cfg->mapped_out_max_blocks;
+  p->strided_copies = (cfg->flags & KV_FLAG_NO_STRIDED_COPIES) == 0;
   if (cfg->mapped_in_grid > 0) p->mapped_grid = cfg->mapped_in_grid;
   p->launch_blocks = kv_max_launch_blocks((uint32_t)C, (uint32_t)p->P, p->unroll, p->variant);
   // staging rings: defaults scale with the pool, capped at 4 GiB (out) and 1 GiB (in)
@@ -196,14 +197,20 @@ int32_t kv_pool_create(const kv_pool_config_t* cfg, kv_pool_t** out) {
     TRY_OR_BAIL(hipEventCreateWithFlags(&p->ev_compute, hipEventDisableTiming));
     if (p->arena_blocks > 0) {
       hipError_t e = hipHostMalloc((void**)&p->host, (size_t)(p->arena_blocks * p->R), hipHostMallocDefault);
-      if (e != hipSuccess) return bail(fail(KV_ENOMEM_HOST, "hipHostMalloc(%lld): %s", (long long)(p->arena_blocks * p->R), hipGetErrorString(e)));
+      if (e != hipSuccess) {
+        (void)hipGetLastError();  // do not leave the refusal behind for the caller's next runtime call to report
+        return bail(fail(KV_ENOMEM_HOST, "hipHostMalloc(%lld): %s", (long long)(p->arena_blocks * p->R), hipGetErrorString(e)));
+      }
       TRY_OR_BAIL(hipHostGetDevicePointer((void**)&p->host_dev, p->host, 0));
     }
     if (cfg->staging_base) {
       p->staging = (char*)cfg->staging_base;
     } else {
       hipError_t e = hipMalloc((void**)&p->staging, (size_t)(out_cap + in_cap));
-      if (e != hipSuccess) return bail(fail(KV_ENOMEM_GPU, "hipMalloc(staging %lld): %s", (long long)(out_cap + in_cap), hipGetErrorString(e)));
+      if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return bail(fail(KV_ENOMEM_GPU, "hipMalloc(staging %lld): %s", (long long)(out_cap + in_cap), hipGetErrorString(e)));
+      }
       p->own_staging = true;
     }
     // address of the static staging array on this device (swap_out_static)

@@ -21,6 +21,7 @@ KV_OK, KV_EINVAL, KV_ENOMEM_GPU, KV_ENOMEM_HOST = 0, -1, -2, -3
 KV_ENOENT, KV_EBUSY, KV_EHIP, KV_ENODEV = -4, -5, -6, -7
 KV_FLAG_PLAN_ONLY, KV_FLAG_PROFILE, KV_FLAG_ORDER_COMPUTE, KV_FLAG_FOUR_STREAMS = 1, 2, 4, 8
 KV_FLAG_MAPPED_SWAP_IN, KV_FLAG_HOST_EVICT, KV_FLAG_MAPPED_SWAP_OUT, KV_FLAG_SCATTER_STREAM = 16, 32, 64, 128
+KV_FLAG_NO_STRIDED_COPIES = 256
 KV_TASK_SWAP_OUT, KV_TASK_SWAP_IN, KV_TASK_SWAP_OUT_DELTA, KV_TASK_SWAP_IN_DELTA = 0, 1, 2, 3
 
 _STATUS_NAMES = {0: "KV_OK", -1: "KV_EINVAL", -2: "KV_ENOMEM_GPU", -3: "KV_ENOMEM_HOST",
@@ -51,7 +52,8 @@ class kv_stats_t(C.Structure):
     _fields_ = [(n, C.c_int64) for n in (
         "bytes_out", "bytes_in", "blocks_out", "blocks_in", "gather_launches",
         "scatter_launches", "d2h_copies", "h2d_copies", "conflict_waits",
-        "host_new_extents", "host_evicted_blocks", "host_arena_used", "host_arena_bytes")]
+        "host_new_extents", "host_evicted_blocks", "host_arena_used", "host_arena_bytes",
+        "strided_copies")]
 
 
 class kv_bg_stats_t(C.Structure):

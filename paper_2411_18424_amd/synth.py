@@ -178,6 +178,37 @@ class PoolContent:
         torch.cuda.synchronize()
 
 
+    def fill_device_payload(self, gpu_flat, blocks, ids) -> None:
+        """payload(ids) written into the physical blocks `blocks` of a flat uint8 torch tensor on
+        the GPU, generated there (only window indices and stamps cross the host link)."""
+        import torch
+        s = self.shape
+        dev = gpu_flat.device
+        view = gpu_flat.view(s.P, s.n_blocks, s.C)
+        if not hasattr(self, "_base_dev") or self._base_dev.device != dev:
+            self._base_dev = torch.from_numpy(self.base).to(dev)
+        blocks = np.asarray(blocks, dtype=np.int64)
+        ids = np.asarray(ids, dtype=np.int64)
+        assert blocks.shape == ids.shape
+        bidx = torch.from_numpy(blocks).to(dev)
+        ps = np.arange(s.P)
+        win = torch.from_numpy(self.window(ps[:, None], ids[None, :])).to(dev)      # [P][n]
+        st = torch.from_numpy(self.stamp(np.broadcast_to(ps[:, None], win.shape), np.broadcast_to(ids[None, :], win.shape))
+                              .view(np.uint8).reshape(s.P, ids.size, 16)).to(dev)
+        for p in range(s.P):
+            chunk = torch.index_select(self._base_dev, 0, win[p])
+            chunk[:, :16] = st[p]
+            view[p, bidx, :] = chunk
+
+    def heads(self, ids) -> np.ndarray:
+        """First 16 bytes of every chunk of payload(ids): uint8 [len(ids)][P][16] (the stamps)."""
+        ids = np.asarray(ids, dtype=np.int64)
+        ps = np.arange(self.shape.P)
+        st = self.stamp(np.broadcast_to(ps[None, :], (ids.size, ps.size)),
+                        np.broadcast_to(ids[:, None], (ids.size, ps.size)))
+        return st.view(np.uint8).reshape(ids.size, self.shape.P, 16)
+
+
 def fresh_tokens(rng: np.random.Generator, shape: KVShape, n_blocks: int) -> np.ndarray:
     """Random replacement payload for n_blocks whole blocks: uint8 [n][P][C]."""
     elts = normal_elements(rng, n_blocks * shape.R // shape.elt_bytes, shape.dtype)

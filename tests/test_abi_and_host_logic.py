@@ -253,6 +253,39 @@ def test_plan_counts_copies_and_launches(kv):
     assert st2["d2h_copies"] - st["d2h_copies"] == 3 + 1
 
 
+def test_scattered_records_travel_as_rows_of_strided_copies(kv):
+    """Equal runs of host records a constant stride apart become one 2-D copy: the dirty blocks
+    {1, 5, 9, 13} (stride 4) and {20, 22} of a 40-block image cost two copies instead of six, a
+    run of three next to them one more; the same for a partial swap-in."""
+    shape = synth.TINY
+    for flags, want_out, want_in in ((0, 3, 3), (kv.KV_FLAG_NO_STRIDED_COPIES, 7, 7)):
+        p = plan_pool(kv, shape, host_blocks=128, flags_extra=flags)
+        t = np.arange(40, dtype=np.int32)
+        p.swap_out(0, t)
+        base = p.kv_stats()
+        dirty = np.zeros(40, np.uint8)
+        dirty[[1, 5, 9, 13, 20, 22, 30, 31, 32]] = 1
+        assert p.swap_out_delta(0, t, dirty) == 9
+        st = p.kv_stats()
+        assert st["d2h_copies"] - base["d2h_copies"] == want_out
+        assert st["strided_copies"] == (2 if flags == 0 else 0)
+        assert st["bytes_out"] - base["bytes_out"] == 9 * shape.R
+        assert p.swap_in_delta(0, t, 1 - dirty) == 9
+        st2 = p.kv_stats()
+        assert st2["h2d_copies"] - st["h2d_copies"] == want_in
+        p.close()
+    # rows may not be cut: a chain is limited by copy_chunk_bytes
+    p = plan_pool(kv, shape, host_blocks=128, copy_chunk_bytes=2 * shape.R)
+    t = np.arange(40, dtype=np.int32)
+    p.swap_out(0, t)
+    base = p.kv_stats()
+    dirty = np.zeros(40, np.uint8)
+    dirty[[1, 5, 9, 13]] = 1
+    p.swap_out_delta(0, t, dirty)
+    assert p.kv_stats()["d2h_copies"] - base["d2h_copies"] == 2  # two copies of two rows
+    p.close()
+
+
 def test_layerwise_swap_in_plan(kv):
     """Layer-wise swap-in: per step of layers one 2-D copy per run of adjacent host records
     (rows cut at copy_chunk_bytes) and one scatter per ring piece; pieces hold more blocks

@@ -230,6 +230,46 @@ def test_multi_turn_delta_and_contamination(harness):
     assert st["host_new_extents"] >= 1 or st["host_arena_used"] > 0
 
 
+@pytest.mark.parametrize("flags", [0, 256], ids=["strided_copies", "one_copy_per_run"])
+def test_scattered_dirty_blocks_and_scattered_swap_in(harness, flags):
+    """Random 20 % dirty masks over a 200-block image, three turns, and swap-ins that skip a
+    random resident set: the scattered records travel as rows of 2-D copies (or one by one),
+    the image and the pool must match the oracle byte for byte either way."""
+    shape = synth.KVShape("s", 8, 8, 128, 16, 2, 512, "bf16")  # R = 512 KiB
+    h = harness(shape, cfg=37, host_bytes=256 * MiB, fill="random", flags=flags, host_slack_blocks=8)
+    rng = synth.rng_for(37)
+    t = rng.permutation(512)[:200].astype(np.int32)
+    h.pool.swap_out(0, t)
+    h.oracle.swap_out(0, t)
+    # a second image right behind the first one, so that growth opens a second extent
+    other = np.setdiff1d(np.arange(512), t)[:20].astype(np.int32)
+    h.pool.swap_out(1, other)
+    h.oracle.swap_out(1, other)
+    h.assert_image_equal(0)
+    spare = np.setdiff1d(np.arange(512), np.concatenate([t, other])).astype(np.int32)
+    for turn in range(3):
+        grow = spare[turn * 15:(turn + 1) * 15]
+        t = np.concatenate([t, grow]).astype(np.int32)
+        dirty = synth.random_mask(rng, t.size, 0.2)
+        dirty[-15:] = 1
+        touched = np.flatnonzero(dirty)
+        h.overwrite_blocks(t[touched], synth.fresh_tokens(rng, shape, touched.size))
+        moved = h.pool.swap_out_delta(0, t, dirty)
+        want = h.oracle.swap_out_delta(0, t, dirty)
+        assert moved == len(want)
+        h.assert_image_equal(0)
+        # scramble the request's GPU blocks, keep a random resident set, bring the rest back
+        resident = synth.random_mask(rng, t.size, 0.6)
+        lost = np.flatnonzero(resident == 0)
+        h.overwrite_blocks(t[lost], np.full((lost.size, shape.P, shape.C), 0xDD, np.uint8))
+        assert h.pool.swap_in_delta(0, t, resident) == len(h.oracle.swap_in(0, t, resident=resident))
+        h.pool.kv_wait(0)
+        h.assert_pool_equal()
+    st = h.pool.kv_stats()
+    assert (st["strided_copies"] > 0) == (flags == 0)
+    assert st["bytes_out"] == h.oracle.bytes_out and st["bytes_in"] == h.oracle.bytes_in
+
+
 def test_partial_swap_in_moves_only_non_resident_blocks(harness):
     h = harness(synth.TINY, cfg=8)
     rng = synth.rng_for(8)
