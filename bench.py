@@ -67,9 +67,9 @@ def device_state():
     return out
 
 
-def cpu_baseline(work, budget_s=12.0):
-    """The CPU oracle, as it stands, on the same victims: swap all out, then in through the
-    resume tables, repeated until about budget_s seconds of work.  One thread."""
+def _oracle_for(work, victims):
+    """A CPU oracle that holds the seeded content of these victims' blocks (the rest of its pool
+    stays untouched zero pages)."""
     import numpy as np
     from oracle.kv_oracle import KVOracle
     from paper_2411_18424_amd import synth
@@ -77,28 +77,92 @@ def cpu_baseline(work, budget_s=12.0):
     s = work.shape
     o = KVOracle(s.n_layers, s.n_kv_heads, s.head_dim, s.block_size, s.elt_bytes, s.n_blocks)
     content = synth.PoolContent(s, work.cfg)
-    for v in work.victims:  # only the victims' blocks are materialised (the rest stays untouched zero pages)
+    for v in victims:
         blocks = work.tables[v].astype(np.int64)
         for p in range(s.P):
             o.G[p, blocks, :] = content.plane(p, blocks)
-    cur = {v: work.tables[v] for v in work.victims}
-    nxt = {v: t for v, t in zip(work.victims, work.resume_tables)}
+    return o
+
+
+def _oracle_steps(work, o, victims, budget_s, max_steps, start=None):
+    """Swap the victims out, then in through the resume tables, repeatedly: (bytes, seconds, steps)."""
+    resume = {v: t for v, t in zip(work.victims, work.resume_tables)}
+    cur = {v: work.tables[v] for v in victims}
+    nxt = {v: resume[v] for v in victims}
+    s = work.shape
+    if start is not None:
+        start.wait()
     steps, moved = 0, 0
     t0 = time.perf_counter()
     while True:
-        for v in work.victims:
+        for v in victims:
             moved += len(o.swap_out(v, cur[v])) * s.R
-        for v in work.victims:
+        for v in victims:
             moved += len(o.swap_in(v, nxt[v])) * s.R
         cur, nxt = nxt, cur
         steps += 1
         dt = time.perf_counter() - t0
-        if dt >= budget_s or steps >= 50:
-            break
+        if dt >= budget_s or steps >= max_steps:
+            return moved, dt, steps
+
+
+def _oracle_worker(args):
+    work, victims, budget_s, start, q = args
+    o = _oracle_for(work, victims)
+    q.put((victims, _oracle_steps(work, o, victims, budget_s, 10**6, start)))
+
+
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def cpu_baseline(work, budget_s=12.0, all_cores_budget_s=8.0):
+    """The CPU oracle, as it stands, on the same victims: swap all out, then in through the
+    resume tables, repeated until about budget_s seconds of work.  (i) one thread; (ii) all the
+    cores of this machine's share, one process per core, the victims dealt to them (one request
+    per process where there are as many cores as victims), started together; the aggregate is
+    total bytes over the time of the slowest.  Runs before this process has touched the GPU."""
+    import multiprocessing as mp
+
+    s = work.shape
+    o = _oracle_for(work, work.victims)
+    moved, dt, steps = _oracle_steps(work, o, work.victims, budget_s, 50)
+    del o
     nb = sum(len(work.tables[v]) for v in work.victims)
-    return {"value": moved / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "sample": "same 16 victims (%d blocks, %.2f GiB each way), %d full out+in steps, %.1f s"
-                      % (nb, nb * s.R / GiB, steps, dt)}
+    out = {"value": moved / dt / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle", "cpu": cpu_model(),
+           "sample": "same 16 victims (%d blocks, %.2f GiB each way), %d full out+in steps, %.1f s"
+                     % (nb, nb * s.R / GiB, steps, dt)}
+    try:
+        n_cpu = len(os.sched_getaffinity(0))
+    except AttributeError:
+        n_cpu = os.cpu_count() or 1
+    n_proc = max(1, min(16, n_cpu, len(work.victims)))
+    ctx = mp.get_context("fork")
+    start, q = ctx.Barrier(n_proc), ctx.Queue()
+    # victims dealt largest first to the least loaded process
+    loads, groups = [0] * n_proc, [[] for _ in range(n_proc)]
+    for v in sorted(work.victims, key=lambda v: -len(work.tables[v])):
+        k = loads.index(min(loads))
+        groups[k].append(v)
+        loads[k] += len(work.tables[v])
+    procs = [ctx.Process(target=_oracle_worker, args=((work, g, all_cores_budget_s, start, q),)) for g in groups]
+    for p in procs:
+        p.start()
+    res = [q.get() for _ in procs]
+    for p in procs:
+        p.join()
+    tot = sum(r[1][0] for r in res)
+    slowest = max(r[1][1] for r in res)
+    out["all_cores"] = {"value": tot / slowest / 1e9, "unit": "GB/s", "cores": n_proc,
+                        "sample": "the same victims dealt to %d processes (largest first), each repeating its own "
+                                  "out+in steps for %.0f s; total bytes / %.1f s" % (n_proc, all_cores_budget_s, slowest)}
+    return out
 
 
 def main() -> int:
@@ -111,14 +175,23 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5],
                     help="workload config; 2 is the headline (default), the others print their own JSON line")
     ap.add_argument("--preemptions", type=int, default=200, help="config 3: length of the stream")
-    ap.add_argument("--conversations", type=int, default=32, help="config 4: conversations held on the host")
+    ap.add_argument("--conversations", type=int, default=128, help="config 4: conversations (in waves that fit the arena)")
+    ap.add_argument("--arena-gib", type=int, default=56, help="config 4: pinned host arena (one allocation)")
+    ap.add_argument("--no-strided-copies", action="store_true",
+                    help="one copy per run of adjacent host records (KV_FLAG_NO_STRIDED_COPIES), for comparison")
+    ap.add_argument("--no-fairness", action="store_true", help="config 3: skip the small-copy latency measurement")
+    ap.add_argument("--no-manager-pass", action="store_true", help="config 3: skip the pass through kv_manager_iterate")
+    ap.add_argument("--out-first", action="store_true",
+                    help="config 3: issue the swap-out of an iteration before its swap-in (default: swap-in first)")
     ap.add_argument("--requests", type=int, default=4, help="config 5: 10 GiB requests per run length")
     ap.add_argument("--mapped-swap-in", action="store_true",
                     help="swap-in by a kernel that reads the pinned host image directly (KV_FLAG_MAPPED_SWAP_IN)")
     ap.add_argument("--mapped-swap-out", action="store_true",
                     help="config 1: swap-out by a kernel that stores into the pinned image (KV_FLAG_MAPPED_SWAP_OUT)")
     ap.add_argument("--copy-chunk-mib", type=int, default=0,
-                    help="config 2: cut host-link copies at this many MiB (0 = the library's default)")
+                    help="configs 2 and 3: cut host-link copies at this many MiB (0 = the library's default)")
+    ap.add_argument("--max-piece-mib", type=int, default=0,
+                    help="config 2: most MiB one piece of a swap carries (0 = the library's default)")
     ap.add_argument("--scatter-stream", action="store_true",
                     help="three streams: scatter kernels on a stream of their own (KV_FLAG_SCATTER_STREAM)")
     ap.add_argument("--four-streams", action="store_true",
@@ -130,9 +203,20 @@ def main() -> int:
         return 2
 
     import numpy as np
+    from paper_2411_18424_amd import synth
+
+    # The CPU oracle is timed first, in this process, before anything has touched the GPU (its
+    # all-cores leg forks workers); the GPU is idle meanwhile and the timed region below has
+    # the host to itself.
+    cpu = None
+    if args.config == 2 and not args.no_cpu_baseline:
+        log("timing the CPU oracle (one thread, then all cores) ...")
+        cpu = cpu_baseline(synth.llama3_8b_preempt_workload())
+        log("cpu oracle: %.2f GB/s on one core, %.2f GB/s on %d (%s)"
+            % (cpu["value"], cpu["all_cores"]["value"], cpu["all_cores"]["cores"], cpu["cpu"]))
+
     import torch
     from paper_2411_18424_amd import kvswap as kv
-    from paper_2411_18424_amd import synth
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
@@ -169,7 +253,7 @@ def main() -> int:
                      | (kv.KV_FLAG_SCATTER_STREAM if args.scatter_stream else 0)
                      | (kv.KV_FLAG_MAPPED_SWAP_IN if args.mapped_swap_in else 0),
                      pack_variant=int(os.environ.get("KVSWAP_PACK_VARIANT", "0")),
-                     copy_chunk_bytes=args.copy_chunk_mib << 20)
+                     copy_chunk_bytes=args.copy_chunk_mib << 20, max_piece_bytes=args.max_piece_mib << 20)
     cur = [work.tables[v] for v in victims]
     nxt = list(work.resume_tables)
 
@@ -318,15 +402,35 @@ def main() -> int:
     del gpu
     torch.cuda.empty_cache()
 
-    # HBM bytes per gather launch from the committed rocprofv3 counter summary (FETCH_SIZE +
-    # WRITE_SIZE runs of this same command); null when the summary is not there
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "gather_llama3_8b_cfg2_pmc.txt")
-    if os.path.exists(tpath):
-        with open(tpath) as f:
-            for line in f:
-                if line.startswith("hbm_bytes_per_launch:"):
-                    traffic = int(line.split(":")[1].split()[0])
+    # HBM bytes per launch as the rocprofv3 counters read them (FETCH_SIZE and WRITE_SIZE passes of
+    # this same command, scaled by what they read for a plain copy of known size).  The counters
+    # cannot be read from inside this process: the figures are those of the committed summary,
+    # labelled as such; null when the summary is not there.
+    def profiled_traffic(fname):
+        tpath = os.path.join(ROOT, "profiles", fname)
+        if os.path.exists(tpath):
+            with open(tpath) as f:
+                for line in f:
+                    if line.startswith("hbm_bytes_per_launch:"):
+                        return (int(line.split(":")[1].split()[0]),
+                                "profiles/%s (rocprofv3 --pmc runs of this command; a stored figure, not measured in this run)" % fname)
+        return None, None
+
+    g_traffic, g_src = profiled_traffic("gather_llama3_8b_cfg2_pmc.txt")
+    s_traffic, s_src = profiled_traffic("scatter_llama3_8b_cfg2_pmc.txt")
+    pack = {
+        "gather": {"kernel": "kv_pack_xcd_kernel<256,1,true,false,true> (kv_pack_tile_kernel below 64 blocks per launch)",
+                   "achieved": round(gather_gbps, 1), "frac": round(gather_gbps / HBM_PEAK_GBPS, 4),
+                   "launches": n_g, "avg_launch_ms": round(ms_g / max(1, n_g), 4),
+                   "algorithmic_bytes_per_launch": int(2 * b_g / max(1, n_g)),
+                   "traffic": g_traffic, "traffic_source": g_src},
+        "scatter": {"kernel": "kv_pack_xcd_kernel<256,1,true,true,true> (kv_pack_tile_kernel below 64 blocks per launch)",
+                    "achieved": round(scatter_gbps, 1), "frac": round(scatter_gbps / HBM_PEAK_GBPS, 4),
+                    "launches": n_s, "avg_launch_ms": round(ms_s / max(1, n_s), 4),
+                    "algorithmic_bytes_per_launch": int(2 * b_s / max(1, n_s)),
+                    "traffic": s_traffic, "traffic_source": s_src},
+    }
+    low = "scatter" if scatter_gbps < gather_gbps else "gather"  # the headline fraction is the lower of the two
 
     result = {
         "metric": "KV swap GB/s (out+in) and per-preemption switch latency, 1 MI355X",
@@ -352,23 +456,27 @@ def main() -> int:
         "in_gbps": round(payload * args.steps / phase_s[1] / 1e9, 3),
         "roofline": {
             "bound": "hbm",
-            "kernel": "kv_pack_xcd_kernel, gather direction (kv_pack_tile_kernel below 64 blocks per launch)",
-            "achieved": round(gather_gbps, 1),
+            "kernel": "%s direction of the pack kernel (the slower of the two): %s" % (low, pack[low]["kernel"]),
+            "achieved": pack[low]["achieved"],
             "peak": HBM_PEAK_GBPS,
             "unit": "GB/s",
-            "frac": round(gather_gbps / HBM_PEAK_GBPS, 4),
-            "traffic": traffic,
-            "launches": n_g,
-            "avg_launch_ms": round(ms_g / max(1, n_g), 4),
-            "algorithmic_bytes_per_launch": int(2 * b_g / max(1, n_g)),
-            "scatter_achieved": round(scatter_gbps, 1),
-            "scatter_frac": round(scatter_gbps / HBM_PEAK_GBPS, 4),
+            "frac": pack[low]["frac"],
+            "traffic": pack[low]["traffic"],
+            "traffic_source": pack[low]["traffic_source"],
+            "launches": pack[low]["launches"],
+            "avg_launch_ms": pack[low]["avg_launch_ms"],
+            "algorithmic_bytes_per_launch": pack[low]["algorithmic_bytes_per_launch"],
+            "gather": pack["gather"],
+            "scatter": pack["scatter"],
             "device_copy_kernel_gbps": round(hbm_copy, 1),
-            # every gather launch of this process (warm-up, timed region, sampled check and the
+            # every launch of this process (warm-up, timed region, sampled check and the
             # per-request latency phases): the population a kernel trace of this command sees
             "gather_calls_whole_process": len([r for r in all_recs if r[0] == 0]),
             "gather_avg_ms_whole_process": round(
                 sum(r[2] for r in all_recs if r[0] == 0) / max(1, len([r for r in all_recs if r[0] == 0])), 4),
+            "scatter_calls_whole_process": len([r for r in all_recs if r[0] == 1]),
+            "scatter_avg_ms_whole_process": round(
+                sum(r[2] for r in all_recs if r[0] == 1) / max(1, len([r for r in all_recs if r[0] == 1])), 4),
         },
         "link": {
             "measured_peak_d2h_gbps": round(link_d2h, 2),
@@ -404,12 +512,13 @@ def main() -> int:
         },
         "device_state": dev_state,
         "streams": 4 if args.four_streams else 3 if args.scatter_stream else 2,
+        "pack_variant": int(os.environ.get("KVSWAP_PACK_VARIANT", "0")),  # development aid; 0 = the default kernels
         "swap_in_path": "mapped host reads" if args.mapped_swap_in else "staged copies + scatter",
         "verified_samples_ok": ok,
         "stats": {k: stats[k] for k in ("gather_launches", "scatter_launches", "d2h_copies", "h2d_copies")},
     }
-    if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(work)
+    if cpu is not None:
+        result["cpu_baseline"] = cpu
     print(json.dumps(result), flush=True)
     return 0 if ok else 1
 

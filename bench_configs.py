@@ -33,14 +33,22 @@ def _flags(args, kv, base=0):
     return (base | (kv.KV_FLAG_FOUR_STREAMS if args.four_streams else 0)
             | (kv.KV_FLAG_SCATTER_STREAM if getattr(args, "scatter_stream", False) else 0)
             | (kv.KV_FLAG_MAPPED_SWAP_IN if args.mapped_swap_in else 0)
-            | (kv.KV_FLAG_MAPPED_SWAP_OUT if getattr(args, "mapped_swap_out", False) else 0))
+            | (kv.KV_FLAG_MAPPED_SWAP_OUT if getattr(args, "mapped_swap_out", False) else 0)
+            | (kv.KV_FLAG_NO_STRIDED_COPIES if getattr(args, "no_strided_copies", False) else 0))
+
+
+def _variant_note():
+    """What the environment changed in the timed kernels (development aids), for the JSON line."""
+    import os
+    return {"KVSWAP_PACK_VARIANT": int(os.environ.get("KVSWAP_PACK_VARIANT", "0")),
+            "KVSWAP_MAPPED_GRID": int(os.environ.get("KVSWAP_MAPPED_GRID", "0"))}
 
 
 def _pool(kv, torch, s, host_bytes, **kw):
     import os
-    if "KVSWAP_PACK_VARIANT" in os.environ:  # development aid: force a kernel variant
+    if "KVSWAP_PACK_VARIANT" in os.environ:  # development aid: force a kernel variant (echoed in the JSON line)
         kw["pack_variant"] = int(os.environ["KVSWAP_PACK_VARIANT"])
-    if "KVSWAP_MAPPED_GRID" in os.environ:  # development aid: workgroups of the mapped kernels
+    if "KVSWAP_MAPPED_GRID" in os.environ:  # development aid: workgroups of the mapped kernels (echoed)
         kw["mapped_in_grid"] = int(os.environ["KVSWAP_MAPPED_GRID"])
     gpu = torch.empty(s.R * s.n_blocks, dtype=torch.uint8, device="cuda:0")
     pool = kv.KVPool(n_layers=s.n_layers, n_kv_heads=s.n_kv_heads, head_dim=s.head_dim,
@@ -151,7 +159,9 @@ def _copy_fairness(kv, torch, s, gpu):
 
 def config3(args):
     """Llama-2-13B MHA shape, pool at 80 % of 288 GB, a stream of preemptions: request i leaves
-    while request i-2 resumes, both on side streams, with a compute kernel running beside."""
+    while request i-2 resumes, both on side streams, with a compute kernel running beside.
+    Run twice: the scheduler calls swap_in / swap_out itself, and the same stream through
+    kv_manager_iterate (Algorithm 1: dispatcher thread, step-1 polling, strategy)."""
     import torch
     from paper_2411_18424_amd import kvswap as kv, synth
     s = synth.LLAMA2_13B
@@ -159,7 +169,7 @@ def config3(args):
     rng = synth.rng_for(3)
     nblk = synth.blocks_for(rng.integers(512, 4097, size=n_pre), s.block_size)
     host_bytes = int((lag + 2) * (256 + 40)) * s.R
-    gpu, pool = _pool(kv, torch, s, host_bytes,
+    gpu, pool = _pool(kv, torch, s, host_bytes, copy_chunk_bytes=args.copy_chunk_mib << 20,
                       flags=_flags(args, kv, kv.KV_FLAG_PROFILE))
     a = torch.randn(8192, 8192, device="cuda:0", dtype=torch.bfloat16)
     comp = torch.cuda.Stream()
@@ -181,63 +191,103 @@ def config3(args):
     alone_ms = e0.elapsed_time(e1) / 200
     # about as much compute per iteration as the median swap takes on the link
     per_iter = max(1, int(float(np.median(nblk)) * s.R / 57e9 * 1e3 / alone_ms))
-    # tables from the library's block-group allocator (groups of >= 8 where the pool allows)
-    lat, evs = [], []
-    in_tables = {}
-    moved = 0
-    t_start = time.perf_counter()
-    for i in range(n_pre + lag):
-        evs.append(compute(per_iter))  # keeps the compute stream busy for about one iteration
-        t0 = time.perf_counter()
-        j = i - lag
-        if j >= 0:
-            # the swap-in the scheduler will wait for goes first: its copies then never queue
-            # behind those of the swap-out issued in the same iteration
-            ids2, _ = pool.alloc_block_group(10**6 + j, int(nblk[j]), 8)
-            pool.swap_in(j, ids2)          # ordered after request j's own swap-out by the library
-            in_tables[j] = ids2
-            moved += int(nblk[j]) * s.R
-        if i < n_pre:
-            ids, _ = pool.alloc_block_group(i, int(nblk[i]), 8)
-            pool.swap_out(i, ids)
-            pool.free_block_group(i, ids)  # parked until the gather has read them
-            moved += int(nblk[i]) * s.R
-        if j >= 0:
-            # the scheduler only has to wait for the request it resumes (Algorithm 1, step 1);
-            # the swap-out of request i drains in the background
-            pool.kv_wait(j)
-            lat.append((time.perf_counter() - t0) * 1e3)
-            pool.kv_host_release(j)  # the resumed request runs again; copy and blocks are recycled
-            pool.free_block_group(10**6 + j, in_tables.pop(j))
-    pool.kv_wait_all()
-    total_s = time.perf_counter() - t_start
-    comp.synchronize()
-    busy_ms = sum(x.elapsed_time(y) for x, y in evs) / (per_iter * len(evs))
-    rates = _rates(pool.kv_profile_read())
+
+    def stream(mgr):
+        """The 200-preemption stream; tables from the library's block-group allocator (groups of >= 8
+        where the pool allows).  mgr None: direct calls; else through kv_manager_iterate."""
+        lat, evs, in_tables, moved = [], [], {}, 0
+        pool.kv_profile_reset()
+        t_start = time.perf_counter()
+        for i in range(n_pre + lag):
+            evs.append(compute(per_iter))  # keeps the compute stream busy for about one iteration
+            t0 = time.perf_counter()
+            j = i - lag
+            ids = ids2 = None
+            if j >= 0:
+                ids2, _ = pool.alloc_block_group(10**6 + j, int(nblk[j]), 8)
+                in_tables[j] = ids2
+                moved += int(nblk[j]) * s.R
+            if i < n_pre:
+                ids, _ = pool.alloc_block_group(i, int(nblk[i]), 8)
+                moved += int(nblk[i]) * s.R
+            if mgr is None:
+                # by default the swap-in the scheduler will wait for goes first (Algorithm 1's order);
+                # --out-first issues the swap-out of the iteration before it
+                if i < n_pre and out_first:
+                    pool.swap_out(i, ids)
+                    pool.free_block_group(i, ids)  # parked until the gather has read them
+                if j >= 0:
+                    pool.swap_in(j, ids2)      # ordered after request j's own swap-out by the library
+                if i < n_pre and not out_first:
+                    pool.swap_out(i, ids)
+                    pool.free_block_group(i, ids)
+                if j >= 0:
+                    # the scheduler only has to wait for the request it resumes (Algorithm 1, step 1);
+                    # the swap-out of request i drains in the background
+                    pool.kv_wait(j)
+            else:
+                resumed, _ = mgr.kv_manager_iterate(swap_in=[(j, ids2)] if j >= 0 else [],
+                                                    swap_out=[(i, ids)] if i < n_pre else [],
+                                                    free_out_blocks=True)
+                while j >= 0 and j not in resumed:   # the scheduler has nothing else to run: step 1 until j is back
+                    resumed, _ = mgr.kv_manager_iterate()
+            if j >= 0:
+                lat.append((time.perf_counter() - t0) * 1e3)
+                pool.kv_host_release(j)  # the resumed request runs again; copy and blocks are recycled
+                pool.free_block_group(10**6 + j, in_tables.pop(j))
+        if mgr is not None:
+            mgr.kv_manager_drain()
+        pool.kv_wait_all()
+        total_s = time.perf_counter() - t_start
+        comp.synchronize()
+        busy_ms = sum(x.elapsed_time(y) for x, y in evs) / (per_iter * len(evs))
+        return {"gbps": round(moved / total_s / 1e9, 3),
+                "switch_latency_ms": {"median": _pct(lat, 50), "p99": _pct(lat, 99), "max": _pct(lat, 100)},
+                "kernels_and_copies": _rates(pool.kv_profile_read()),
+                "compute_slowdown": round(busy_ms / alone_ms, 4), "compute_ms_beside_swaps": round(busy_ms, 4)}
+
+    out_first = bool(getattr(args, "out_first", False))
+    direct = stream(None)
     st = pool.kv_stats()
+    via = {}
+    if not getattr(args, "no_manager_pass", False):
+        mgr = kv.KVManager(pool)
+        via = stream(mgr)
+        via["iteration_stats"] = mgr.kv_manager_iteration_stats()
+        ms = mgr.kv_manager_stats()
+        via["strategy_async_fraction"] = round(ms["strategy_async"] / max(1, ms["strategy_calls"]), 3)
+        via["dispatcher_us_per_task"] = round(ms["dispatch_us_sum"] / max(1, ms["dispatched"]), 1)
+        via["queue_wait_us_per_task"] = round(ms["queue_wait_us_sum"] / max(1, ms["dispatched"]), 1)
+        mgr.kv_manager_destroy()
     pool.kv_pool_destroy()
-    fairness = _copy_fairness(kv, torch, s, gpu)
+    fairness = _copy_fairness(kv, torch, s, gpu) if not getattr(args, "no_fairness", False) else None
     return {"metric": "KV swap GB/s (out+in) and per-preemption switch latency, 1 MI355X", "unit": "GB/s",
-            "value": round(moved / total_s / 1e9, 3),
+            "value": direct["gbps"],
             "config": {"workload": "config 3: Llama-2-13B-shaped MHA KV (40 layers, 40 KV heads, head_dim 128, fp16), "
                                    "pool %d blocks = %.1f GB, %d preemptions of 512..4096 tokens, one out while one in, "
                                    "compute running on a third stream" % (s.n_blocks, s.n_blocks * s.R / 1e9, n_pre)},
             "switch_latency_ms": {"what": "swap_in(i-2) and swap_out(i) issued together -> the resumed request i-2 is back",
-                                  "median": _pct(lat, 50), "p99": _pct(lat, 99), "max": _pct(lat, 100)},
+                                  **direct["switch_latency_ms"]},
             "request_MiB": {"median": round(float(np.median(nblk)) * s.R / MiB, 1),
                             "max": round(float(nblk.max()) * s.R / MiB, 1)},
-            "kernels_and_copies": rates,
+            "kernels_and_copies": direct["kernels_and_copies"],
             "compute_matmul_ms": {"what": "8192^3 bf16 matmul on the compute stream, %d per iteration" % per_iter,
-                                  "alone": round(alone_ms, 4), "beside_swaps": round(busy_ms, 4),
-                                  "slowdown": round(busy_ms / alone_ms, 4)},
+                                  "alone": round(alone_ms, 4), "beside_swaps": direct["compute_ms_beside_swaps"],
+                                  "slowdown": direct["compute_slowdown"]},
+            "via_manager": {"what": "the same stream through kv_manager_iterate (Algorithm 1): swaps dispatched by the "
+                                    "manager's thread, victims' blocks freed by the dispatcher, the resumed request "
+                                    "picked up by step-1 polling or by the synchronous branch of step 4", **via},
             "streams": 4 if args.four_streams else 3 if args.scatter_stream else 2, "mapped_swap_in": bool(args.mapped_swap_in),
+            "call_order": "swap-out first" if out_first else "swap-in first", "pack_variant": _variant_note(),
             "conflict_waits": st["conflict_waits"], "host_arena_bytes": st["host_arena_bytes"],
             "small_copy_latency_us": fairness}
 
 
 def config4(args):
     """Multi-turn delta swap on the Llama-3-8B shape: conversations with a host copy return,
-    append 64..512 tokens and leave; only dirty blocks move out."""
+    append 64..512 tokens and leave; only dirty blocks move out.  The stated 128 conversations
+    need about 110 GiB of pinned memory at once, more than one allocation gets on these machines
+    (64 GiB was granted, 72 GiB refused): they go through an arena of --arena-gib in waves."""
     import torch
     from paper_2411_18424_amd import kvswap as kv, synth
     s = synth.LLAMA3_8B
@@ -246,67 +296,94 @@ def config4(args):
     B = s.block_size
     ctx = synth.lengths_loguniform(rng, n_conv, 1024, 16384)
     nb0 = synth.blocks_for(ctx, B)
-    host_bytes = int(nb0.sum() + 140 * n_conv) * s.R
+    arena_blocks = (args.arena_gib << 30) // s.R
+    waves, cur, used = [], [], 0
+    for c in range(n_conv):  # greedy waves that fit the arena (context + room for two turns)
+        need = int(nb0[c]) + 140
+        if cur and used + need > arena_blocks:
+            waves.append(cur)
+            cur, used = [], 0
+        cur.append(c)
+        used += need
+    waves.append(cur)
+    host_bytes = arena_blocks * s.R
     gpu, pool = _pool(kv, torch, s, host_bytes, flags=_flags(args, kv, kv.KV_FLAG_PROFILE))
     gpu.random_(0, 256)
     torch.cuda.synchronize()
     work = rng.permutation(s.n_blocks)[:1200].astype(np.int32)
-    t_build = time.perf_counter()
-    tok = {}
-    for c in range(n_conv):
-        pool.swap_out(c, rng.permutation(work)[:int(nb0[c])])
-        tok[c] = int(ctx[c])
-    pool.kv_wait_all()
-    t_build = time.perf_counter() - t_build
     full_ms, delta_ms, in_ms, fracs, delta_bytes, full_bytes = [], [], [], [], 0, 0
-    full_recs = []
-    for turn in range(2):
-        for c in range(n_conv):
-            n_old = int(synth.blocks_for(tok[c], B))
-            t = rng.permutation(work)[:n_old]
-            a0 = time.perf_counter()
-            pool.swap_in(c, t)
-            pool.kv_wait(c)
-            in_ms.append((time.perf_counter() - a0) * 1e3)
-            new_tokens = int(rng.integers(64, 513))
-            dirty = synth.turn_dirty_mask(n_old, tok[c], new_tokens, B)
-            target = rng.uniform(0.05, 0.30)
-            dirty[:n_old] |= synth.random_mask(rng, n_old, max(0.0, target - dirty.mean()))
-            grown = np.concatenate([t, np.setdiff1d(work, t)[:len(dirty) - n_old]]).astype(np.int32)
-            a0 = time.perf_counter()
-            moved = pool.swap_out_delta(c, grown, dirty)
-            pool.kv_wait(c)
-            delta_ms.append((time.perf_counter() - a0) * 1e3)
-            assert moved == int(dirty.sum()), (moved, int(dirty.sum()))
-            delta_bytes += moved * s.R
-            fracs.append(moved / len(dirty))
-            tok[c] += new_tokens
-            if turn == 1:  # the same conversation swapped out in full, for comparison
-                n_rec = len(pool.kv_profile_read())
+    delta_op_gbps, full_recs, probes = [], [], []
+
+    def probe():  # is the link itself disturbed right now?  (a 256 MiB device-to-host copy, best of 3)
+        probes.append(round(kv.kv_link_probe(256 * MiB, 0, 3), 2))
+
+    for wave in waves:
+        probe()
+        tok = {}
+        for c in wave:
+            pool.swap_out(c, rng.permutation(work)[:int(nb0[c])])
+            tok[c] = int(ctx[c])
+        pool.kv_wait_all()
+        for turn in range(2):
+            for c in wave:
+                n_old = int(synth.blocks_for(tok[c], B))
+                t = rng.permutation(work)[:n_old]
                 a0 = time.perf_counter()
-                pool.swap_out(c, grown)
+                pool.swap_in(c, t)
                 pool.kv_wait(c)
-                full_ms.append((time.perf_counter() - a0) * 1e3)
-                full_bytes += len(grown) * s.R
-                full_recs += pool.kv_profile_read()[n_rec:]
+                in_ms.append((time.perf_counter() - a0) * 1e3)
+                new_tokens = int(rng.integers(64, 513))
+                dirty = synth.turn_dirty_mask(n_old, tok[c], new_tokens, B)
+                target = rng.uniform(0.05, 0.30)
+                dirty[:n_old] |= synth.random_mask(rng, n_old, max(0.0, target - dirty.mean()))
+                grown = np.concatenate([t, np.setdiff1d(work, t)[:len(dirty) - n_old]]).astype(np.int32)
+                a0 = time.perf_counter()
+                moved = pool.swap_out_delta(c, grown, dirty)
+                pool.kv_wait(c)
+                ms = (time.perf_counter() - a0) * 1e3
+                delta_ms.append(ms)
+                assert moved == int(dirty.sum()), (moved, int(dirty.sum()))
+                delta_bytes += moved * s.R
+                delta_op_gbps.append(moved * s.R / ms / 1e6)
+                fracs.append(moved / len(dirty))
+                tok[c] += new_tokens
+                if turn == 1:  # the same conversation swapped out in full, for comparison
+                    n_rec = len(pool.kv_profile_read())
+                    a0 = time.perf_counter()
+                    pool.swap_out(c, grown)
+                    pool.kv_wait(c)
+                    full_ms.append((time.perf_counter() - a0) * 1e3)
+                    full_bytes += len(grown) * s.R
+                    full_recs += pool.kv_profile_read()[n_rec:]
+            probe()
+        for c in wave:
+            pool.kv_host_release(c)
     st = pool.kv_stats()
     pool_recs = pool.kv_profile_read()
     pool.kv_pool_destroy()
     return {"metric": "KV swap GB/s (out+in) and per-preemption switch latency, 1 MI355X", "unit": "GB/s",
             "value": round(delta_bytes / (sum(delta_ms) * 1e-3) / 1e9, 3),
-            "value_is": "payload rate of the delta swap-outs alone",
-            "config": {"workload": "config 4: Llama-3-8B shape, %d conversations (capped from 128 by pinned memory: %.1f GiB "
-                                   "arena) with 1k..16k tokens on the host, 2 turns of +64..512 tokens, dirty fraction 5..30 %%"
-                                   % (n_conv, host_bytes / GiB)},
+            "value_is": "payload rate of the delta swap-outs alone (all of them: bytes / summed call-to-done times)",
+            "config": {"workload": "config 4: Llama-3-8B shape, %d conversations with 1k..16k tokens on the host, in %d wave(s) "
+                                   "through a %.0f GiB pinned arena, 2 turns of +64..512 tokens, dirty fraction 5..30 %%"
+                                   % (n_conv, len(waves), host_bytes / GiB)},
             "dirty_fraction": {"min": round(min(fracs), 3), "median": _pct(fracs, 50), "max": round(max(fracs), 3)},
             "delta_swap_out_ms": {"median": _pct(delta_ms, 50), "p99": _pct(delta_ms, 99)},
+            "delta_swap_out_gbps_per_op": {"what": "payload rate of each delta swap-out, call to done; the spread shows "
+                                                   "how steady the small device-to-host copies were in this run",
+                                           "p10": _pct(delta_op_gbps, 10), "median": _pct(delta_op_gbps, 50),
+                                           "p90": _pct(delta_op_gbps, 90)},
+            "link_probe_d2h_gbps": {"what": "256 MiB pinned copies between the phases of the run: is the link itself steady",
+                                    "min": min(probes), "median": _pct(probes, 50), "max": max(probes)},
             "full_swap_out_ms": {"median": _pct(full_ms, 50), "p99": _pct(full_ms, 99)},
             "full_swap_out_gbps": round(full_bytes / (sum(full_ms) * 1e-3) / 1e9, 3),
             "swap_in_ms": {"median": _pct(in_ms, 50), "p99": _pct(in_ms, 99)},
             "full_swap_out_kernels_and_copies": _rates(full_recs),
             "all_kernels_and_copies": _rates(pool_recs),
             "bytes_moved_equals_dirty_blocks": True, "mapped_swap_in": bool(args.mapped_swap_in),
-            "host_new_extents": st["host_new_extents"], "d2h_copies": st["d2h_copies"]}
+            "strided_copies": not getattr(args, "no_strided_copies", False), "pack_variant": _variant_note(),
+            "host_new_extents": st["host_new_extents"], "d2h_copies": st["d2h_copies"],
+            "d2h_copies_strided": st["strided_copies"]}
 
 
 def config5(args):

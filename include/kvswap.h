@@ -387,6 +387,66 @@ int32_t kv_manager_strategy(kv_manager_t* mgr, int32_t n_swap_in, int64_t swap_i
                             int32_t* async_out);
 int32_t kv_manager_stats(kv_manager_t* mgr, kv_manager_stats_t* out);
 
+/* Algorithm 1 (Section 3.2) as one call per scheduler iteration.  The manager keeps the
+ * algorithm's queues: every request it has seen is `running` (on the GPU), `swapped` (host
+ * copy only) or in `ongoing_swap_in`.  The scheduler passes what it decided for this iteration:
+ * the requests to resume with their new block tables, and the requests to preempt with their
+ * block tables (and dirty masks, for swap-out with reuse; NULL = full swap-outs).  The call
+ *   1. polls the swap-ins started by earlier iterations: those that have finished move from
+ *      ongoing_swap_in to running and are written to resumed[];
+ *   2. dispatches the swap-ins, 3. dispatches the swap-outs (through the dispatcher thread),
+ *      recording both in the window of recent swaps (r_info);
+ *   3.1 detects KV cache conflicts - a physical block that a swap-out of this iteration reads
+ *      and a swap-in of this iteration overwrites - on the tables, before anything is
+ *      dispatched: conflicting swap-outs are dispatched ahead of the swap-ins, and the pool
+ *      makes exactly the scatters concerned wait for their gathers on the device (fine-
+ *      grained synchronisation; the host never stalls for it);
+ *   4. asks the strategy: asynchronous - the new swap-ins join ongoing_swap_in and the
+ *      scheduler goes on; synchronous - the call waits for them (SwapInStreamSynchronize) and
+ *      they are in resumed[] already.  force_mode 1 / 2 overrides the strategy (always
+ *      asynchronous / always synchronous), 0 leaves it to kv_manager_strategy.
+ * A request is preempted from `running` only (one the manager has never seen counts as
+ * running), and resumed from `swapped` only: KV_EBUSY / KV_ENOENT otherwise, nothing is
+ * dispatched then.  A swap that fails when it is dispatched (arena full, bad table) is booked
+ * by the next call: the request returns to the queue it came from and is listed by
+ * kv_manager_failures.  *n_resumed is the number of resumed requests even when cap is smaller. */
+typedef struct {
+  int32_t n_swap_in, n_swap_out;
+  const int64_t* in_reqs;       /* [n_swap_in] */
+  const int32_t* in_tables;     /* concatenated new block tables */
+  const int32_t* in_n_blocks;   /* [n_swap_in] */
+  const int64_t* out_reqs;      /* [n_swap_out] */
+  const int32_t* out_tables;    /* concatenated block tables */
+  const int32_t* out_n_blocks;  /* [n_swap_out] */
+  const uint8_t* out_dirty;     /* concatenated dirty masks, or NULL */
+  int32_t force_mode;           /* 0 strategy decides, 1 asynchronous, 2 synchronous */
+  int32_t flags;                /* KV_IT_* */
+} kv_iteration_t;
+#define KV_IT_FREE_OUT_BLOCKS 1 /* preemption gives the victims' GPU blocks up: the dispatcher calls
+                                   free_block_group(req, table) right after each swap-out is enqueued - the
+                                   earliest moment at which the allocator knows to hold them back until the
+                                   gather has read them.  (A scheduler that frees them itself must not do so
+                                   before the swap-out has been dispatched.) */
+typedef struct {
+  int32_t completed_swap_ins;   /* step 1: ongoing swap-ins that had finished */
+  int32_t waited_swap_ins;      /* step 4: swap-ins of this iteration the call waited for */
+  int32_t async;                /* step 4 decision: 1 asynchronous, 0 synchronous */
+  int32_t conflicts;            /* step 3.1: swap-outs of this iteration dispatched ahead of the swap-ins */
+  int32_t ongoing_swap_ins;     /* length of ongoing_swap_in after the call */
+  int32_t failures;             /* failed swaps waiting in kv_manager_failures */
+} kv_iteration_result_t;
+typedef struct {
+  int64_t iterations, swap_ins, swap_outs, async_iterations, sync_iterations, conflicts, resumed;
+} kv_iteration_stats_t;
+#define KV_WHERE_RUNNING 0
+#define KV_WHERE_SWAPPED 1
+#define KV_WHERE_ONGOING_SWAP_IN 2
+int32_t kv_manager_iterate(kv_manager_t* mgr, const kv_iteration_t* it, int64_t* resumed, int32_t cap,
+                           int32_t* n_resumed, kv_iteration_result_t* result /* may be NULL */);
+int32_t kv_manager_failures(kv_manager_t* mgr, int64_t* reqs, int32_t* status, int32_t cap, int32_t* n_out);
+int32_t kv_manager_where(kv_manager_t* mgr, int64_t req, int32_t* where); /* KV_WHERE_*; KV_ENOENT: never seen */
+int32_t kv_manager_iteration_stats(kv_manager_t* mgr, kv_iteration_stats_t* out);
+
 /* Thread-local text of the last error. */
 const char* kv_last_error(void);
 const char* kv_version(void);

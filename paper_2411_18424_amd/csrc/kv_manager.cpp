@@ -17,6 +17,7 @@
 #include <stdint.h>
 #include <string.h>
 
+#include <algorithm>
 #include <chrono>
 #include <condition_variable>
 #include <deque>
@@ -37,6 +38,7 @@ struct Task {
   int64_t req = 0;
   std::vector<int32_t> table;
   std::vector<uint8_t> mask;
+  bool free_blocks = false;  // swap-outs: give the table's blocks back to the allocator once dispatched
   Clock::time_point t_submit;
 };
 
@@ -71,6 +73,18 @@ struct kv_manager {
   bool stop = false;
   std::thread worker;
   kv_manager_stats_t st{};
+
+  // Algorithm 1's queues, kept by kv_manager_iterate: where each request is, and the
+  // swap-ins / swap-outs whose outcome has not been booked yet.
+  enum Where : uint8_t { RUNNING = 0, SWAPPED = 1, ONGOING_SWAP_IN = 2 };
+  struct Pending {
+    int64_t req;
+    uint64_t ticket;
+  };
+  std::unordered_map<int64_t, uint8_t> where;
+  std::vector<Pending> ongoing_swap_in, pending_out;
+  std::vector<std::pair<int64_t, int32_t>> failures;  // (request, status), reported by the next iterate
+  kv_iteration_stats_t it_st{};
 };
 
 namespace {
@@ -79,17 +93,23 @@ int32_t dispatch(kv_manager* m, Task& t) {
   const int32_t n = (int32_t)t.table.size();
   const int32_t* tab = n ? t.table.data() : nullptr;
   const uint8_t* mask = t.mask.empty() ? nullptr : t.mask.data();
+  int32_t rc = KV_EINVAL;
   switch (t.kind) {
     case KV_TASK_SWAP_OUT:
-      return swap_out(m->pool, t.req, tab, n);
+      rc = swap_out(m->pool, t.req, tab, n);
+      break;
     case KV_TASK_SWAP_IN:
       return swap_in(m->pool, t.req, tab, n);
     case KV_TASK_SWAP_OUT_DELTA:
-      return swap_out_delta(m->pool, t.req, tab, n, mask, nullptr);
+      rc = swap_out_delta(m->pool, t.req, tab, n, mask, nullptr);
+      break;
     case KV_TASK_SWAP_IN_DELTA:
       return swap_in_delta(m->pool, t.req, tab, n, mask, nullptr);
   }
-  return KV_EINVAL;
+  // preemption gives the victim's blocks up: only now that the gather is enqueued does the
+  // allocator know to hold them back until it has read them
+  if (rc == KV_OK && t.free_blocks && n > 0) rc = free_block_group(m->pool, t.req, tab, n);
+  return rc;
 }
 
 // Moves flights whose device work has finished to the finished list.  Lock held.
@@ -181,8 +201,16 @@ int32_t kv_manager_destroy(kv_manager_t* m) {
   return KV_OK;
 }
 
+static int32_t submit_task(kv_manager_t* m, int32_t kind, int64_t req, const int32_t* table, int32_t n,
+                           const uint8_t* mask, uint64_t* ticket, bool free_blocks);
+
 int32_t kv_manager_submit(kv_manager_t* m, int32_t kind, int64_t req, const int32_t* table, int32_t n,
                           const uint8_t* mask, uint64_t* ticket) {
+  return submit_task(m, kind, req, table, n, mask, ticket, false);
+}
+
+static int32_t submit_task(kv_manager_t* m, int32_t kind, int64_t req, const int32_t* table, int32_t n,
+                           const uint8_t* mask, uint64_t* ticket, bool free_blocks) {
   if (!m || n < 0 || (n > 0 && !table) || kind < KV_TASK_SWAP_OUT || kind > KV_TASK_SWAP_IN_DELTA)
     return KV_EINVAL;
   if ((kind == KV_TASK_SWAP_OUT_DELTA || kind == KV_TASK_SWAP_IN_DELTA) && n > 0 && !mask) return KV_EINVAL;
@@ -191,6 +219,7 @@ int32_t kv_manager_submit(kv_manager_t* m, int32_t kind, int64_t req, const int3
   t.req = req;
   t.table.assign(table, table + n);
   if (mask && (kind == KV_TASK_SWAP_OUT_DELTA || kind == KV_TASK_SWAP_IN_DELTA)) t.mask.assign(mask, mask + n);
+  t.free_blocks = free_blocks;
   t.t_submit = Clock::now();
   {
     std::lock_guard<std::mutex> g(m->mu);
@@ -286,6 +315,195 @@ int32_t kv_manager_strategy(kv_manager_t* m, int32_t n_swap_in, int64_t swap_in_
   *async_out = (n_swap_in > 0 && typical_ms >= m->cfg.sync_below_ms) ? 1 : 0;
   m->st.strategy_calls++;
   if (*async_out) m->st.strategy_async++;
+  return KV_OK;
+}
+
+// ------------------------------------------------------------------------------------------
+// Algorithm 1 as one call per scheduler iteration.
+//
+// The paper's listing executes swap-ins (step 2) before swap-outs (step 3) and then checks the
+// two sets for a KV cache conflict (step 3.1).  On this library a conflict is a physical block
+// that a swap-out of the iteration still has to read and a swap-in of the same iteration
+// overwrites; the pool orders such a pair correctly on the device only if the reader was
+// enqueued first.  The check is therefore made on the block tables before anything is
+// dispatched: conflicting swap-outs go first (their gathers take well under a millisecond and
+// the pool makes exactly the scatters concerned wait for them - the fine-grained
+// Synchronize), everything else keeps the listing's order, swap-ins before swap-outs, which
+// also keeps the host-to-device copies the scheduler waits for ahead of the iteration's
+// device-to-host copies.
+int32_t kv_manager_iterate(kv_manager_t* m, const kv_iteration_t* it, int64_t* resumed, int32_t cap,
+                           int32_t* n_resumed, kv_iteration_result_t* res) {
+  if (!m || !it || !n_resumed || cap < 0 || (cap > 0 && !resumed)) return KV_EINVAL;
+  if (it->n_swap_in < 0 || it->n_swap_out < 0) return KV_EINVAL;
+  if (it->n_swap_in > 0 && (!it->in_reqs || !it->in_n_blocks)) return KV_EINVAL;
+  if (it->n_swap_out > 0 && (!it->out_reqs || !it->out_n_blocks)) return KV_EINVAL;
+  kv_iteration_result_t r{};
+  int32_t nres = 0;
+  auto report = [&](int64_t req) {
+    if (nres < cap) resumed[nres] = req;
+    ++nres;
+  };
+  std::vector<int64_t> in_off((size_t)it->n_swap_in + 1, 0), out_off((size_t)it->n_swap_out + 1, 0);
+  for (int32_t i = 0; i < it->n_swap_in; ++i) {
+    if (it->in_n_blocks[i] < 0) return KV_EINVAL;
+    in_off[(size_t)i + 1] = in_off[(size_t)i] + it->in_n_blocks[i];
+  }
+  for (int32_t i = 0; i < it->n_swap_out; ++i) {
+    if (it->out_n_blocks[i] < 0) return KV_EINVAL;
+    out_off[(size_t)i + 1] = out_off[(size_t)i] + it->out_n_blocks[i];
+  }
+  if ((in_off.back() > 0 && !it->in_tables) || (out_off.back() > 0 && !it->out_tables)) return KV_EINVAL;
+
+  // ---- step 1: swap-ins of earlier iterations that have completed join the running requests
+  {
+    std::lock_guard<std::mutex> g(m->mu);
+    harvest(m);
+    auto settle = [&](std::vector<kv_manager::Pending>& list, bool is_in) {
+      size_t w = 0;
+      for (size_t i = 0; i < list.size(); ++i) {
+        auto f = m->finished.find(list[i].ticket);
+        if (f == m->finished.end()) {
+          list[w++] = list[i];
+          continue;
+        }
+        const int32_t status = f->second;
+        m->finished.erase(f);
+        if (status != KV_OK) {
+          m->failures.push_back({list[i].req, status});
+          m->where[list[i].req] = is_in ? kv_manager::SWAPPED : kv_manager::RUNNING;
+        } else if (is_in) {
+          m->where[list[i].req] = kv_manager::RUNNING;
+          report(list[i].req);
+          ++r.completed_swap_ins;
+        }
+      }
+      list.resize(w);
+    };
+    settle(m->ongoing_swap_in, true);
+    settle(m->pending_out, false);  // swap-outs only have failures to book
+    while (!m->finished_order.empty() && !m->finished.count(m->finished_order.front())) m->finished_order.pop_front();
+    // queue transitions of this iteration are checked before anything is dispatched
+    for (int32_t i = 0; i < it->n_swap_in; ++i) {
+      auto f = m->where.find(it->in_reqs[i]);
+      if (f == m->where.end() || f->second != kv_manager::SWAPPED) return KV_ENOENT;  // not in `swapped`
+    }
+    for (int32_t i = 0; i < it->n_swap_out; ++i) {
+      auto f = m->where.find(it->out_reqs[i]);
+      if (f != m->where.end() && f->second != kv_manager::RUNNING) return KV_EBUSY;  // not in `running`
+    }
+  }
+
+  // ---- step 3.1 (made first, see above): blocks named by a swap-out and by a swap-in
+  std::vector<uint8_t> out_first((size_t)it->n_swap_out, 0);
+  if (it->n_swap_in > 0 && it->n_swap_out > 0) {
+    std::vector<int32_t> in_blocks(it->in_tables, it->in_tables + in_off.back());
+    std::sort(in_blocks.begin(), in_blocks.end());
+    for (int32_t i = 0; i < it->n_swap_out; ++i)
+      for (int64_t k = out_off[(size_t)i]; k < out_off[(size_t)i + 1]; ++k)
+        if (std::binary_search(in_blocks.begin(), in_blocks.end(), it->out_tables[k])) {
+          out_first[(size_t)i] = 1;
+          ++r.conflicts;
+          break;
+        }
+  }
+  std::vector<uint64_t> in_tickets((size_t)it->n_swap_in, 0), out_tickets((size_t)it->n_swap_out, 0);
+  auto submit_out = [&](int32_t i) -> int32_t {
+    const uint8_t* mask = it->out_dirty ? it->out_dirty + out_off[(size_t)i] : nullptr;
+    return submit_task(m, mask ? KV_TASK_SWAP_OUT_DELTA : KV_TASK_SWAP_OUT, it->out_reqs[i],
+                       it->out_tables + out_off[(size_t)i], it->out_n_blocks[i], mask,
+                       &out_tickets[(size_t)i], (it->flags & KV_IT_FREE_OUT_BLOCKS) != 0);
+  };
+  int32_t rc;
+  for (int32_t i = 0; i < it->n_swap_out; ++i)
+    if (out_first[(size_t)i] && (rc = submit_out(i))) return rc;
+  // ---- step 2: swap-ins
+  int64_t in_blocks_total = 0;
+  for (int32_t i = 0; i < it->n_swap_in; ++i) {
+    if ((rc = kv_manager_submit(m, KV_TASK_SWAP_IN, it->in_reqs[i], it->in_tables + in_off[(size_t)i],
+                                it->in_n_blocks[i], nullptr, &in_tickets[(size_t)i])))
+      return rc;
+    in_blocks_total += it->in_n_blocks[i];
+  }
+  // ---- step 3: swap-outs
+  for (int32_t i = 0; i < it->n_swap_out; ++i)
+    if (!out_first[(size_t)i] && (rc = submit_out(i))) return rc;
+
+  // ---- step 4: asynchronous or synchronous swap-in
+  int32_t async = 1;
+  if (it->n_swap_in > 0 && (rc = kv_manager_strategy(m, it->n_swap_in, in_blocks_total, &async))) return rc;
+  if (it->force_mode == 1) async = 1;
+  if (it->force_mode == 2) async = 0;
+  r.async = async;
+  {
+    std::lock_guard<std::mutex> g(m->mu);
+    for (int32_t i = 0; i < it->n_swap_out; ++i) {
+      m->where[it->out_reqs[i]] = kv_manager::SWAPPED;
+      m->pending_out.push_back({it->out_reqs[i], out_tickets[(size_t)i]});
+    }
+    for (int32_t i = 0; i < it->n_swap_in; ++i) {
+      m->where[it->in_reqs[i]] = kv_manager::ONGOING_SWAP_IN;
+      if (async) m->ongoing_swap_in.push_back({it->in_reqs[i], in_tickets[(size_t)i]});
+    }
+  }
+  if (!async) {  // SwapInStreamSynchronize: the scheduler stalls until they are back
+    for (int32_t i = 0; i < it->n_swap_in; ++i) {
+      int32_t status = KV_OK;
+      rc = kv_manager_wait(m, in_tickets[(size_t)i], &status);
+      std::lock_guard<std::mutex> g(m->mu);
+      if (rc == KV_OK && status == KV_OK) {
+        m->where[it->in_reqs[i]] = kv_manager::RUNNING;
+        report(it->in_reqs[i]);
+        ++r.waited_swap_ins;
+      } else {
+        m->where[it->in_reqs[i]] = kv_manager::SWAPPED;
+        m->failures.push_back({it->in_reqs[i], rc != KV_OK ? rc : status});
+      }
+    }
+  }
+  {
+    std::lock_guard<std::mutex> g(m->mu);
+    r.ongoing_swap_ins = (int32_t)m->ongoing_swap_in.size();
+    r.failures = (int32_t)m->failures.size();
+    m->it_st.iterations++;
+    m->it_st.swap_ins += it->n_swap_in;
+    m->it_st.swap_outs += it->n_swap_out;
+    m->it_st.async_iterations += (it->n_swap_in > 0 && async) ? 1 : 0;
+    m->it_st.sync_iterations += (it->n_swap_in > 0 && !async) ? 1 : 0;
+    m->it_st.conflicts += r.conflicts;
+    m->it_st.resumed += nres;
+  }
+  *n_resumed = nres;
+  if (res) *res = r;
+  return KV_OK;
+}
+
+int32_t kv_manager_failures(kv_manager_t* m, int64_t* reqs, int32_t* status, int32_t cap, int32_t* n_out) {
+  if (!m || !n_out || cap < 0 || (cap > 0 && (!reqs || !status))) return KV_EINVAL;
+  std::lock_guard<std::mutex> g(m->mu);
+  int32_t k = 0;
+  while (k < cap && !m->failures.empty()) {
+    reqs[k] = m->failures.front().first;
+    status[k] = m->failures.front().second;
+    m->failures.erase(m->failures.begin());
+    ++k;
+  }
+  *n_out = k;
+  return KV_OK;
+}
+
+int32_t kv_manager_where(kv_manager_t* m, int64_t req, int32_t* where) {
+  if (!m || !where) return KV_EINVAL;
+  std::lock_guard<std::mutex> g(m->mu);
+  auto f = m->where.find(req);
+  if (f == m->where.end()) return KV_ENOENT;
+  *where = f->second;
+  return KV_OK;
+}
+
+int32_t kv_manager_iteration_stats(kv_manager_t* m, kv_iteration_stats_t* out) {
+  if (!m || !out) return KV_EINVAL;
+  std::lock_guard<std::mutex> g(m->mu);
+  *out = m->it_st;
   return KV_OK;
 }
 

@@ -145,7 +145,7 @@ int32_t kv_pool_create(const kv_pool_config_t* cfg, kv_pool_t** out) {
   p->ring_out.cap = out_cap;
   p->ring_out.piece_blocks = piece_blocks(out_cap, p->launch_blocks * p->R);
   p->ring_in.cap = in_cap;
-  p->ring_in.piece_blocks = piece_blocks(in_cap, 256ll << 20);
+  p->ring_in.piece_blocks = piece_blocks(in_cap, 512ll << 20);
   p->arena_blocks = cfg->host_bytes / p->R;
   if (p->arena_blocks > 0xFFFFFFFFll) {
     delete p;

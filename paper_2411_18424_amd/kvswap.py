@@ -23,6 +23,8 @@ KV_FLAG_PLAN_ONLY, KV_FLAG_PROFILE, KV_FLAG_ORDER_COMPUTE, KV_FLAG_FOUR_STREAMS 
 KV_FLAG_MAPPED_SWAP_IN, KV_FLAG_HOST_EVICT, KV_FLAG_MAPPED_SWAP_OUT, KV_FLAG_SCATTER_STREAM = 16, 32, 64, 128
 KV_FLAG_NO_STRIDED_COPIES = 256
 KV_TASK_SWAP_OUT, KV_TASK_SWAP_IN, KV_TASK_SWAP_OUT_DELTA, KV_TASK_SWAP_IN_DELTA = 0, 1, 2, 3
+KV_WHERE_RUNNING, KV_WHERE_SWAPPED, KV_WHERE_ONGOING_SWAP_IN = 0, 1, 2
+KV_IT_FREE_OUT_BLOCKS = 1
 
 _STATUS_NAMES = {0: "KV_OK", -1: "KV_EINVAL", -2: "KV_ENOMEM_GPU", -3: "KV_ENOMEM_HOST",
                  -4: "KV_ENOENT", -5: "KV_EBUSY", -6: "KV_EHIP", -7: "KV_ENODEV"}
@@ -70,6 +72,25 @@ class kv_manager_stats_t(C.Structure):
     _fields_ = [(n, C.c_int64) for n in ("submitted", "dispatched", "failed", "queued", "in_flight",
                                          "strategy_calls", "strategy_async")] + \
                [("dispatch_us_sum", C.c_double), ("queue_wait_us_sum", C.c_double)]
+
+
+class kv_iteration_t(C.Structure):
+    _fields_ = [("n_swap_in", C.c_int32), ("n_swap_out", C.c_int32),
+                ("in_reqs", C.POINTER(C.c_int64)), ("in_tables", C.POINTER(C.c_int32)),
+                ("in_n_blocks", C.POINTER(C.c_int32)),
+                ("out_reqs", C.POINTER(C.c_int64)), ("out_tables", C.POINTER(C.c_int32)),
+                ("out_n_blocks", C.POINTER(C.c_int32)), ("out_dirty", C.POINTER(C.c_uint8)),
+                ("force_mode", C.c_int32), ("flags", C.c_int32)]
+
+
+class kv_iteration_result_t(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("completed_swap_ins", "waited_swap_ins", "async", "conflicts",
+                                         "ongoing_swap_ins", "failures")]
+
+
+class kv_iteration_stats_t(C.Structure):
+    _fields_ = [(n, C.c_int64) for n in ("iterations", "swap_ins", "swap_outs", "async_iterations",
+                                         "sync_iterations", "conflicts", "resumed")]
 
 
 class kv_prof_record_t(C.Structure):
@@ -137,6 +158,11 @@ def _load() -> C.CDLL:
         "kv_manager_drain": (C.c_int32, [C.c_void_p]),
         "kv_manager_strategy": (C.c_int32, [C.c_void_p, C.c_int32, C.c_int64, i32p]),
         "kv_manager_stats": (C.c_int32, [C.c_void_p, P(kv_manager_stats_t)]),
+        "kv_manager_iterate": (C.c_int32, [C.c_void_p, P(kv_iteration_t), i64p, C.c_int32, i32p,
+                                           P(kv_iteration_result_t)]),
+        "kv_manager_failures": (C.c_int32, [C.c_void_p, i64p, i32p, C.c_int32, i32p]),
+        "kv_manager_where": (C.c_int32, [C.c_void_p, C.c_int64, i32p]),
+        "kv_manager_iteration_stats": (C.c_int32, [C.c_void_p, P(kv_iteration_stats_t)]),
         "kv_last_error": (C.c_char_p, []),
         "kv_version": (C.c_char_p, []),
     }
@@ -486,6 +512,52 @@ class KVManager:
         a = C.c_int32()
         _check(lib.kv_manager_strategy(self._m, n_swap_in, swap_in_blocks, C.byref(a)))
         return bool(a.value)
+
+    def kv_manager_iterate(self, swap_in=(), swap_out=(), force_mode: int = 0, cap: int = 256,
+                           free_out_blocks: bool = False):
+        """swap_in: [(req, new_table)]; swap_out: [(req, table)] or [(req, table, dirty_mask)] (all or
+        none with masks).  Returns (resumed request ids, result dict)."""
+        def pack(items):
+            reqs, rp = _i64([it[0] for it in items])
+            nb, nbp = _i32([len(it[1]) for it in items])
+            cat = np.concatenate([np.asarray(it[1], dtype=np.int32) for it in items]) if len(items) else \
+                np.zeros(0, np.int32)
+            cat, cp = _i32(cat)
+            return (reqs, nb, cat), rp, cp, nbp
+        keep_in, irp, icp, inbp = pack(swap_in)
+        keep_out, orp, ocp, onbp = pack(swap_out)
+        dirty, dp = None, None
+        if len(swap_out) and len(swap_out[0]) > 2:
+            dirty, dp = _u8(np.concatenate([np.asarray(it[2], dtype=np.uint8) for it in swap_out]))
+            if dirty.size != keep_out[2].size:
+                raise KVError(KV_EINVAL, "dirty masks do not match the tables")
+        it = kv_iteration_t(n_swap_in=len(swap_in), n_swap_out=len(swap_out), in_reqs=irp, in_tables=icp,
+                            in_n_blocks=inbp, out_reqs=orp, out_tables=ocp, out_n_blocks=onbp,
+                            out_dirty=dp, force_mode=force_mode, flags=KV_IT_FREE_OUT_BLOCKS if free_out_blocks else 0)
+        resumed = np.zeros(max(1, cap), dtype=np.int64)
+        n = C.c_int32()
+        res = kv_iteration_result_t()
+        _check(lib.kv_manager_iterate(self._m, C.byref(it), resumed.ctypes.data_as(C.POINTER(C.c_int64)), cap,
+                                      C.byref(n), C.byref(res)))
+        return ([int(x) for x in resumed[:min(n.value, cap)]],
+                {k: getattr(res, k) for k, _ in kv_iteration_result_t._fields_})
+
+    def kv_manager_failures(self, cap: int = 64):
+        reqs = (C.c_int64 * cap)()
+        status = (C.c_int32 * cap)()
+        n = C.c_int32()
+        _check(lib.kv_manager_failures(self._m, reqs, status, cap, C.byref(n)))
+        return [(reqs[i], status[i]) for i in range(n.value)]
+
+    def kv_manager_where(self, req: int) -> int:
+        w = C.c_int32()
+        _check(lib.kv_manager_where(self._m, req, C.byref(w)))
+        return w.value
+
+    def kv_manager_iteration_stats(self) -> dict:
+        st = kv_iteration_stats_t()
+        _check(lib.kv_manager_iteration_stats(self._m, C.byref(st)))
+        return {n: getattr(st, n) for n, _ in kv_iteration_stats_t._fields_}
 
     def kv_manager_stats(self) -> dict:
         st = kv_manager_stats_t()

@@ -238,6 +238,64 @@ static void scheduler(kv_pool_t* pool, int iters) {
   }
 }
 
+// A scheduler thread that runs Algorithm 1 through kv_manager_iterate: two requests take turns,
+// one leaves while the other resumes into the blocks it vacates (a conflict in every iteration).
+static void iterating_scheduler(kv_pool_t* pool, int iters) {
+  kv_manager_t* mgr = nullptr;
+  EXPECT(kv_manager_create(pool, nullptr, &mgr) == KV_OK, "kv_manager_create");
+  if (!mgr) return;
+  const int64_t a = 30000, b = 30001;
+  std::vector<int32_t> table(12);
+  int32_t rc = alloc_block_group(pool, a, 12, 1, table.data(), nullptr);
+  EXPECT(rc == KV_OK, "iterating scheduler alloc -> %d", rc);
+  if (rc != KV_OK) {
+    kv_manager_destroy(mgr);
+    return;
+  }
+  EXPECT(kv_host_set_priority(pool, a, 100) == KV_OK && kv_host_set_priority(pool, b, 100) == KV_OK, "priority");
+  int32_t twelve = 12, n_res = 0;
+  int64_t resumed[4];
+  kv_iteration_t it;
+  memset(&it, 0, sizeof it);
+  it.n_swap_out = 1, it.out_reqs = &b, it.out_tables = table.data(), it.out_n_blocks = &twelve;
+  EXPECT(kv_manager_iterate(mgr, &it, resumed, 4, &n_res, nullptr) == KV_OK && n_res == 0, "first iterate");
+  int64_t out = a, in = b, total_resumed = 0, swap_ins = 0;
+  for (int k = 0; k < iters; ++k) {
+    int32_t where = -1;
+    EXPECT(kv_manager_where(mgr, in, &where) == KV_OK, "where");
+    if (where != KV_WHERE_SWAPPED || (kv_manager_where(mgr, out, &where) == KV_OK && where != KV_WHERE_RUNNING)) {
+      memset(&it, 0, sizeof it);  // an asynchronous swap-in is still ongoing: poll
+      EXPECT(kv_manager_iterate(mgr, &it, resumed, 4, &n_res, nullptr) == KV_OK, "polling iterate");
+      total_resumed += n_res;
+      continue;
+    }
+    memset(&it, 0, sizeof it);
+    it.n_swap_in = 1, it.in_reqs = &in, it.in_tables = table.data(), it.in_n_blocks = &twelve;
+    it.n_swap_out = 1, it.out_reqs = &out, it.out_tables = table.data(), it.out_n_blocks = &twelve;
+    it.force_mode = 1 + k % 2;
+    kv_iteration_result_t res;
+    rc = kv_manager_iterate(mgr, &it, resumed, 4, &n_res, &res);
+    EXPECT(rc == KV_OK && res.conflicts == 1, "iterate -> %d, conflicts %d", rc, res.conflicts);
+    total_resumed += n_res;
+    ++swap_ins;
+    std::swap(out, in);
+  }
+  EXPECT(kv_manager_drain(mgr) == KV_OK, "drain");
+  memset(&it, 0, sizeof it);
+  EXPECT(kv_manager_iterate(mgr, &it, resumed, 4, &n_res, nullptr) == KV_OK, "last iterate");
+  total_resumed += n_res;
+  int64_t fr[4];
+  int32_t fs[4], nf = 0;
+  EXPECT(kv_manager_failures(mgr, fr, fs, 4, &nf) == KV_OK, "failures");
+  // the tight arena may refuse a swap-out (priority protects these two from eviction, not from a full arena)
+  EXPECT(total_resumed + nf >= swap_ins - 1 && total_resumed <= swap_ins, "resumed %lld of %lld swap-ins, %d failures",
+         (long long)total_resumed, (long long)swap_ins, nf);
+  EXPECT(kv_manager_destroy(mgr) == KV_OK, "kv_manager_destroy");
+  EXPECT(free_block_group(pool, a, table.data(), 12) == KV_OK, "iterating scheduler free");
+  (void)kv_host_release(pool, a);
+  (void)kv_host_release(pool, b);
+}
+
 // Readers of global state.
 static void observer(kv_pool_t* pool, std::atomic<bool>* stop) {
   while (!stop->load()) {
@@ -277,6 +335,7 @@ int main(int argc, char** argv) {
   for (int t = 0; t < 3; ++t) th.emplace_back(swapper, pool, t, iters);
   for (int t = 0; t < 2; ++t) th.emplace_back(grower, pool, t, iters);
   th.emplace_back(scheduler, pool, iters / 10);
+  th.emplace_back(iterating_scheduler, pool, iters / 10);
   std::thread obs(observer, pool, &stop);
   for (auto& t : th) t.join();
   stop = true;

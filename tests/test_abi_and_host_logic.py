@@ -448,6 +448,57 @@ def test_swap_manager_dispatches_in_order_and_reports_each_task_once(kv):
     m.kv_manager_destroy()
 
 
+def test_algorithm_1_iterations_move_requests_between_the_queues(kv):
+    """kv_manager_iterate on a plan-only pool: running -> swapped by a swap-out, swapped ->
+    ongoing_swap_in -> running by an asynchronous swap-in (reported by a later iteration's
+    step 1), swapped -> running at once by a synchronous one; conflicts between the two sets of
+    an iteration are counted and the conflicting swap-out is dispatched first (the moved bytes
+    then equal the oracle's, which applies the swap-out first); illegal transitions are
+    refused; a failed swap is booked by the next iteration."""
+    shape = synth.KVShape("s", 1, 1, 8, 1, 2, 512, "fp16")
+    p = plan_pool(kv, shape, host_blocks=600)
+    m = kv.KVManager(p, sync_below_ms=1e-9)  # the strategy always answers asynchronous
+    W = (kv.KV_WHERE_RUNNING, kv.KV_WHERE_SWAPPED, kv.KV_WHERE_ONGOING_SWAP_IN)
+    ta, tb, tc = (np.arange(i * 40, i * 40 + 30, dtype=np.int32) for i in range(3))
+    # iteration 1: A and B leave
+    resumed, r = m.kv_manager_iterate(swap_out=[(1, ta), (2, tb)])
+    assert resumed == [] and r["conflicts"] == 0 and r["ongoing_swap_ins"] == 0
+    assert m.kv_manager_where(1) == W[1] and m.kv_manager_where(2) == W[1]
+    with pytest.raises(kv.KVError) as ei:
+        m.kv_manager_iterate(swap_out=[(1, ta)])          # not running
+    assert ei.value.status == kv.KV_EBUSY
+    with pytest.raises(kv.KVError) as ei:
+        m.kv_manager_iterate(swap_in=[(3, tc)])           # never swapped out
+    assert ei.value.status == kv.KV_ENOENT
+    # iteration 2: A resumes asynchronously into the blocks C vacates in the same iteration
+    resumed, r = m.kv_manager_iterate(swap_in=[(1, tc)], swap_out=[(3, tc)])
+    assert r["async"] == 1 and r["conflicts"] == 1 and resumed == []
+    assert m.kv_manager_where(1) == W[2] and m.kv_manager_where(3) == W[1]
+    m.kv_manager_drain()
+    assert p.kv_stats()["conflict_waits"] == 0  # plan-only: nothing is in flight, but the order held:
+    assert p.kv_host_len(3)[0] == 30            # C's swap-out was accepted (its table was still C's)
+    # iteration 3: step 1 finds A's swap-in complete; B resumes synchronously
+    resumed, r = m.kv_manager_iterate(swap_in=[(2, ta)], force_mode=2)
+    assert sorted(resumed) == [1, 2] and r["completed_swap_ins"] == 1 and r["waited_swap_ins"] == 1
+    assert r["async"] == 0 and r["ongoing_swap_ins"] == 0
+    assert m.kv_manager_where(1) == W[0] and m.kv_manager_where(2) == W[0]
+    # a swap-out that fails when it is dispatched (arena full) returns the request to running
+    big = np.arange(0, 500, dtype=np.int32)
+    m.kv_manager_iterate(swap_out=[(7, big)])
+    m.kv_manager_drain()
+    resumed, r = m.kv_manager_iterate()
+    assert r["failures"] == 1 and m.kv_manager_failures() == [(7, kv.KV_ENOMEM_HOST)]
+    assert m.kv_manager_where(7) == W[0]
+    # delta swap-outs through the iteration
+    resumed, r = m.kv_manager_iterate(swap_out=[(1, tc, np.ones(30, np.uint8))])
+    m.kv_manager_drain()
+    st = m.kv_manager_iteration_stats()
+    assert st["iterations"] == 6 and st["swap_outs"] == 5 and st["swap_ins"] == 2 and st["conflicts"] == 1
+    assert st["async_iterations"] == 1 and st["sync_iterations"] == 1 and st["resumed"] == 2
+    assert p.kv_stats()["blocks_out"] == 30 * 4 and p.kv_stats()["blocks_in"] == 60
+    m.kv_manager_destroy()
+
+
 def test_swap_manager_strategy_follows_swap_in_size(kv):
     """Step 4: short swap-ins are waited for, long ones proceed asynchronously; the recent
     window damps single outliers."""

@@ -646,6 +646,79 @@ def test_swap_manager_path_matches_oracle(harness):
         m.kv_manager_destroy()
 
 
+@pytest.mark.parametrize("flags", [0, 128], ids=["two_streams", "three_streams"])
+def test_algorithm_1_iterations_match_oracle(harness, flags):
+    """A scheduler loop through kv_manager_iterate: every iteration preempts one running request
+    and resumes one swapped request - into the very blocks the victim leaves (a KV cache
+    conflict, step 3.1) or into spare blocks - asynchronously or synchronously (step 4).  The
+    oracle replays every iteration with the conflicting swap-out first; nothing is waited for
+    except through the manager."""
+    shape = synth.KVShape("s", 8, 8, 128, 16, 2, 512, "bf16")  # R = 512 KiB, 30 MiB per request
+    h = harness(shape, cfg=38, host_bytes=512 * MiB, fill="random", flags=flags)
+    kv = h.kv
+    m = kv.KVManager(h.pool)
+    try:
+        rng = synth.rng_for(38)
+        perm = rng.permutation(512).astype(np.int32)
+        table = {r: perm[r * 60:(r + 1) * 60] for r in range(6)}
+        spare = list(perm[360:])
+        running, swapped, ongoing = set(range(6)), [], set()
+        stats = {"conflicts": 0, "async": 0, "sync": 0}
+        # two requests leave first
+        m.kv_manager_iterate(swap_out=[(0, table[0]), (1, table[1])])
+        for r in (0, 1):
+            h.oracle.swap_out(r, table[r])
+            running.discard(r)
+            swapped.append(r)
+            spare.extend(table.pop(r))
+        for k in range(14):
+            v = sorted(running)[int(rng.integers(0, len(running)))]
+            u = swapped.pop(0)
+            n = 60
+            if k % 2 == 0:   # the resumed request takes over the victim's blocks
+                new = table[v][::-1].copy()
+            else:            # or blocks that have been free for a while
+                new = np.array(spare[:n], dtype=np.int32)
+                del spare[:n]
+                spare.extend(int(b) for b in table[v])
+            mode = (0, 1, 2)[k % 3]
+            resumed, r = m.kv_manager_iterate(swap_in=[(u, new)], swap_out=[(v, table[v])], force_mode=mode)
+            h.oracle.swap_out(v, table[v])   # a conflicting swap-out is dispatched first; otherwise
+            h.oracle.swap_in(u, new)         # the two touch different blocks and the order is free
+            assert r["conflicts"] == (1 if k % 2 == 0 else 0)
+            stats["conflicts"] += r["conflicts"]
+            stats["async" if r["async"] else "sync"] += 1
+            running.discard(v)
+            swapped.append(v)
+            table.pop(v)
+            table[u] = new
+            ongoing.add(u)
+            for q in resumed:
+                assert q in ongoing
+                ongoing.discard(q)
+                running.add(q)
+            if not running:  # the scheduler has nothing to run: it waits for a swap-in (an empty iteration polls)
+                while not running:
+                    resumed, _ = m.kv_manager_iterate()
+                    for q in resumed:
+                        ongoing.discard(q)
+                        running.add(q)
+        m.kv_manager_drain()
+        resumed, r = m.kv_manager_iterate()
+        for q in resumed:
+            ongoing.discard(q)
+            running.add(q)
+        assert not ongoing and r["ongoing_swap_ins"] == 0 and r["failures"] == 0
+        assert stats["conflicts"] == 7 and stats["sync"] >= 4 and stats["async"] >= 4
+        for q in swapped:
+            h.assert_image_equal(q)
+        h.assert_pool_equal()
+        st = h.pool.kv_stats()
+        assert st["bytes_out"] == h.oracle.bytes_out and st["bytes_in"] == h.oracle.bytes_in
+    finally:
+        m.kv_manager_destroy()
+
+
 def test_concurrent_host_threads(harness):
     """The pool may be driven from several host threads: four threads swap disjoint requests
     out and back in at the same time."""
