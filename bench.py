@@ -256,6 +256,9 @@ def main() -> int:
                      copy_chunk_bytes=args.copy_chunk_mib << 20, max_piece_bytes=args.max_piece_mib << 20)
     cur = [work.tables[v] for v in victims]
     nxt = list(work.resume_tables)
+    import bench_configs
+    settled = bench_configs.settle(torch)  # not while the driver still clears a previous process's device memory
+    log("settle:", settled)
 
     phase_s = [0.0, 0.0]  # time in the swap-out and the swap-in half of the steps (host clock)
 
@@ -511,6 +514,7 @@ def main() -> int:
                                        if mgr_stats else None),
         },
         "device_state": dev_state,
+        "settle": settled,
         "streams": 4 if args.four_streams else 3 if args.scatter_stream else 2,
         "pack_variant": int(os.environ.get("KVSWAP_PACK_VARIANT", "0")),  # development aid; 0 = the default kernels
         "swap_in_path": "mapped host reads" if args.mapped_swap_in else "staged copies + scatter",

@@ -44,6 +44,50 @@ def _variant_note():
             "KVSWAP_MAPPED_GRID": int(os.environ.get("KVSWAP_MAPPED_GRID", "0"))}
 
 
+def settle(torch, max_s=60.0, quiet_s=3.0):
+    """Waits until small swap-outs run at their normal rate, steadily.  When a process that held
+    much device memory has just ended (the previous benchmark or test on this machine), the kernel
+    driver is still busy with that memory, and for several seconds the device-to-host copies of a
+    few MiB behind a gather take several times as long (measured: 98 of 120 delta swap-outs slow
+    right after a process with 214 GiB exited, 1 of 120 after 20 s of sleep; large copies lose a
+    few per cent).  That is the machine's state, not the workload's: timing starts when every
+    probe of the last quiet_s seconds was back to normal.  The probe is the library's own path on a
+    small pool of its own: a delta swap-out of 11 scattered 2 MiB block records (gather, then one
+    copy per record or pair).  Returns what it saw."""
+    from paper_2411_18424_amd import kvswap as kv, synth
+    s = synth.LLAMA3_8B.with_blocks(64)
+    gpu = torch.zeros(s.R * s.n_blocks, dtype=torch.uint8, device="cuda:0")
+    pool = kv.KVPool(n_layers=s.n_layers, n_kv_heads=s.n_kv_heads, head_dim=s.head_dim, block_size=s.block_size,
+                     elt_bytes=s.elt_bytes, n_gpu_blocks=s.n_blocks, gpu_base=gpu.data_ptr(), host_bytes=128 * s.R,
+                     staging_out_bytes=64 * s.R, staging_in_bytes=2 * s.R)
+    t = np.arange(64, dtype=np.int32)
+    pool.swap_out(0, t)
+    pool.kv_wait(0)
+    dirty = np.zeros(64, np.uint8)
+    dirty[[0, 1, 3, 6, 10, 15, 21, 28, 36, 45, 55]] = 1  # gaps 1, 2, 3, ...: no arithmetic progression beyond pairs
+    rates, t0 = [], time.perf_counter()
+    quiet_since = None
+    while True:
+        a = time.perf_counter()
+        moved = pool.swap_out_delta(0, t, dirty)
+        pool.kv_wait(0)
+        now = time.perf_counter()
+        rates.append(round(moved * s.R / (now - a) / 1e9, 1))
+        if rates[-1] < 28.0:
+            quiet_since = None
+        elif quiet_since is None:
+            quiet_since = a
+        if (quiet_since is not None and now - quiet_since >= quiet_s) or now - t0 > max_s:
+            break
+        time.sleep(0.02)
+    pool.kv_pool_destroy()
+    del gpu
+    return {"what": "delta swap-outs of 11 scattered 2 MiB records on a small pool, GB/s call to done, repeated until every "
+                    "probe of the last %g s reached 28 (normal: about 40)" % quiet_s,
+            "waited_s": round(time.perf_counter() - t0, 2), "first": rates[0], "min": min(rates), "last": rates[-1],
+            "slow_probes": sum(1 for r in rates if r < 28.0), "probes": len(rates)}
+
+
 def _pool(kv, torch, s, host_bytes, **kw):
     import os
     if "KVSWAP_PACK_VARIANT" in os.environ:  # development aid: force a kernel variant (echoed in the JSON line)
@@ -69,6 +113,7 @@ def config1(args):
     gpu, pool = _pool(kv, torch, s, 64 * MiB, flags=_flags(args, kv))
     gpu.random_(0, 256)
     torch.cuda.synchronize()
+    settled = settle(torch)
     out_us, in_us, all_ms = [], [], []
     for rep in range(args.warmup + args.steps * 5):
         t0 = time.perf_counter()
@@ -110,7 +155,8 @@ def config1(args):
             "per_request_in_us": {"median": _pct(in_us, 50), "p99": _pct(in_us, 99)},
             "batched_all8_out_in_ms": {"median": _pct(b_ms, 50), "p99": _pct(b_ms, 99)},
             "batched_gbps": round(2 * payload / (np.median(b_ms) * 1e-3) / 1e9, 3),
-            "mapped_swap_in": bool(args.mapped_swap_in), "mapped_swap_out": bool(args.mapped_swap_out)}
+            "mapped_swap_in": bool(args.mapped_swap_in), "mapped_swap_out": bool(args.mapped_swap_out),
+            "settle": settled}
 
 
 def _copy_fairness(kv, torch, s, gpu):
@@ -173,6 +219,7 @@ def config3(args):
                       flags=_flags(args, kv, kv.KV_FLAG_PROFILE))
     a = torch.randn(8192, 8192, device="cuda:0", dtype=torch.bfloat16)
     comp = torch.cuda.Stream()
+    settled = settle(torch)
 
     def compute(n):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -280,7 +327,7 @@ def config3(args):
             "streams": 4 if args.four_streams else 3 if args.scatter_stream else 2, "mapped_swap_in": bool(args.mapped_swap_in),
             "call_order": "swap-out first" if out_first else "swap-in first", "pack_variant": _variant_note(),
             "conflict_waits": st["conflict_waits"], "host_arena_bytes": st["host_arena_bytes"],
-            "small_copy_latency_us": fairness}
+            "settle": settled, "small_copy_latency_us": fairness}
 
 
 def config4(args):
@@ -310,6 +357,7 @@ def config4(args):
     gpu, pool = _pool(kv, torch, s, host_bytes, flags=_flags(args, kv, kv.KV_FLAG_PROFILE))
     gpu.random_(0, 256)
     torch.cuda.synchronize()
+    settled = settle(torch)
     work = rng.permutation(s.n_blocks)[:1200].astype(np.int32)
     full_ms, delta_ms, in_ms, fracs, delta_bytes, full_bytes = [], [], [], [], 0, 0
     delta_op_gbps, full_recs, probes = [], [], []
@@ -383,7 +431,7 @@ def config4(args):
             "bytes_moved_equals_dirty_blocks": True, "mapped_swap_in": bool(args.mapped_swap_in),
             "strided_copies": not getattr(args, "no_strided_copies", False), "pack_variant": _variant_note(),
             "host_new_extents": st["host_new_extents"], "d2h_copies": st["d2h_copies"],
-            "d2h_copies_strided": st["strided_copies"]}
+            "d2h_copies_strided": st["strided_copies"], "settle": settled}
 
 
 def config5(args):
@@ -398,6 +446,7 @@ def config5(args):
                                   "= %.1f GB, %d requests of 2048 blocks (10 GiB) per run length, one at a time"
                                   % (s.n_blocks, s.n_blocks * s.R / 1e9, n_req)}}
     gpu, pool = _pool(kv, torch, s, (2048 + 40) * s.R, flags=_flags(args, kv, kv.KV_FLAG_PROFILE))
+    out["settle"] = settle(torch)
     payload = 2048 * s.R
     for run in (1, 16):
         rng = synth.rng_for(5, stream=run)

@@ -210,9 +210,10 @@ int32_t swap_out_static(kv_pool_t* pool, const int32_t* block_table, int32_t n_b
                         void* stream);
 
 /* Section 3.2 swap-in path.  Copies the host image into new_block_table's blocks.  The
- * image is kept (Section 3.3).  When one scheduling step both resumes and preempts, issue the
- * swap-in the scheduler will wait for before the swap-out: calls reach the copy engines in
- * call order.  KV_ENOENT: no image, or a needed block's host copy is not
+ * image is kept (Section 3.3).  Note: any order of calls is correct; when one scheduling step
+ * both resumes and preempts, the resumed request is back soonest if its swap-in is issued
+ * before the step's swap-out (Algorithm 1's order, which kv_manager_iterate follows), because
+ * calls reach the copy engines in call order.  KV_ENOENT: no image, or a needed block's host copy is not
  * valid.  KV_EINVAL: n_blocks differs from the image, bad ids. */
 int32_t swap_in(kv_pool_t* pool, int64_t req, const int32_t* new_block_table, int32_t n_blocks);
 /* As swap_in, but logical blocks with resident_mask[j] != 0 are already on the GPU and are

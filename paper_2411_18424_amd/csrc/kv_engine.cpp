@@ -175,33 +175,22 @@ int32_t launch_pack(kv_pool* p, bool scatter, char* staging, const Move* mv, int
 // records far apart on the host: 45.5 GB/s one by one, 50.6 / 52.5 / 53.6 / 55.2 GB/s as
 // 2-D copies of 2 / 3 / 4 / 8 rows, for pitches up to 1 GiB.  Every copy is cut at
 // copy_chunk bytes.
-constexpr int64_t KV_MAX_COPY_PITCH = 1ll << 30;  // largest host pitch of a 2-D copy (measured up to here)
 
-int32_t issue_copies(kv_pool* p, bool to_host, char* slot, const Move* mv, int64_t m) {
-  hipStream_t s = to_host ? p->s_d2h : p->s_h2d;
-  hipEvent_t e0 = nullptr, e1 = nullptr;
-  if (p->profile && !p->plan) {
-    int32_t rc = get_timing_event(p, &e0);
-    if (rc) return rc;
-    rc = get_timing_event(p, &e1);
-    if (rc) return rc;
-    p->prof.push_back({to_host ? 2 : 3, m * p->R, e0, e1});
-    HIP_TRY(hipEventRecord(e0, s));
-  }
+void plan_copies(const Move* mv, int64_t m, int64_t R, int64_t copy_chunk, bool strided, std::vector<CopyDesc>* out) {
   auto run_end = [&](int64_t i) {  // last move of the maximal run of adjacent records that starts at i
     int64_t j = i;
-    while (j + 1 < m && mv[j + 1].host_off == mv[j].host_off + p->R) ++j;
+    while (j + 1 < m && mv[j + 1].host_off == mv[j].host_off + R) ++j;
     return j;
   };
   int64_t i = 0;
   while (i < m) {
     const int64_t j = run_end(i);
-    const int64_t len = j - i + 1, width = len * p->R;
+    const int64_t len = j - i + 1, width = len * R;
     // further rows: runs of the same length, a constant stride apart
     int64_t rows = 1, pitch = 0;
-    if (p->strided_copies && width < p->copy_chunk) {
+    if (strided && width < copy_chunk) {
       int64_t nx = j + 1;
-      while (nx < m && (rows + 1) * width <= p->copy_chunk) {
+      while (nx < m && (rows + 1) * width <= copy_chunk) {
         if (run_end(nx) - nx + 1 != len) break;
         const int64_t d = mv[nx].host_off - mv[nx - len].host_off;
         if (rows == 1) {
@@ -214,32 +203,48 @@ int32_t issue_copies(kv_pool* p, bool to_host, char* slot, const Move* mv, int64
         nx += len;
       }
     }
-    char* h = at(p->host, mv[i].host_off);
-    char* d = at(slot, i * p->R);
     if (rows > 1) {
-      (to_host ? p->st.d2h_copies : p->st.h2d_copies)++;
-      p->st.strided_copies++;
-      if (!p->plan) {
-        if (to_host)
-          HIP_TRY(hipMemcpy2DAsync(h, (size_t)pitch, d, (size_t)width, (size_t)width, (size_t)rows,
-                                   hipMemcpyDeviceToHost, s));
-        else
-          HIP_TRY(hipMemcpy2DAsync(d, (size_t)width, h, (size_t)pitch, (size_t)width, (size_t)rows,
-                                   hipMemcpyHostToDevice, s));
-      }
+      out->push_back({mv[i].host_off, i * R, width, rows, pitch});
       i += rows * len;
       continue;
     }
-    for (int64_t o = 0; o < width; o += p->copy_chunk) {
-      int64_t nb = std::min(p->copy_chunk, width - o);
-      (to_host ? p->st.d2h_copies : p->st.h2d_copies)++;
-      if (p->plan) continue;
-      if (to_host)
-        HIP_TRY(hipMemcpyAsync(h + o, d + o, (size_t)nb, hipMemcpyDeviceToHost, s));
-      else
-        HIP_TRY(hipMemcpyAsync(d + o, h + o, (size_t)nb, hipMemcpyHostToDevice, s));
-    }
+    for (int64_t o = 0; o < width; o += copy_chunk)
+      out->push_back({mv[i].host_off + o, i * R + o, std::min(copy_chunk, width - o), 1, 0});
     i = j + 1;
+  }
+}
+
+int32_t issue_copies(kv_pool* p, bool to_host, char* slot, const Move* mv, int64_t m) {
+  hipStream_t s = to_host ? p->s_d2h : p->s_h2d;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  if (p->profile && !p->plan) {
+    int32_t rc = get_timing_event(p, &e0);
+    if (rc) return rc;
+    rc = get_timing_event(p, &e1);
+    if (rc) return rc;
+    p->prof.push_back({to_host ? 2 : 3, m * p->R, e0, e1});
+    HIP_TRY(hipEventRecord(e0, s));
+  }
+  std::vector<CopyDesc> plan;
+  plan_copies(mv, m, p->R, p->copy_chunk, p->strided_copies, &plan);
+  for (const CopyDesc& c : plan) {
+    (to_host ? p->st.d2h_copies : p->st.h2d_copies)++;
+    if (c.rows > 1) p->st.strided_copies++;
+    if (p->plan) continue;
+    char* h = p->host + c.host_off;
+    char* d = slot + c.slot_off;
+    if (c.rows > 1) {
+      if (to_host)
+        HIP_TRY(hipMemcpy2DAsync(h, (size_t)c.pitch, d, (size_t)c.width, (size_t)c.width, (size_t)c.rows,
+                                 hipMemcpyDeviceToHost, s));
+      else
+        HIP_TRY(hipMemcpy2DAsync(d, (size_t)c.width, h, (size_t)c.pitch, (size_t)c.width, (size_t)c.rows,
+                                 hipMemcpyHostToDevice, s));
+    } else if (to_host) {
+      HIP_TRY(hipMemcpyAsync(h, d, (size_t)c.width, hipMemcpyDeviceToHost, s));
+    } else {
+      HIP_TRY(hipMemcpyAsync(d, h, (size_t)c.width, hipMemcpyHostToDevice, s));
+    }
   }
   if (e1) HIP_TRY(hipEventRecord(e1, s));
   return KV_OK;

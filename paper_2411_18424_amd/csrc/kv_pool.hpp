@@ -101,6 +101,14 @@ struct Move {
   int32_t phys;
 };
 
+// One host<->device copy of a swap: `rows` rows of `width` bytes, `pitch` bytes apart on the host
+// side and packed in staging (rows == 1: a plain contiguous copy).  Offsets are bytes into the
+// arena and into the staging slot.
+struct CopyDesc {
+  int64_t host_off, slot_off, width, rows, pitch;
+};
+constexpr int64_t KV_MAX_COPY_PITCH = 1ll << 30;  // largest host pitch of a 2-D copy (measured up to here)
+
 struct ProfRec {
   int32_t kind;
   int64_t bytes;
@@ -191,6 +199,7 @@ Op* find_op(std::deque<OpRef>& dq, uint64_t seq);
 int32_t host_wait_op(kv_pool* p, const OpRef& op);
 int32_t new_op(kv_pool* p, bool is_out, OpRef* out);
 void order_for_strided_copies(kv_pool* p, std::vector<Move>& mv);
+void plan_copies(const Move* mv, int64_t m, int64_t R, int64_t copy_chunk, bool strided, std::vector<CopyDesc>* out);
 int32_t enqueue_out(kv_pool* p, const std::vector<Move>& mv, const std::vector<hipEvent_t>& pre,
                     const OpRef& op);
 int32_t enqueue_in(kv_pool* p, const std::vector<Move>& mv, const std::vector<hipEvent_t>& pre_copy,

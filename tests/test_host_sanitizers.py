@@ -57,3 +57,19 @@ def test_polling_never_harvests_an_op_that_is_still_being_enqueued(tmp_path):
     run = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=60,
                          env=dict(os.environ, ASAN_OPTIONS="detect_leaks=0"))
     assert run.returncode == 0 and "reap_unissued: 0 failures" in run.stdout, run.stdout[-4000:]
+
+
+def test_copy_plans_move_exactly_the_moved_records(tmp_path):
+    """tests/host/copy_plan.cpp: move lists reordered for strided copies and cut into contiguous
+    and 2-D copies, applied to byte arrays on the CPU in both directions.  Host only."""
+    hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+    if not os.path.exists(hipcc):
+        pytest.skip("hipcc not found")
+    exe = str(tmp_path / "copy_plan")
+    srcs = [os.path.join(ROOT, "tests", "host", "copy_plan.cpp")] + SOURCES[1:]
+    build = subprocess.run([hipcc] + FLAGS + SANITIZERS["address_undefined"] + srcs + ["-o", exe],
+                           stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=600)
+    assert build.returncode == 0, build.stdout[-4000:]
+    run = subprocess.run([exe], stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=120,
+                         env=dict(os.environ, ASAN_OPTIONS="detect_leaks=0"))
+    assert run.returncode == 0 and "copy_plan: 0 failures" in run.stdout, run.stdout[-4000:]
