@@ -171,6 +171,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="config 2 only: leave the short runs of configs 1, 3, 4 and 5 out of the JSON line")
     ap.add_argument("--latency-reps", type=int, default=3)
     ap.add_argument("--config", type=int, default=2, choices=[1, 2, 3, 4, 5],
                     help="workload config; 2 is the headline (default), the others print their own JSON line")
@@ -523,6 +525,11 @@ def main() -> int:
     }
     if cpu is not None:
         result["cpu_baseline"] = cpu
+    if not args.headline_only:
+        # the other workload configs in short form (after the headline's timed region; each waits for
+        # the copy engines to be quiet first); `python bench.py --config N` is the long form of each
+        log("running configs 1, 4, 5, 3 in short form ...")
+        result["other_configs"] = bench_configs.other_configs(args)
     print(json.dumps(result), flush=True)
     return 0 if ok else 1
 

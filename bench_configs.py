@@ -487,7 +487,7 @@ def config5(args):
     # groups (20 blocks is the average granularity the paper reports for its block groups);
     # the packed path is flat across all of them
     sweep = {}
-    for run in (4, 20, 64, 256, 2048):
+    for run in (() if getattr(args, "no_group_sweep", False) else (4, 20, 64, 256, 2048)):
         rng = synth.rng_for(5, stream=1000 + run)
         ta, tb = synth.deal_tables(rng, s.n_blocks, [2048, 2048], run=run)
         t0 = time.perf_counter()
@@ -507,7 +507,32 @@ def config5(args):
                                  "direct_out_gbps": round(payload / (t1 - t0) / 1e9, 2),
                                  "direct_in_gbps": round(payload / (t2 - t1) / 1e9, 2),
                                  "packed_out_gbps": round(payload / (t4 - t3) / 1e9, 2)}
-    out["direct_by_group_length"] = sweep
+    if sweep:
+        out["direct_by_group_length"] = sweep
     pool.kv_pool_destroy()
     out["value"] = round(2 * payload / ((out["run_16"]["out_ms"] + out["run_16"]["in_ms"]) * 1e-3) / 1e9, 3)
+    return out
+
+
+def other_configs(args):
+    """Configs 1, 3, 4 and 5 in short form, for the default benchmark run: the stated counts (200
+    preemptions, 128 conversations), fewer repetitions and none of the side measurements.  Each
+    runs in pools of its own, after waiting for the copy engines to be quiet."""
+    import copy
+    import torch
+    a = copy.copy(args)
+    a.warmup, a.steps = 2, 4
+    a.preemptions, a.no_fairness, a.out_first, a.no_manager_pass = 200, True, False, False
+    a.conversations, a.arena_gib = 128, 56
+    a.requests, a.no_group_sweep = 2, True
+    a.mapped_swap_in = a.mapped_swap_out = a.four_streams = a.scatter_stream = a.no_strided_copies = False
+    a.copy_chunk_mib = 0
+    out = {}
+    for name, fn in (("config_1", config1), ("config_4", config4), ("config_5", config5), ("config_3", config3)):
+        t0 = time.perf_counter()
+        r = fn(a)
+        r.pop("metric", None)
+        r["seconds"] = round(time.perf_counter() - t0, 1)
+        out[name] = r
+        torch.cuda.empty_cache()
     return out

@@ -3,10 +3,12 @@
 // Section 3.2: asynchronous swapping on side streams, progress recorded with pooled events,
 // conflicts resolved by waiting for exactly the transfer concerned).
 //
-// Swap-out packs first and drains afterwards: all gathers of a call that fit the staging ring
-// run back to back (the request's GPU blocks are reusable after about a millisecond), then
-// the copies drain the ring; only a call larger than the ring interleaves the two.  Swap-in
-// is pipelined piece by piece.
+// Swap-out packs first and drains afterwards where gathers and copies share a stream (the
+// default): all gathers of a call that fit the staging ring run back to back (the request's
+// GPU blocks are reusable after about a millisecond), then the copies drain the ring; only a
+// call larger than the ring interleaves the two.  With KV_FLAG_FOUR_STREAMS the copies of a
+// piece are issued right behind its gather and the later gathers run under them.  Swap-in is
+// pipelined piece by piece.
 
 #include <algorithm>
 
@@ -361,6 +363,9 @@ int32_t enqueue_out(kv_pool* p, const std::vector<Move>& mv, const std::vector<h
       if ((rc = launch_pack(p, false, at(r.base, off + k * p->R), &mv[(size_t)(i + k)], ml))) return rc;
     }
     pending.push_back({i, mp, off});
+    // gathers and copies on streams of their own: a piece's copies start as soon as its gather is
+    // done, and the following gathers run under them
+    if (p->s_pack != p->s_d2h && (rc = flush())) return rc;
   }
   if ((rc = record(p, op->packed, p->s_pack))) return rc;
   if ((rc = flush())) return rc;

@@ -143,7 +143,8 @@ int32_t kv_pool_create(const kv_pool_config_t* cfg, kv_pool_t** out) {
     return std::max<int64_t>(1, b / p->R);
   };
   p->ring_out.cap = out_cap;
-  p->ring_out.piece_blocks = piece_blocks(out_cap, p->launch_blocks * p->R);
+  // four streams: gathers run under the copies, so the first piece is what the link waits for - keep it short
+  p->ring_out.piece_blocks = piece_blocks(out_cap, (cfg->flags & KV_FLAG_FOUR_STREAMS) ? (256ll << 20) : p->launch_blocks * p->R);
   p->ring_in.cap = in_cap;
   p->ring_in.piece_blocks = piece_blocks(in_cap, 512ll << 20);
   p->arena_blocks = cfg->host_bytes / p->R;
