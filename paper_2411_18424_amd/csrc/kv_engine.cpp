@@ -175,8 +175,9 @@ int32_t launch_pack(kv_pool* p, bool scatter, char* staging, const Move* mv, int
 // about 9 us per copy whatever its shape, so scattered block records (a delta swap-out's
 // dirty blocks, Section 3.3) cost a third of the dispatches.  Measured on MI355X, 2 MiB
 // records far apart on the host: 45.5 GB/s one by one, 50.6 / 52.5 / 53.6 / 55.2 GB/s as
-// 2-D copies of 2 / 3 / 4 / 8 rows, for pitches up to 1 GiB.  Every copy is cut at
-// copy_chunk bytes.
+// 2-D copies of 2 / 3 / 4 / 8 rows, for pitches up to 1 GiB; the same 13 us per copy for rows
+// of 32 KiB, 4 MiB, 12.5 MiB and 16 MiB.  Rows wider than 16 MiB (not measured, and efficient
+// on their own) always travel as plain copies.  Every copy is cut at copy_chunk bytes.
 
 void plan_copies(const Move* mv, int64_t m, int64_t R, int64_t copy_chunk, bool strided, std::vector<CopyDesc>* out) {
   auto run_end = [&](int64_t i) {  // last move of the maximal run of adjacent records that starts at i
@@ -190,7 +191,7 @@ void plan_copies(const Move* mv, int64_t m, int64_t R, int64_t copy_chunk, bool 
     const int64_t len = j - i + 1, width = len * R;
     // further rows: runs of the same length, a constant stride apart
     int64_t rows = 1, pitch = 0;
-    if (strided && width < copy_chunk) {
+    if (strided && width < copy_chunk && width <= KV_MAX_STRIDED_WIDTH) {
       int64_t nx = j + 1;
       while (nx < m && (rows + 1) * width <= copy_chunk) {
         if (run_end(nx) - nx + 1 != len) break;

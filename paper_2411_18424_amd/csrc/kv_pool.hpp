@@ -107,7 +107,8 @@ struct Move {
 struct CopyDesc {
   int64_t host_off, slot_off, width, rows, pitch;
 };
-constexpr int64_t KV_MAX_COPY_PITCH = 1ll << 30;  // largest host pitch of a 2-D copy (measured up to here)
+constexpr int64_t KV_MAX_COPY_PITCH = 1ll << 30;      // largest host pitch of a 2-D copy (measured up to here)
+constexpr int64_t KV_MAX_STRIDED_WIDTH = 16ll << 20;  // widest row of a 2-D copy (measured up to here)
 
 struct ProfRec {
   int32_t kind;

@@ -77,6 +77,7 @@ int main() {
         ++total_strided;
         EXPECT(p.strided_copies, "strided copy although switched off");
         EXPECT(c.pitch >= c.width && c.pitch <= kvi::KV_MAX_COPY_PITCH, "pitch %lld width %lld", (long long)c.pitch, (long long)c.width);
+        EXPECT(c.width <= kvi::KV_MAX_STRIDED_WIDTH, "row of %lld bytes in a strided copy", (long long)c.width);
       }
       for (int64_t r = 0; r < c.rows; ++r) {
         const int64_t h0 = c.host_off + r * c.pitch, s0 = c.slot_off + r * c.width;
