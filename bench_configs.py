@@ -530,8 +530,11 @@ def other_configs(args):
     out = {}
     for name, fn in (("config_1", config1), ("config_4", config4), ("config_5", config5), ("config_3", config3)):
         t0 = time.perf_counter()
-        r = fn(a)
-        r.pop("metric", None)
+        try:
+            r = fn(a)
+            r.pop("metric", None)
+        except Exception as e:  # e.g. not enough free device or pinned memory for this config's pool: say so, go on
+            r = {"error": "%s: %s" % (type(e).__name__, str(e)[:300])}
         r["seconds"] = round(time.perf_counter() - t0, 1)
         out[name] = r
         torch.cuda.empty_cache()
