@@ -77,7 +77,9 @@ typedef enum {
                                        in reserve goes first, then the records of the victim's last logical
                                        blocks, whose host_valid bits are cleared */
 #define KV_FLAG_FOUR_STREAMS     8u /* separate streams for kernels and copies of each direction (default:
-                                       one stream per direction, which needs fewer hardware queues).  Only
+                                       one stream per direction, which needs fewer hardware queues): the
+                                       copies of a piece of a swap-out start right behind its gather and the
+                                       later gathers run under them; scatters run under the next copies.  Only
                                        where the process has hardware queues to spare (HIP's default is 4
                                        per process, GPU_MAX_HW_QUEUES): streams that share a queue with the
                                        application's compute stream wait behind its kernels */
