@@ -489,13 +489,19 @@ def test_algorithm_1_iterations_move_requests_between_the_queues(kv):
     resumed, r = m.kv_manager_iterate()
     assert r["failures"] == 1 and m.kv_manager_failures() == [(7, kv.KV_ENOMEM_HOST)]
     assert m.kv_manager_where(7) == W[0]
+    # preemption that gives the victim's blocks up: the dispatcher frees them once the swap-out is enqueued
+    ids, _ = p.alloc_block_group(50, 40, 8)
+    assert p.kv_free_blocks()[0] == 512 - 40
+    m.kv_manager_iterate(swap_out=[(50, ids)], free_out_blocks=True)
+    m.kv_manager_drain()
+    assert p.kv_free_blocks()[0] == 512 and p.kv_host_len(50)[0] == 40
     # delta swap-outs through the iteration
     resumed, r = m.kv_manager_iterate(swap_out=[(1, tc, np.ones(30, np.uint8))])
     m.kv_manager_drain()
     st = m.kv_manager_iteration_stats()
-    assert st["iterations"] == 6 and st["swap_outs"] == 5 and st["swap_ins"] == 2 and st["conflicts"] == 1
+    assert st["iterations"] == 7 and st["swap_outs"] == 6 and st["swap_ins"] == 2 and st["conflicts"] == 1
     assert st["async_iterations"] == 1 and st["sync_iterations"] == 1 and st["resumed"] == 2
-    assert p.kv_stats()["blocks_out"] == 30 * 4 and p.kv_stats()["blocks_in"] == 60
+    assert p.kv_stats()["blocks_out"] == 30 * 4 + 40 and p.kv_stats()["blocks_in"] == 60
     m.kv_manager_destroy()
 
 

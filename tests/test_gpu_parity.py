@@ -719,6 +719,67 @@ def test_algorithm_1_iterations_match_oracle(harness, flags):
         m.kv_manager_destroy()
 
 
+def test_algorithm_1_with_the_allocator_and_blocks_freed_by_the_dispatcher(harness):
+    """The scheduler loop of the benchmark's config 3 in small: tables come from the block-group
+    allocator, kv_manager_iterate preempts with KV_IT_FREE_OUT_BLOCKS (the dispatcher frees the
+    victim's blocks right after its swap-out is enqueued, so the allocator parks them until the
+    gather has read them) and resumes into freshly allocated blocks - often the ones just vacated.
+    New KV is written into every request before it leaves; the oracle replays the same calls."""
+    shape = synth.KVShape("s", 8, 8, 128, 16, 2, 256, "bf16")  # R = 512 KiB; the pool is tight on purpose
+    h = harness(shape, cfg=39, host_bytes=400 * MiB, fill="random")
+    kv = h.kv
+    m = kv.KVManager(h.pool)
+    checker = AllocChecker(shape.n_blocks)
+    try:
+        rng = synth.rng_for(39)
+        n_req, lag = 24, 2
+        nblk = rng.integers(20, 90, size=n_req)
+        out_tab, in_tab, waiting = {}, {}, set()
+        for i in range(n_req + lag):
+            j = i - lag
+            swap_in, swap_out = [], []
+            if i < n_req:
+                ids, _ = h.pool.alloc_block_group(i, int(nblk[i]), 8)   # waits for parked blocks if it must
+                checker.on_alloc(i, ids)
+                h.overwrite_blocks(ids, synth.fresh_tokens(rng, shape, len(ids)))  # the request's KV
+                out_tab[i] = ids
+                swap_out = [(i, ids)]
+            if j >= 0:
+                ids2, _ = h.pool.alloc_block_group(10**6 + j, int(nblk[j]), 8)
+                checker.on_alloc(10**6 + j, ids2)
+                in_tab[j] = ids2
+                swap_in = [(j, ids2)]
+                waiting.add(j)
+            resumed, r = m.kv_manager_iterate(swap_in=swap_in, swap_out=swap_out, free_out_blocks=True,
+                                              force_mode=1 + i % 2)
+            assert r["conflicts"] == 0   # the allocator never hands out a block the iteration's swap-out still owns
+            if swap_out:
+                h.oracle.swap_out(i, out_tab[i])
+                checker.on_free(i, out_tab[i])    # freed by the dispatcher
+            if swap_in:
+                h.oracle.swap_in(j, in_tab[j])
+            while True:                            # the scheduler has nothing else to do: poll (step 1)
+                for q in resumed:
+                    waiting.discard(q)
+                    h.pool.kv_host_release(q)
+                    h.oracle.host_release(q)
+                    h.pool.free_block_group(10**6 + q, in_tab[q])
+                    checker.on_free(10**6 + q, in_tab.pop(q))
+                if j < 0 or j not in waiting:
+                    break
+                resumed, _ = m.kv_manager_iterate()
+        m.kv_manager_drain()
+        assert not waiting and m.kv_manager_failures() == []
+        h.pool.kv_wait_all()
+        h.assert_pool_equal()
+        st = h.pool.kv_stats()
+        assert st["bytes_out"] == h.oracle.bytes_out and st["bytes_in"] == h.oracle.bytes_in
+        free, largest = h.pool.kv_free_blocks()
+        assert free == shape.n_blocks == largest and checker.n_used() == 0
+    finally:
+        m.kv_manager_destroy()
+
+
 def test_concurrent_host_threads(harness):
     """The pool may be driven from several host threads: four threads swap disjoint requests
     out and back in at the same time."""
