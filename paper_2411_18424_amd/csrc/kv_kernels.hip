@@ -256,18 +256,25 @@ int64_t kv_max_launch_blocks(uint32_t C, uint32_t P, int unroll, int variant) {
 
 enum LaunchMode { MODE_TILE_3D = 0, MODE_PERSISTENT = 1, MODE_TILE_XCD = 2 };
 
+// The extended launch attaches the dispatch's own begin / end timestamps to two events; without
+// events the plain launch is used (which a stream capture records like any other kernel node).
+#define KV_LAUNCH(kernel, grid_dim, block_dim)                                                    \
+  do {                                                                                            \
+    if (start || stop)                                                                            \
+      hipExtLaunchKernelGGL(kernel, grid_dim, block_dim, 0, stream, start, stop, 0, a);           \
+    else                                                                                          \
+      hipLaunchKernelGGL(kernel, grid_dim, block_dim, 0, stream, a);                              \
+  } while (0)
+
 template <int WG, int U, bool FULL, bool SCATTER, bool SC1>
 static hipError_t launch_one(const KvPackArgs& a, int mode, int grid, hipStream_t stream,
                              hipEvent_t start, hipEvent_t stop) {
   if (mode == MODE_PERSISTENT) {
-    hipExtLaunchKernelGGL((kv_pack_persistent_kernel<WG, U, FULL, SCATTER, SC1>), dim3(grid), dim3(WG), 0,
-                          stream, start, stop, 0, a);
+    KV_LAUNCH((kv_pack_persistent_kernel<WG, U, FULL, SCATTER, SC1>), dim3(grid), dim3(WG));
   } else if (mode == MODE_TILE_XCD) {
-    hipExtLaunchKernelGGL((kv_pack_xcd_kernel<WG, U, FULL, SCATTER, SC1>), dim3(grid), dim3(WG), 0,
-                          stream, start, stop, 0, a);
+    KV_LAUNCH((kv_pack_xcd_kernel<WG, U, FULL, SCATTER, SC1>), dim3(grid), dim3(WG));
   } else {
-    hipExtLaunchKernelGGL((kv_pack_tile_kernel<WG, U, FULL, SCATTER, SC1>),
-                          dim3(a.tiles_per_chunk, a.P, a.m), dim3(WG), 0, stream, start, stop, 0, a);
+    KV_LAUNCH((kv_pack_tile_kernel<WG, U, FULL, SCATTER, SC1>), dim3(a.tiles_per_chunk, a.P, a.m), dim3(WG));
   }
   return hipGetLastError();
 }

@@ -1,5 +1,6 @@
 """swap_out_static, the entry point that allocates nothing, against swap_out (and the oracle):
-two calls in a row, the second with a smaller input, through the C ABI."""
+two calls in a row, the second with a smaller input, through the C ABI; and recorded into a HIP
+graph by stream capture (it allocates nothing, so it can be), every replay checked."""
 
 import numpy as np
 import pytest
@@ -48,5 +49,35 @@ def test_swap_out_static_matches_swap_out():
         pool.swap_out_static(np.zeros(0, np.int32), dst.data_ptr(), 0)
         torch.cuda.synchronize()
         assert (dst.numpy() == 0x11).all()
+    finally:
+        h.close()
+
+
+def test_swap_out_static_in_a_captured_graph():
+    import torch
+    from gpu_util import Harness
+    shape = synth.KVShape("s", 8, 8, 128, 16, 2, 512, "bf16")  # R = 512 KiB
+    h = Harness(shape, 72, 64 * MiB, fill="random")
+    try:
+        rng = synth.rng_for(72)
+        n = 90
+        table = rng.permutation(shape.n_blocks)[:n].astype(np.int32)
+        dst = torch.empty(n * shape.R, dtype=torch.uint8).pin_memory()
+        side = torch.cuda.Stream()
+        # eager call first (loads the code object, proves the path)
+        h.pool.swap_out_static(table, dst.data_ptr(), side.cuda_stream)
+        side.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            h.pool.swap_out_static(table, dst.data_ptr(), torch.cuda.current_stream().cuda_stream)
+        for rep in range(3):
+            # eager work between the replays: the blocks get new content on both sides
+            h.overwrite_blocks(table, synth.fresh_tokens(rng, shape, n))
+            dst.fill_(0xEE)
+            g.replay()
+            torch.cuda.synchronize()
+            h.oracle.swap_out(100 + rep, table)
+            got = dst.numpy().reshape(n, shape.P, shape.C)
+            assert np.array_equal(got, h.oracle.host[100 + rep].Hq), "replay %d delivered other bytes" % rep
     finally:
         h.close()
