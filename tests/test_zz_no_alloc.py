@@ -53,6 +53,26 @@ def test_swap_out_static_matches_swap_out():
         h.close()
 
 
+@pytest.mark.parametrize("L,H,D,N,n", [(3, 3, 40, 300, 200),    # chunk of 3840 bytes: not a multiple of the tile
+                                       (2, 4, 64, 256, 63),     # 63 blocks: the 3-D grid (below 64 blocks)
+                                       (1, 40, 128, 200, 150)]) # one layer, 160 KiB chunks, XCD-aware order
+def test_swap_out_static_on_other_shapes(L, H, D, N, n):
+    import torch
+    from gpu_util import Harness
+    shape = synth.KVShape("s", L, H, D, 16, 2, N, "fp16")
+    h = Harness(shape, 73, 8 * MiB, fill="random")
+    try:
+        rng = synth.rng_for(73)
+        table = rng.permutation(N)[:n].astype(np.int32)
+        dst = torch.empty(n * shape.R, dtype=torch.uint8).pin_memory()
+        dst.fill_(0xEE)
+        h.pool.swap_out_static(table, dst.data_ptr(), 0)
+        h.oracle.swap_out(0, table)
+        assert np.array_equal(dst.numpy().reshape(n, shape.P, shape.C), h.oracle.host[0].Hq)
+    finally:
+        h.close()
+
+
 def test_swap_out_static_in_a_captured_graph():
     import torch
     from gpu_util import Harness
