@@ -692,7 +692,7 @@ void order_for_strided_copies(kv_pool* p, std::vector<Move>& mv) {
     const int64_t len = runs[order[g0]].len;
     const int64_t max_rows = std::max<int64_t>(1, p->copy_chunk / (len * p->R));
     const int64_t max_stride = KV_MAX_COPY_PITCH / p->R;
-    if (n < 3 || max_rows < 2) {
+    if (n < 3 || max_rows < 2 || len * p->R > KV_MAX_STRIDED_WIDTH) {
       for (size_t a = g0; a < g1; ++a) emit(runs[order[a]]);
       g0 = g1;
       continue;
