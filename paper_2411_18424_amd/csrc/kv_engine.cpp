@@ -154,7 +154,7 @@ int32_t launch_pack(kv_pool* p, bool scatter, char* staging, const Move* mv, int
   a.C = (uint32_t)p->C;
   a.P = (uint32_t)np;
   a.m = (uint32_t)m;
-  a.tiles_per_chunk = a.n_tiles = a.pad = 0;
+  a.tiles_per_chunk = a.n_tiles = a.xcd_blocks = 0;
   for (int64_t i = 0; i < m; ++i) a.table[i] = mv[i].phys;
   hipEvent_t e0 = nullptr, e1 = nullptr;
   if (p->profile) {

@@ -17,7 +17,7 @@ struct KvPackArgs {
   uint32_t m;            // blocks in this launch (<= KV_MAX_LAUNCH_BLOCKS)
   uint32_t tiles_per_chunk;
   uint32_t n_tiles;      // m * P * tiles_per_chunk
-  uint32_t pad;
+  uint32_t xcd_blocks;   // XCD-aware order: blocks one XCD works on at a time (set by the launcher)
   int32_t table[KV_MAX_LAUNCH_BLOCKS];  // physical block id of each of the m blocks
 };
 

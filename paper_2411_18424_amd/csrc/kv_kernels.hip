@@ -20,9 +20,9 @@
 //  TILE, XCD-aware order (default for launches of 64 blocks or more): the same tiles through a
 //    1-D grid.  Workgroups are dealt round-robin to the 8 XCDs (each with its own L2), so
 //    workgroup w runs on XCD w % 8 (confirmed by reading XCC_ID in a probe kernel); the mapping gives every XCD two blocks of the launch at a
-//    time and lets it walk them chunk by chunk, alternating between the two (plane 0 of block
-//    A, plane 0 of block B, plane 1 of A ...), instead of spreading every chunk's tiles over
-//    all XCDs.  Measured on MI355X on the Llama-3-8B shape (896-block launches, read+write):
+//    time (one where a block record is 4 MiB or more, see kv_xcd_blocks) and lets it walk them
+//    chunk by chunk, alternating between the two (plane 0 of block A, plane 0 of block B, plane 1
+//    of A ...), instead of spreading every chunk's tiles over all XCDs.  Measured on MI355X on the Llama-3-8B shape (896-block launches, read+write):
 //    gather 6.57 against 6.18 TB/s, scatter 6.52 against 5.99 TB/s with block groups of 8, and
 //    6.34 against 5.91 / 6.04 against 5.82 with fully fragmented tables; one block per XCD gives
 //    6.37 / 6.32, four 6.38 / 6.41, eight 6.18 / 6.13, whole chunks per XCD 5.70 / 5.95.
@@ -96,20 +96,20 @@ __global__ __launch_bounds__(WG) void kv_pack_tile_kernel(const KvPackArgs a) {
   move_tile<WG, U, FULL, SCATTER, SC1>(pool_ptr, stag_ptr, (a.C >> 4) - v0);
 }
 
-// The tile kernel in XCD-aware order: grid = groups of 16 blocks x 8 XCDs x (2 blocks' tiles).
+// The tile kernel in XCD-aware order: grid = groups of 8 XCDs x (K blocks' tiles), K = a.xcd_blocks
+// blocks per XCD at a time (see kv_xcd_blocks).
 constexpr uint32_t KV_XCDS = 8;
-constexpr uint32_t KV_XCD_BLOCKS = 2;  // blocks one XCD works on at a time
 
 template <int WG, int U, bool FULL, bool SCATTER, bool SC1>
 __global__ __launch_bounds__(WG) void kv_pack_xcd_kernel(const KvPackArgs a) {
   constexpr uint32_t TILE_VECS = WG * U;
   const uint32_t w = blockIdx.x, xcd = w % KV_XCDS, slot = w / KV_XCDS;
-  const uint32_t tpc = a.tiles_per_chunk;
-  const uint32_t per = KV_XCD_BLOCKS * tpc * a.P;  // tiles of the blocks one XCD holds
+  const uint32_t tpc = a.tiles_per_chunk, K = a.xcd_blocks;
+  const uint32_t per = K * tpc * a.P;           // tiles of the blocks one XCD holds
   const uint32_t g = slot / per, r = slot - g * per;
-  const uint32_t c = r / tpc, t = r - c * tpc;     // chunk among the XCD's blocks, tile in it
-  const uint32_t k = (g * KV_XCDS + xcd) * KV_XCD_BLOCKS + c % KV_XCD_BLOCKS, p = c / KV_XCD_BLOCKS;
-  if (k >= a.m) return;  // the last group of 16 may be short
+  const uint32_t c = r / tpc, t = r - c * tpc;  // chunk among the XCD's blocks, tile in it
+  const uint32_t k = (g * KV_XCDS + xcd) * K + c % K, p = c / K;
+  if (k >= a.m) return;  // the last group may be short
   const int64_t b = a.table[k];
   const uint32_t v0 = t * TILE_VECS;
   u32x4* pool_ptr =
@@ -217,6 +217,14 @@ static int store_policy(int variant, bool scatter, bool xcd_order) {
   return scatter ? (bits >> 1) & 1 : bits & 1;
 }
 
+// Blocks one XCD works on at a time in XCD-aware order.  Measured on MI355X (read+write TB/s,
+// gather / scatter): Llama-3-8B shape (record 2 MiB, 16 GiB pool) one block 6.75 / 6.49, two 6.84 /
+// 6.59, four 6.68 / 6.42; Qwen2-72B shape (record 5 MiB, 236 GB pool) one 6.16 / 6.76 - 6.82, two
+// 6.04 - 6.13 / 6.49 - 6.67, four 5.93 - 6.10 / 6.16 - 6.60; Llama-2-13B shape (record 12.5 MiB,
+// 230 GB pool) one 6.27 / 6.67, two 6.18 / 6.38, four 6.13 / 6.13.  An XCD wants about 4 MiB of
+// records in hand: two blocks while a record is smaller than that, one block otherwise.
+static uint32_t kv_xcd_blocks(uint32_t C, uint32_t P) { return (uint64_t)C * P >= (4u << 20) ? 1u : 2u; }
+
 static int pick_wg(int variant) { return variant == KV_PACK_TILE_1024 ? 1024 : 256; }
 
 int kv_pick_unroll(uint32_t C, int wg) {
@@ -306,8 +314,9 @@ hipError_t kv_launch_pack(bool scatter, const KvPackArgs& a_in, int unroll, int 
   if (grid <= 0) grid = 2048;
   if ((uint64_t)grid > n_tiles) grid = (int)n_tiles;
   if (mode == MODE_TILE_3D && variant != KV_PACK_TILE_256 && a.m >= KV_XCD_MIN_BLOCKS) {
-    // XCD-aware order; the grid is padded to whole groups of 16 blocks
-    const uint64_t group = (uint64_t)KV_XCDS * KV_XCD_BLOCKS;
+    // XCD-aware order; the grid is padded to whole groups of 8 or 16 blocks
+    a.xcd_blocks = kv_xcd_blocks(a.C, a.P);
+    const uint64_t group = (uint64_t)KV_XCDS * a.xcd_blocks;
     const uint64_t padded = (a.m + group - 1) / group * group * a.P * a.tiles_per_chunk;
     if (padded * (uint64_t)s.wg <= (1ull << 31)) {
       mode = MODE_TILE_XCD;

@@ -235,7 +235,7 @@ int32_t kv_pool_create(const kv_pool_config_t* cfg, kv_pool_t** out) {
       a.C = (uint32_t)p->C;
       a.P = (uint32_t)p->P;
       a.m = 1;
-      a.tiles_per_chunk = a.n_tiles = a.pad = 0;
+      a.tiles_per_chunk = a.n_tiles = a.xcd_blocks = 0;
       a.table[0] = 0;
       TRY_OR_BAIL(kv_launch_pack(false, a, p->unroll, p->variant, p->grid, p->s_pack, nullptr, nullptr));
       TRY_OR_BAIL(hipStreamSynchronize(p->s_pack));
@@ -436,7 +436,7 @@ int32_t swap_out_static(kv_pool_t* p, const int32_t* block_table, int32_t n_bloc
   a.C = (uint32_t)p->C;
   a.P = (uint32_t)p->P;
   a.m = (uint32_t)n_blocks;
-  a.tiles_per_chunk = a.n_tiles = a.pad = 0;
+  a.tiles_per_chunk = a.n_tiles = a.xcd_blocks = 0;
   for (int32_t i = 0; i < n_blocks; ++i) a.table[i] = block_table[i];
   HIP_TRY(kv_launch_pack(false, a, p->unroll, p->variant, p->grid, s, nullptr, nullptr));
   HIP_TRY(hipMemcpyAsync(host_dst, p->static_staging, (size_t)n_blocks * (size_t)p->R, hipMemcpyDeviceToHost, s));
