@@ -26,6 +26,11 @@ HBM_PEAK_GBPS = 8000.0  # MI355X published HBM3E bandwidth
 GiB = 1 << 30
 
 
+def dist3(v):
+    v = sorted(v)
+    return {"min": round(v[0], 3), "median": round(v[len(v) // 2], 3), "max": round(v[-1], 3)}
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -263,6 +268,7 @@ def main() -> int:
     log("settle:", settled)
 
     phase_s = [0.0, 0.0]  # time in the swap-out and the swap-in half of the steps (host clock)
+    step_ms = []  # (swap-out half, swap-in half) of every step
 
     def step():
         nonlocal cur, nxt
@@ -275,6 +281,7 @@ def main() -> int:
         t_c = time.perf_counter()
         phase_s[0] += t_b - t_a
         phase_s[1] += t_c - t_b
+        step_ms.append(((t_b - t_a) * 1e3, (t_c - t_b) * 1e3))
         cur, nxt = nxt, cur
 
     for _ in range(args.warmup):
@@ -283,6 +290,7 @@ def main() -> int:
     dev_state = device_state()  # right after the warm-up steps, before the timed region
     torch.cuda.synchronize()
     phase_s[0] = phase_s[1] = 0.0
+    del step_ms[:]
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
@@ -459,6 +467,8 @@ def main() -> int:
         },
         "out_gbps": round(payload * args.steps / phase_s[0] / 1e9, 3),
         "in_gbps": round(payload * args.steps / phase_s[1] / 1e9, 3),
+        "step_halves_ms": {"what": "host clock, swap-out call -> all done and swap-in call -> all done, over the timed steps",
+                           "out": dist3([a for a, _ in step_ms]), "in": dist3([b for _, b in step_ms])},
         "roofline": {
             "bound": "hbm",
             "kernel": "%s direction of the pack kernel (the slower of the two): %s" % (low, pack[low]["kernel"]),

@@ -53,19 +53,20 @@ def settle(torch, max_s=60.0, quiet_s=3.0):
     few per cent).  That is the machine's state, not the workload's: timing starts when every
     probe of the last quiet_s seconds was back to normal.  The probe is the library's own path on a
     small pool of its own: a delta swap-out of 11 scattered 2 MiB block records (gather, then one
-    copy per record or pair).  Returns what it saw."""
+    copy per record or pair), and the same records swapped back in.  Returns what it saw."""
     from paper_2411_18424_amd import kvswap as kv, synth
     s = synth.LLAMA3_8B.with_blocks(64)
     gpu = torch.zeros(s.R * s.n_blocks, dtype=torch.uint8, device="cuda:0")
     pool = kv.KVPool(n_layers=s.n_layers, n_kv_heads=s.n_kv_heads, head_dim=s.head_dim, block_size=s.block_size,
                      elt_bytes=s.elt_bytes, n_gpu_blocks=s.n_blocks, gpu_base=gpu.data_ptr(), host_bytes=128 * s.R,
-                     staging_out_bytes=64 * s.R, staging_in_bytes=2 * s.R)
+                     staging_out_bytes=64 * s.R, staging_in_bytes=32 * s.R)
     t = np.arange(64, dtype=np.int32)
     pool.swap_out(0, t)
     pool.kv_wait(0)
     dirty = np.zeros(64, np.uint8)
     dirty[[0, 1, 3, 6, 10, 15, 21, 28, 36, 45, 55]] = 1  # gaps 1, 2, 3, ...: no arithmetic progression beyond pairs
-    rates, t0 = [], time.perf_counter()
+    resident = (1 - dirty).astype(np.uint8)
+    rates, rates_in, t0 = [], [], time.perf_counter()
     quiet_since = None
     while True:
         a = time.perf_counter()
@@ -73,7 +74,12 @@ def settle(torch, max_s=60.0, quiet_s=3.0):
         pool.kv_wait(0)
         now = time.perf_counter()
         rates.append(round(moved * s.R / (now - a) / 1e9, 1))
-        if rates[-1] < 28.0:
+        pool.swap_in_delta(0, t, resident)  # the same records back: small host-to-device copies, then a scatter
+        pool.kv_wait(0)
+        back = time.perf_counter()
+        rates_in.append(round(moved * s.R / (back - now) / 1e9, 1))
+        now = back
+        if rates[-1] < 28.0 or rates_in[-1] < 28.0:
             quiet_since = None
         elif quiet_since is None:
             quiet_since = a
@@ -82,10 +88,12 @@ def settle(torch, max_s=60.0, quiet_s=3.0):
         time.sleep(0.02)
     pool.kv_pool_destroy()
     del gpu
-    return {"what": "delta swap-outs of 11 scattered 2 MiB records on a small pool, GB/s call to done, repeated until every "
-                    "probe of the last %g s reached 28 (normal: about 40)" % quiet_s,
+    return {"what": "delta swap-outs of 11 scattered 2 MiB records on a small pool (and the same records swapped back in), "
+                    "GB/s call to done, repeated until every probe of the last %g s reached 28 (normal: about 40)" % quiet_s,
             "waited_s": round(time.perf_counter() - t0, 2), "first": rates[0], "min": min(rates), "last": rates[-1],
-            "slow_probes": sum(1 for r in rates if r < 28.0), "probes": len(rates)}
+            "slow_probes": sum(1 for r in rates if r < 28.0), "probes": len(rates),
+            "back_in": {"first": rates_in[0], "min": min(rates_in), "last": rates_in[-1],
+                        "slow_probes": sum(1 for r in rates_in if r < 28.0)}}
 
 
 def _pool(kv, torch, s, host_bytes, **kw):
