@@ -188,6 +188,10 @@ def main() -> int:
                     help="one copy per run of adjacent host records (KV_FLAG_NO_STRIDED_COPIES), for comparison")
     ap.add_argument("--no-fairness", action="store_true", help="config 3: skip the small-copy latency measurement")
     ap.add_argument("--no-manager-pass", action="store_true", help="config 3: skip the pass through kv_manager_iterate")
+    ap.add_argument("--no-defer-copies", action="store_true",
+                    help="KV_FLAG_NO_DEFER_COPIES: every swap-out's copies are enqueued inside the call and wait for "
+                         "their gathers on the device (default: the pool's copy thread enqueues them once the gathers "
+                         "have finished)")
     ap.add_argument("--out-first", action="store_true",
                     help="config 3: issue the swap-out of an iteration before its swap-in (default: swap-in first)")
     ap.add_argument("--requests", type=int, default=4, help="config 5: 10 GiB requests per run length")
@@ -258,6 +262,7 @@ def main() -> int:
                      gpu_base=gpu.data_ptr(), host_bytes=payload + 64 * len(victims) * s.R,
                      flags=kv.KV_FLAG_PROFILE | (kv.KV_FLAG_FOUR_STREAMS if args.four_streams else 0)
                      | (kv.KV_FLAG_SCATTER_STREAM if args.scatter_stream else 0)
+                     | (kv.KV_FLAG_NO_DEFER_COPIES if args.no_defer_copies else 0)
                      | (kv.KV_FLAG_MAPPED_SWAP_IN if args.mapped_swap_in else 0),
                      pack_variant=int(os.environ.get("KVSWAP_PACK_VARIANT", "0")),
                      copy_chunk_bytes=args.copy_chunk_mib << 20, max_piece_bytes=args.max_piece_mib << 20)

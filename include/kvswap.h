@@ -86,6 +86,21 @@ typedef enum {
 #define KV_FLAG_SCATTER_STREAM 128u /* three streams: the scatter kernels get a stream of their own, so the
                                        scatter of a piece runs under the next piece's host-to-device copy */
 
+#define KV_FLAG_NO_DEFER_COPIES 512u /* every swap-out's device-to-host copies are enqueued inside the swap-out
+                                       call and wait for their gathers on the device.  Default (flag off): a
+                                       swap-out that moves defer_min_bytes or more has its copies handed to the
+                                       runtime only when the gathers they follow have finished - a thread of the
+                                       pool waits for each piece's gathers on the host, then enqueues its copies
+                                       (Section 3.2's control of dispatch order, made inside the library).
+                                       Copies enqueued at once wait inside a copy engine's queue, where a
+                                       host-to-device copy of another request can end up behind them: a swap-in
+                                       issued right after a swap-out then finishes late, and callers have to
+                                       issue the swap-in first.  With the copies held back the order of the two
+                                       calls does not matter.  The swap-out call returns when its gathers are
+                                       enqueued, as always; kv_query reports it unfinished and the waits block
+                                       until the copies are done; the next swap-out, and a swap-in of the same
+                                       request, first wait on the host for the hand-over.  Costs a few
+                                       microseconds per swap-out. */
 #define KV_FLAG_NO_STRIDED_COPIES 256u /* one copy per run of adjacent host records, never a 2-D copy over
                                        several equal runs a constant stride apart (for comparison) */
 
@@ -123,6 +138,9 @@ typedef struct {
   int32_t mapped_in_grid;   /* workgroups of the mapped swap-in / swap-out kernels; 0 = default 64 */
   int32_t mapped_out_max_blocks; /* with KV_FLAG_MAPPED_SWAP_OUT: largest moved set that takes the
                                mapped path; 0 = every swap-out; < 0 is KV_EINVAL */
+  int64_t defer_min_bytes;  /* smallest swap-out (bytes moved) whose copies are held back until its
+                               gathers have finished (see KV_FLAG_NO_DEFER_COPIES); 0 = default
+                               16 MiB, 1 = every swap-out; < 0 is KV_EINVAL */
 } kv_pool_config_t;
 
 /* Section 3.1 (KV pool + block groups).  Creates the pool object: pinned host arena,

@@ -70,7 +70,7 @@ void reap(kv_pool* p) {
   }
   for (auto& o : p->ops_out) {
     if (o->packed_done) continue;
-    if (!o->issued || p->event_query(o->packed) != hipSuccess) break;
+    if (!o->packed_recorded || p->event_query(o->packed) != hipSuccess) break;
     o->packed_done = true;
     p->pack_done_seq = o->seq;
   }
@@ -116,8 +116,11 @@ Op* find_op(std::deque<OpRef>& dq, uint64_t seq) {
 }
 
 // Host wait for one op (lock held by caller; short waits only on rare paths).
-int32_t host_wait_op(kv_pool* p, const OpRef& op) {
+int32_t host_wait_op(kv_pool* p, const OpRef& op_ref) {
+  const OpRef op = op_ref;  // the caller's reference may point into the request table
   if (!op || op->all_done || p->plan) return KV_OK;
+  int32_t rc = wait_issued(p, op);  // drops the lock while a held-back swap-out is handed over
+  if (rc) return rc;
   if (op->done) HIP_TRY(hipEventSynchronize(op->done));
   reap(p);
   return KV_OK;
@@ -321,6 +324,88 @@ int32_t ring_claim(kv_pool* p, ByteRing* r, int64_t len, uint64_t op_seq, hipStr
   return KV_OK;
 }
 
+// Copies of one gathered piece (moves [first, first + count) at ring offset off) to the host, and
+// the event that gives its ring region back.
+static int32_t drain_piece(kv_pool* p, ByteRing& r, uint64_t op_seq, const Move* mv, int64_t first,
+                           int64_t count, int64_t off) {
+  int32_t rc;
+  if ((rc = issue_copies(p, true, at(r.base, off), mv + first, count))) return rc;
+  for (Region& g : r.live)
+    if (g.off == off && g.op_seq == op_seq && !g.recorded) {
+      if ((rc = record(p, g.freed, p->s_d2h))) return rc;
+      g.recorded = true;
+    }
+  return KV_OK;
+}
+
+// The copy thread of a pool (none with KV_FLAG_NO_DEFER_COPIES).  A device-to-host copy that is handed to
+// the runtime while the gather it follows has not finished waits for it inside a copy engine's
+// queue, and a host-to-device copy of another request that the runtime puts on the same engine
+// afterwards waits behind it (seen in a serving loop beside GEMMs: a swap-in issued right after a
+// swap-out finished only when two queued swap-outs had drained).  Here a swap-out's copies reach
+// the runtime only when nothing holds them back any more: this thread waits on the host for
+// each piece's gathers, then enqueues the piece's copies, and after the last piece the op's
+// completion event.  Until then the op counts as not issued: nothing polls or waits for its
+// completion event (wait_issued), and the next swap-out waits for this one's hand-over.
+static void copy_thread_main(kv_pool* p) {
+  (void)hipSetDevice(p->device);
+  std::unique_lock<std::mutex> lk(p->mu);
+  for (;;) {
+    p->cv_job.wait(lk, [&] { return p->copy_thread_stop || !p->jobs.empty(); });
+    if (p->jobs.empty()) return;
+    DeferredOut job = std::move(p->jobs.front());
+    p->jobs.pop_front();
+    int32_t rc = KV_OK;
+    auto note = [&](int32_t r2) {
+      if (r2 && !rc) rc = r2;
+    };
+    for (const DeferredPiece& q : job.pieces) {
+      lk.unlock();
+      const hipError_t e = hipEventSynchronize(q.ready);
+      lk.lock();
+      if (e != hipSuccess) note(fail(KV_EHIP, "copy thread: hipEventSynchronize: %s", hipGetErrorString(e)));
+      note(stream_wait(p, p->s_d2h, q.ready));  // already complete: costs nothing, and keeps the order on the device explicit
+      note(drain_piece(p, p->ring_out, job.op->seq, job.mv.data(), q.first, q.count, q.off));
+    }
+    note(record(p, job.op->done, p->s_d2h));
+    job.op->issued = true;
+    if (rc && !p->copy_thread_rc) {
+      p->copy_thread_rc = rc;
+      p->copy_thread_err = g_err;
+    }
+    --p->deferred_pending;
+    p->cv_issued.notify_all();
+  }
+}
+
+int32_t wait_issued(kv_pool* p, const OpRef& op) {
+  if (op && !op->issued) p->cv_issued.wait(p->mu, [&] { return op->issued; });
+  if (p->copy_thread_rc) {
+    g_err = p->copy_thread_err;
+    return p->copy_thread_rc;
+  }
+  return KV_OK;
+}
+
+int32_t wait_all_issued(kv_pool* p) {
+  if (p->deferred_pending > 0) p->cv_issued.wait(p->mu, [&] { return p->deferred_pending == 0; });
+  if (p->copy_thread_rc) {
+    g_err = p->copy_thread_err;
+    return p->copy_thread_rc;
+  }
+  return KV_OK;
+}
+
+void stop_copy_thread(kv_pool* p, std::unique_lock<std::mutex>& lk) {
+  (void)wait_all_issued(p);
+  if (!p->copy_thread.joinable()) return;
+  p->copy_thread_stop = true;
+  p->cv_job.notify_all();
+  lk.unlock();
+  p->copy_thread.join();
+  lk.lock();
+}
+
 // Swap-out of a move list: gather pieces into the staging ring, then drain them to the host.
 // pre: events the first gather must wait for.
 int32_t enqueue_out(kv_pool* p, const std::vector<Move>& mv, const std::vector<hipEvent_t>& pre,
@@ -333,6 +418,7 @@ int32_t enqueue_out(kv_pool* p, const std::vector<Move>& mv, const std::vector<h
   const int64_t m = (int64_t)mv.size();
   struct Pending {
     int64_t first, count, off;
+    hipEvent_t ready;  // held-back copies only: recorded behind this piece's gathers
   };
   std::vector<Pending> pending;  // gathered, copies not issued yet
   auto flush = [&]() -> int32_t {
@@ -343,17 +429,12 @@ int32_t enqueue_out(kv_pool* p, const std::vector<Move>& mv, const std::vector<h
     if (ready) op->aux.push_back(ready);
     if ((rc2 = record(p, ready, p->s_pack))) return rc2;
     if ((rc2 = stream_wait(p, p->s_d2h, ready))) return rc2;
-    for (const Pending& q : pending) {
-      if ((rc2 = issue_copies(p, true, at(r.base, q.off), &mv[(size_t)q.first], q.count))) return rc2;
-      for (Region& g : r.live)
-        if (g.off == q.off && g.op_seq == op->seq && !g.recorded) {
-          if ((rc2 = record(p, g.freed, p->s_d2h))) return rc2;
-          g.recorded = true;
-        }
-    }
+    for (const Pending& q : pending)
+      if ((rc2 = drain_piece(p, r, op->seq, mv.data(), q.first, q.count, q.off))) return rc2;
     pending.clear();
     return KV_OK;
   };
+  const bool defer = p->defer_copies && !p->plan && m * p->R >= p->defer_min;
   for (int64_t i = 0; i < m; i += r.piece_blocks) {
     const int64_t mp = std::min(r.piece_blocks, m - i);
     Region* g;
@@ -363,17 +444,37 @@ int32_t enqueue_out(kv_pool* p, const std::vector<Move>& mv, const std::vector<h
       int64_t ml = std::min<int64_t>(p->launch_blocks, mp - k);
       if ((rc = launch_pack(p, false, at(r.base, off + k * p->R), &mv[(size_t)(i + k)], ml))) return rc;
     }
-    pending.push_back({i, mp, off});
+    hipEvent_t piece_ready = nullptr;
+    if (defer) {
+      if ((rc = get_event(p, &piece_ready))) return rc;
+      op->aux.push_back(piece_ready);
+      if ((rc = record(p, piece_ready, p->s_pack))) return rc;
+    }
+    pending.push_back({i, mp, off, piece_ready});
     // gathers and copies on streams of their own: a piece's copies start as soon as its gather is
-    // done, and the following gathers run under them
-    if (p->s_pack != p->s_d2h && (rc = flush())) return rc;
+    // done, and the following gathers run under them (held-back copies: the copy thread does that)
+    if (!defer && p->s_pack != p->s_d2h && (rc = flush())) return rc;
   }
   if ((rc = record(p, op->packed, p->s_pack))) return rc;
+  p->st.bytes_out += m * p->R;
+  p->st.blocks_out += m;
+  if (defer && !pending.empty()) {
+    // the copies, the regions' release and the completion event are the copy thread's to enqueue,
+    // piece by piece, once the host has seen each piece's gathers finish
+    DeferredOut job;
+    job.op = op;
+    job.mv = mv;
+    for (const Pending& q : pending) job.pieces.push_back({q.first, q.count, q.off, q.ready});
+    op->deferred = true;
+    p->jobs.push_back(std::move(job));
+    ++p->deferred_pending;
+    if (!p->copy_thread.joinable()) p->copy_thread = std::thread(copy_thread_main, p);
+    p->cv_job.notify_one();
+    return KV_OK;
+  }
   if ((rc = flush())) return rc;
   if (m == 0 && (rc = stream_wait(p, p->s_d2h, op->packed))) return rc;
   if ((rc = record(p, op->done, p->s_d2h))) return rc;
-  p->st.bytes_out += m * p->R;
-  p->st.blocks_out += m;
   return KV_OK;
 }
 

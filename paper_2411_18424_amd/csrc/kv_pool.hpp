@@ -7,10 +7,12 @@
 #include <string.h>
 
 #include <chrono>
+#include <condition_variable>
 #include <deque>
 #include <memory>
 #include <mutex>
 #include <string>
+#include <thread>
 #include <unordered_map>
 #include <vector>
 
@@ -41,6 +43,9 @@ struct Op {
   bool issued = false;          // every event of the op has been recorded (or the enqueue has failed);
                                 // until then completion polling must not look at them: a query of an
                                 // event that was never recorded, or was recycled, reports success
+  bool packed_recorded = false; // `packed` has been recorded (a swap-out whose copies are held back
+                                // has its gathers enqueued and this set long before `issued`)
+  bool deferred = false;        // the copy thread finishes the enqueue and sets `issued`
   std::vector<hipEvent_t> aux;  // hand-off events of this op, recycled when it is done
   std::vector<hipEvent_t> layer_ev;  // layer-wise swap-in: one per step of layer_step layers (null
                                      // entries in a plan-only pool); recycled when the op is done
@@ -110,6 +115,20 @@ struct CopyDesc {
 constexpr int64_t KV_MAX_COPY_PITCH = 1ll << 30;      // largest host pitch of a 2-D copy (measured up to here)
 constexpr int64_t KV_MAX_STRIDED_WIDTH = 16ll << 20;  // widest row of a 2-D copy (measured up to here)
 
+// A swap-out whose copies are held back until its gathers have finished (the default for swap-outs of defer_min_bytes or more):
+// the pieces already gathered into the staging ring, each with the event recorded behind its
+// gathers.  The pool's copy thread waits for each event on the host and only then hands the
+// piece's copies to the runtime.
+struct DeferredPiece {
+  int64_t first, count, off;  // moves [first, first + count) lie at ring offset off
+  hipEvent_t ready;
+};
+struct DeferredOut {
+  OpRef op;
+  std::vector<Move> mv;
+  std::vector<DeferredPiece> pieces;
+};
+
 struct ProfRec {
   int32_t kind;
   int64_t bytes;
@@ -164,6 +183,9 @@ struct kv_pool {
   int unroll = 0, grid = 0, variant = 0;
   int64_t launch_blocks = KV_MAX_LAUNCH_BLOCKS;  // most blocks one pack launch carries
   int64_t copy_chunk = 0;
+  bool defer_copies = true;   // off with KV_FLAG_NO_DEFER_COPIES
+  int64_t defer_min = 0;      // smallest swap-out (bytes) whose copies are held back
+  int device = 0;             // the device that was current when the pool was created
   bool strided_copies = true;  // equal runs a constant stride apart go out as rows of one 2-D copy
   int64_t slack = 32;
 
@@ -185,6 +207,14 @@ struct kv_pool {
   std::vector<hipEvent_t> timing_pool;  // timing enabled
   std::vector<kvi::ProfRec> prof;
   kv_stats_t st{};
+  // swap-outs whose copies are held back, in issue order, and the thread that releases them
+  std::deque<kvi::DeferredOut> jobs;
+  int deferred_pending = 0;  // jobs queued or in the copy thread's hands
+  std::condition_variable_any cv_job, cv_issued;  // waited for with `mu` held
+  std::thread copy_thread;
+  bool copy_thread_stop = false;
+  int32_t copy_thread_rc = 0;  // first error of the copy thread, reported by the calls that wait for its work
+  std::string copy_thread_err;
   // completion test of an event (hipEventQuery); a host-only unit test substitutes its own
   hipError_t (*event_query)(hipEvent_t) = hipEventQuery;
 };
@@ -198,6 +228,9 @@ void put_event(kv_pool* p, hipEvent_t ev);
 void reap(kv_pool* p);
 Op* find_op(std::deque<OpRef>& dq, uint64_t seq);
 int32_t host_wait_op(kv_pool* p, const OpRef& op);
+int32_t wait_issued(kv_pool* p, const OpRef& op);  // lock held; returns once the op's events are all recorded
+int32_t wait_all_issued(kv_pool* p);               // the same for every swap-out handed to the copy thread
+void stop_copy_thread(kv_pool* p, std::unique_lock<std::mutex>& lk);
 int32_t new_op(kv_pool* p, bool is_out, OpRef* out);
 void order_for_strided_copies(kv_pool* p, std::vector<Move>& mv);
 void plan_copies(const Move* mv, int64_t m, int64_t R, int64_t copy_chunk, bool strided, std::vector<CopyDesc>* out);

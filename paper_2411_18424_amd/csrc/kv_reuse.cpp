@@ -137,8 +137,11 @@ bool arena_evict(kv_pool* p, int64_t need, int32_t prio, const std::vector<int64
 
 
 int32_t do_swap_out(kv_pool* p, std::vector<OutItem>& items, int32_t* out_n_moved, int direct) {
-  reap(p);
   int32_t rc;
+  // one swap-out at a time may have its copies held back: its ring regions are still open and
+  // the host arena must not be rearranged under copies that have not been enqueued yet
+  if ((rc = wait_all_issued(p))) return rc;
+  reap(p);
   // 1. validate tables (ids unique across the whole call) and shapes
   ++p->epoch;
   for (size_t a = 0; a < items.size(); ++a) {
@@ -290,15 +293,25 @@ int32_t do_swap_out(kv_pool* p, std::vector<OutItem>& items, int32_t* out_n_move
     order_for_strided_copies(p, mv);
     rc = enqueue_out(p, mv, pre, op);
   }
-  op->issued = true;  // also after a failed enqueue, so that polling does not stop here for ever
+  op->packed_recorded = true;
+  if (!op->deferred) op->issued = true;  // also after a failed enqueue, so that polling does not stop here for ever
   return rc;
 }
 
 
 int32_t do_swap_in(kv_pool* p, std::vector<InItem>& items, int32_t* out_n_moved, int direct,
                    int32_t layer_step) {
-  reap(p);
   int32_t rc;
+  // a swap-in follows its request's last op through that op's completion event: if the op is a
+  // swap-out whose copies are still held back, the event does not exist on the device yet.
+  // Swap-ins of other requests go ahead - that is what holding the copies back is for.
+  for (const InItem& it : items) {
+    auto f = p->reqs.find(it.req);
+    if (f == p->reqs.end() || !f->second.last) continue;
+    const OpRef last = f->second.last;  // the lock is dropped during the wait
+    if ((rc = wait_issued(p, last))) return rc;
+  }
+  reap(p);
   ++p->epoch;
   for (size_t a = 0; a < items.size(); ++a) {
     InItem& it = items[a];

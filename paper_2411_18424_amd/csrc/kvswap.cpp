@@ -41,6 +41,10 @@ using namespace kvi;
 namespace {
 
 void destroy_pool(kv_pool* p) {
+  {
+    std::unique_lock<std::mutex> lk(p->mu);
+    stop_copy_thread(p, lk);  // after it has enqueued what it holds
+  }
   if (!p->plan) {
     // wait for the library's own streams only: the caller's streams are none of its business
     for (hipStream_t s : {p->s_pack, p->s_d2h, p->s_h2d, p->s_scat, p->s_d2h2})
@@ -98,6 +102,7 @@ int32_t kv_pool_create(const kv_pool_config_t* cfg, kv_pool_t** out) {
       cfg->max_piece_bytes < 0 || cfg->copy_chunk_bytes < 0)
     return fail(KV_EINVAL, "negative size");
   if (cfg->mapped_out_max_blocks < 0) return fail(KV_EINVAL, "negative mapped_out_max_blocks");
+  if (cfg->defer_min_bytes < 0) return fail(KV_EINVAL, "negative defer_min_bytes");
 
   kv_pool* p = new kv_pool();
   p->cfg = *cfg;
@@ -120,6 +125,8 @@ int32_t kv_pool_create(const kv_pool_config_t* cfg, kv_pool_t** out) {
   p->mapped_out = (cfg->flags & KV_FLAG_MAPPED_SWAP_OUT) != 0;
   p->mapped_out_max = cfg->mapped_out_max_blocks;
   p->strided_copies = (cfg->flags & KV_FLAG_NO_STRIDED_COPIES) == 0;
+  p->defer_copies = (cfg->flags & KV_FLAG_NO_DEFER_COPIES) == 0;
+  p->defer_min = cfg->defer_min_bytes > 0 ? cfg->defer_min_bytes : (16ll << 20);
   if (cfg->mapped_in_grid > 0) p->mapped_grid = cfg->mapped_in_grid;
   p->launch_blocks = kv_max_launch_blocks((uint32_t)C, (uint32_t)p->P, p->unroll, p->variant);
   // staging rings: defaults scale with the pool, capped at 4 GiB (out) and 1 GiB (in)
@@ -173,6 +180,7 @@ int32_t kv_pool_create(const kv_pool_config_t* cfg, kv_pool_t** out) {
   } while (0)
 
   if (!plan) {
+    TRY_OR_BAIL(hipGetDevice(&p->device));
     if (p->grid <= 0) {
       int dev = 0, cus = 256;
       TRY_OR_BAIL(hipGetDevice(&dev));
@@ -536,6 +544,8 @@ int32_t kv_wait(kv_pool_t* p, int64_t req) {
   if (f == p->reqs.end()) return fail(KV_ENOENT, "unknown request %lld", (long long)req);
   OpRef op = f->second.last;
   if (!op || op->all_done) return KV_OK;
+  int32_t rc = wait_issued(p, op);
+  if (rc) return rc;
   return wait_event_unlocked(p, lk, op->done);
 }
 
@@ -566,8 +576,11 @@ int32_t kv_stream_wait(kv_pool_t* p, int64_t req, void* stream) {
   auto f = p->reqs.find(req);
   if (f == p->reqs.end()) return fail(KV_ENOENT, "unknown request %lld", (long long)req);
   reap(p);
-  const OpRef& op = f->second.last;
+  const OpRef op = f->second.last;
   if (!op || op->all_done || p->plan) return KV_OK;
+  int32_t rc = wait_issued(p, op);  // the event must have been recorded before a stream can wait for it
+  if (rc) return rc;
+  if (op->all_done) return KV_OK;
   HIP_TRY(hipStreamWaitEvent((hipStream_t)stream, op->done, 0));
   return KV_OK;
 }
@@ -580,8 +593,11 @@ static int32_t layer_event(kv_pool* p, int64_t req, int32_t layer, hipEvent_t* e
   auto f = p->reqs.find(req);
   if (f == p->reqs.end()) return fail(KV_ENOENT, "unknown request %lld", (long long)req);
   reap(p);
-  const OpRef& op = f->second.last;
+  const OpRef op = f->second.last;
   if (!op || op->all_done || p->plan) return KV_OK;
+  int32_t rc = wait_issued(p, op);
+  if (rc) return rc;
+  if (op->all_done) return KV_OK;
   if (op->layer_step > 0 && !op->layer_ev.empty())
     *ev = op->layer_ev[(size_t)(layer / op->layer_step)];
   else
@@ -617,6 +633,8 @@ int32_t kv_wait_layer(kv_pool_t* p, int64_t req, int32_t layer) {
 int32_t kv_wait_all(kv_pool_t* p) {
   if (!p) return fail(KV_EINVAL, "null pool");
   std::unique_lock<std::mutex> lk(p->mu);
+  int32_t rc = wait_all_issued(p);
+  if (rc) return rc;
   if (!p->plan) {
     // wait without the lock: other threads may keep enqueueing (their work is not waited for)
     const hipStream_t streams[4] = {p->s_pack, p->s_d2h, p->s_h2d, p->s_scat};
@@ -664,7 +682,8 @@ int32_t kv_host_read(kv_pool_t* p, int64_t req, int32_t first_block, int32_t n_b
   if (p->plan) return fail(KV_ENODEV, "a plan-only pool holds no bytes");
   OpRef op = f->second.last;
   if (op && !op->all_done) {
-    int32_t rc = wait_event_unlocked(p, lk, op->done);
+    int32_t rc = wait_issued(p, op);
+    if (!rc) rc = wait_event_unlocked(p, lk, op->done);
     if (rc) return rc;
     f = p->reqs.find(req);  // the lock was dropped meanwhile
     if (f == p->reqs.end() || !f->second.has_image || (int64_t)first_block + n_blocks > f->second.img.n)
@@ -740,9 +759,11 @@ int32_t kv_host_set_priority(kv_pool_t* p, int64_t req, int32_t priority) {
 int32_t kv_host_release(kv_pool_t* p, int64_t req) {
   if (!p) return fail(KV_EINVAL, "null pool");
   std::lock_guard<std::mutex> g(p->mu);
+  int32_t rc = wait_all_issued(p);  // before the lookup: the lock is dropped during this wait
+  if (rc) return rc;
   auto f = p->reqs.find(req);
   if (f == p->reqs.end() || !f->second.has_image) return fail(KV_ENOENT, "request %lld has no host copy", (long long)req);
-  int32_t rc = host_wait_op(p, f->second.last);
+  rc = host_wait_op(p, f->second.last);
   if (rc) return rc;
   arena_give(p, f->second.img.ext);
   p->reqs.erase(f);
@@ -768,6 +789,8 @@ int32_t kv_profile_read(kv_pool_t* p, kv_prof_record_t* out, int32_t cap, int32_
   if (!p || !out_n) return fail(KV_EINVAL, "null argument");
   std::lock_guard<std::mutex> g(p->mu);
   if (!p->profile) return fail(KV_EINVAL, "pool was not created with KV_FLAG_PROFILE");
+  int32_t rc = wait_all_issued(p);
+  if (rc) return rc;
   for (hipStream_t s : {p->s_pack, p->s_d2h, p->s_h2d, p->s_scat}) HIP_TRY(hipStreamSynchronize(s));
   *out_n = (int32_t)p->prof.size();
   for (int32_t i = 0; i < cap && i < *out_n; ++i) {
@@ -788,6 +811,8 @@ int32_t kv_profile_reset(kv_pool_t* p) {
   if (!p) return fail(KV_EINVAL, "null pool");
   std::lock_guard<std::mutex> g(p->mu);
   if (!p->profile) return KV_OK;
+  int32_t rc = wait_all_issued(p);
+  if (rc) return rc;
   for (hipStream_t s : {p->s_pack, p->s_d2h, p->s_h2d, p->s_scat}) HIP_TRY(hipStreamSynchronize(s));
   for (auto& r : p->prof) {
     p->timing_pool.push_back(r.start);

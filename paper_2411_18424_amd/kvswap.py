@@ -22,6 +22,7 @@ KV_ENOENT, KV_EBUSY, KV_EHIP, KV_ENODEV = -4, -5, -6, -7
 KV_FLAG_PLAN_ONLY, KV_FLAG_PROFILE, KV_FLAG_ORDER_COMPUTE, KV_FLAG_FOUR_STREAMS = 1, 2, 4, 8
 KV_FLAG_MAPPED_SWAP_IN, KV_FLAG_HOST_EVICT, KV_FLAG_MAPPED_SWAP_OUT, KV_FLAG_SCATTER_STREAM = 16, 32, 64, 128
 KV_FLAG_NO_STRIDED_COPIES = 256
+KV_FLAG_NO_DEFER_COPIES = 512
 KV_TASK_SWAP_OUT, KV_TASK_SWAP_IN, KV_TASK_SWAP_OUT_DELTA, KV_TASK_SWAP_IN_DELTA = 0, 1, 2, 3
 KV_WHERE_RUNNING, KV_WHERE_SWAPPED, KV_WHERE_ONGOING_SWAP_IN = 0, 1, 2
 KV_IT_FREE_OUT_BLOCKS = 1
@@ -47,6 +48,7 @@ class kv_pool_config_t(C.Structure):
         ("host_slack_blocks", C.c_int32), ("gather_grid", C.c_int32),
         ("tile_unroll", C.c_int32), ("pack_variant", C.c_int32),
         ("mapped_in_grid", C.c_int32), ("mapped_out_max_blocks", C.c_int32),
+        ("defer_min_bytes", C.c_int64),
     ]
 
 
@@ -217,7 +219,7 @@ class KVPool:
                  max_piece_bytes=0,
                  host_slack_blocks=-1, copy_chunk_bytes=0, compute_stream=0, flags=0,
                  gather_grid=0, tile_unroll=0, pack_variant=0, mapped_in_grid=0,
-                 mapped_out_max_blocks=0):
+                 mapped_out_max_blocks=0, defer_min_bytes=0):
         cfg = kv_pool_config_t(
             n_layers=n_layers, n_kv_heads=n_kv_heads, head_dim=head_dim, block_size=block_size,
             elt_bytes=elt_bytes, flags=flags, n_gpu_blocks=n_gpu_blocks, gpu_base=gpu_base or None,
@@ -226,7 +228,8 @@ class KVPool:
             max_piece_bytes=max_piece_bytes, copy_chunk_bytes=copy_chunk_bytes,
             compute_stream=compute_stream or None, host_slack_blocks=host_slack_blocks,
             gather_grid=gather_grid, tile_unroll=tile_unroll, pack_variant=pack_variant,
-            mapped_in_grid=mapped_in_grid, mapped_out_max_blocks=mapped_out_max_blocks)
+            mapped_in_grid=mapped_in_grid, mapped_out_max_blocks=mapped_out_max_blocks,
+            defer_min_bytes=defer_min_bytes)
         self._h = C.c_void_p()
         _check(lib.kv_pool_create(C.byref(cfg), C.byref(self._h)))
         self.P = 2 * n_layers

@@ -66,9 +66,19 @@ int main() {
   // an issued op behind an unissued one is not overtaken (ops finish in issue order)
   kvi::OpRef out2;
   EXPECT(kvi::new_op(&p, true, &out2) == KV_OK);
-  out2->issued = true;
+  out2->issued = out2->packed_recorded = true;
   kvi::reap(&p);
   EXPECT(!out2->packed_done && p.pack_done_seq == 0 && p.ops_out.size() == 2);
+
+  // a swap-out whose copies are held back: its gathers are enqueued and their event recorded, its
+  // completion event is not.  The gather counts as finished (the blocks it read are released, and
+  // so is the gather of the op behind it), completion does not, and no event is recycled.
+  out->packed_recorded = true;
+  kvi::reap(&p);
+  EXPECT(out->packed_done && !out->all_done && out2->packed_done && !out2->all_done);
+  EXPECT(p.pack_done_seq == 2 && p.ops_out.size() == 2);
+  EXPECT(out->packed != nullptr && out->done != nullptr);
+  EXPECT(p.alloc.n_draining() == 0 && p.alloc.n_free() == 3);
 
   // once issued, everything is harvested in order
   out->issued = true;

@@ -348,6 +348,9 @@ def test_mapped_swap_out_takes_small_moved_sets_only(kv):
     with pytest.raises(kv.KVError) as ei:
         plan_pool(kv, shape, mapped_out_max_blocks=-1)
     assert ei.value.status == kv.KV_EINVAL
+    with pytest.raises(kv.KVError) as ei:
+        plan_pool(kv, shape, defer_min_bytes=-1)
+    assert ei.value.status == kv.KV_EINVAL
 
 
 def test_host_images_grow_by_extents_and_give_everything_back(kv):

@@ -464,6 +464,57 @@ def test_full_swap_out_of_a_grown_request_while_its_swap_in_is_in_flight(harness
         t2 = perm[700:1000]
 
 
+@pytest.mark.parametrize("flags", [0, 8, 128], ids=["two_streams", "four_streams", "three_streams"])
+def test_swap_out_copies_held_back_until_the_gathers_are_done(harness, flags):
+    """A swap-out of 16 MiB or more returns with its gathers enqueued and its copies in the
+    hands of the pool's copy thread.  Whatever is called next - a swap-in of another request, a
+    swap-in of the same request, a stream wait, a host read, another swap-out, the release of
+    the image - must see the same bytes as with KV_FLAG_NO_DEFER_COPIES, and completion is not reported
+    before the copies have run."""
+    import torch
+    shape = synth.KVShape("s", 8, 8, 128, 16, 2, 1024, "bf16")  # R = 512 KiB
+    h = harness(shape, cfg=37, host_bytes=700 * MiB, fill="random", flags=flags,
+                staging_out_bytes=96 * MiB, max_piece_bytes=16 * MiB)
+    rng = synth.rng_for(37)
+    perm = rng.permutation(1024).astype(np.int32)
+    ta, tb, tc, td = perm[:300], perm[300:500], perm[500:800], perm[800:1000]
+    h.pool.swap_out(2, tb)
+    h.oracle.swap_out(2, tb)
+    h.pool.kv_wait(2)
+    side = torch.cuda.Stream()
+    for rep in range(3):
+        # request 1 leaves (150 MiB: larger than the out ring, so the call also drains pieces itself),
+        # request 2 comes back into other blocks at once, then request 1 follows it back in
+        h.pool.swap_out(1, ta)
+        done_at_once = h.pool.kv_query(1)
+        h.pool.swap_in(2, td)
+        h.oracle.swap_out(1, ta)
+        h.oracle.swap_in(2, td)
+        assert not done_at_once  # 150 MiB take 2.6 ms on the link
+        if rep == 0:
+            h.pool.kv_stream_wait(1, side.cuda_stream)   # needs the completion event to exist
+            side.synchronize()
+            assert h.pool.kv_query(1)
+        elif rep == 1:
+            h.assert_image_equal(1)                      # a host read right behind the call
+        h.pool.swap_in(1, tc)                            # follows the swap-out of the same request
+        h.oracle.swap_in(1, tc)
+        h.pool.swap_out(2, td)                           # the next swap-out waits for the hand-over
+        h.oracle.swap_out(2, td)
+        h.pool.kv_wait(1)
+        h.pool.kv_wait(2)
+        h.assert_pool_equal()
+        h.assert_image_equal(1)
+        h.assert_image_equal(2)
+        ta, tc = tc, ta
+        tb, td = td, tb
+    st = h.pool.kv_stats()
+    assert st["blocks_out"] == 200 + 3 * 500 and st["blocks_in"] == 3 * 500
+    h.pool.swap_out(1, ta)
+    h.pool.kv_host_release(1)   # gives the image back: only after the held-back copies have run
+    h.pool.swap_out(2, tb)      # and the pool is destroyed (by the fixture) with a swap-out just handed over
+
+
 def test_a_c_caller_reads_host_images_in_the_contract_layout():
     """tests/host/host_read_check.cpp (built by paper_2411_18424_amd.build): kv_host_read and
     kv_host_view from a C++ program, including an image that continues in a second extent."""

@@ -18,6 +18,7 @@ SHAPE = synth.KVShape("stream", 2, 2, 64, 16, 2, 512, "fp16")  # C = 4 KiB, R = 
 BIG = synth.KVShape("stream_big", 8, 8, 128, 16, 2, 4096, "bf16")
 
 ORDER_COMPUTE, FOUR_STREAMS, MAPPED_SWAP_IN, MAPPED_SWAP_OUT, SCATTER_STREAM = 4, 8, 16, 64, 128
+NO_DEFER_COPIES = 512
 
 
 class Loop:
@@ -345,6 +346,12 @@ CASES = {
     "mapped_small_swap_outs": (106, ORDER_COMPUTE | MAPPED_SWAP_OUT, dict(mapped_out_max_blocks=12,
                                                                            host_slack_blocks=4)),
     "tight_host_arena": (105, ORDER_COMPUTE, dict(host_slack_blocks=2)),
+    # every swap-out's copies enqueued by the pool's copy thread once its gathers have finished (the default does
+    # that for swap-outs of 16 MiB or more only, which this small shape never reaches)
+    "deferred_copies_two_streams": (108, ORDER_COMPUTE, dict(staging_out_bytes=1 * MiB, staging_in_bytes=512 * KiB,
+                                                             max_piece_bytes=128 * KiB, defer_min_bytes=1)),
+    "deferred_copies_three_streams": (109, ORDER_COMPUTE | SCATTER_STREAM, dict(host_slack_blocks=4, defer_min_bytes=1)),
+    "deferred_copies_tight_host_arena": (110, ORDER_COMPUTE, dict(host_slack_blocks=2, defer_min_bytes=1)),
 }
 
 
@@ -353,14 +360,14 @@ def test_random_serving_loop_matches_oracle(case):
     import torch
     from gpu_util import Harness
     seed, flags, kw = CASES[case]
-    host_bytes = 2 * MiB if case == "tight_host_arena" else 64 * MiB
+    host_bytes = 2 * MiB if case.endswith("tight_host_arena") else 64 * MiB
     stream = torch.cuda.Stream()
     h = Harness(SHAPE, seed, host_bytes, fill="random", flags=flags,
                 compute_stream=stream.cuda_stream, **kw)
     try:
         rng = synth.rng_for(seed)
         loop = Loop(h, stream, rng, n_req=14)
-        loop.tight = case == "tight_host_arena"
+        loop.tight = case.endswith("tight_host_arena")
         for i in range(1500):
             loop.step()
             if i % 150 == 149:
@@ -380,6 +387,11 @@ BIG_CASES = {
     "three_streams": (204, ORDER_COMPUTE | SCATTER_STREAM, dict(staging_out_bytes=128 * MiB, staging_in_bytes=32 * MiB,
                                                              max_piece_bytes=8 * MiB)),
     "mapped_both_ways": (203, ORDER_COMPUTE | MAPPED_SWAP_IN | MAPPED_SWAP_OUT, dict(mapped_out_max_blocks=64)),
+    # the cases above hold back the copies of swap-outs of 16 MiB or more (the default); these hold back all, or none
+    "all_copies_held_back_small_rings": (205, ORDER_COMPUTE, dict(staging_out_bytes=48 * MiB, staging_in_bytes=24 * MiB,
+                                                                 max_piece_bytes=8 * MiB, defer_min_bytes=1)),
+    "no_copies_held_back_three_streams": (206, ORDER_COMPUTE | SCATTER_STREAM | NO_DEFER_COPIES,
+                                          dict(staging_out_bytes=128 * MiB, staging_in_bytes=32 * MiB)),
 }
 
 
