@@ -230,11 +230,14 @@ int32_t swap_out_static(kv_pool_t* pool, const int32_t* block_table, int32_t n_b
                         void* stream);
 
 /* Section 3.2 swap-in path.  Copies the host image into new_block_table's blocks.  The
- * image is kept (Section 3.3).  Note: any order of calls is correct; when one scheduling step
- * both resumes and preempts, the resumed request is back soonest if its swap-in is issued
- * before the step's swap-out (Algorithm 1's order, which kv_manager_iterate follows), because
- * calls reach the copy engines in call order.  KV_ENOENT: no image, or a needed block's host copy is not
- * valid.  KV_EINVAL: n_blocks differs from the image, bad ids. */
+ * image is kept (Section 3.3).  Note: any order of calls is correct, and when one scheduling step
+ * both resumes and preempts, the resumed request is back equally soon whether its swap-in is issued
+ * before or after the step's swap-out - except in a KV_FLAG_NO_DEFER_COPIES pool, where calls reach the
+ * copy engines in call order and the swap-in should go first (Algorithm 1's order, which
+ * kv_manager_iterate follows in any case).  A swap-in of a request whose swap-out has just been issued
+ * first waits, on the host, until that swap-out's copies have been enqueued.
+ * KV_ENOENT: no image, or a needed block's host copy is not valid.  KV_EINVAL: n_blocks differs from
+ * the image, bad ids. */
 int32_t swap_in(kv_pool_t* pool, int64_t req, const int32_t* new_block_table, int32_t n_blocks);
 /* As swap_in, but logical blocks with resident_mask[j] != 0 are already on the GPU and are
  * skipped (only non-resident blocks move). */
