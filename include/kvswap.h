@@ -98,8 +98,9 @@ typedef enum {
                                        issue the swap-in first.  With the copies held back the order of the two
                                        calls does not matter.  The swap-out call returns when its gathers are
                                        enqueued, as always; kv_query reports it unfinished and the waits block
-                                       until the copies are done; the next swap-out, and a swap-in of the same
-                                       request, first wait on the host for the hand-over.  Costs a few
+                                       until the copies are done; a swap-in or swap-out of the same request,
+                                       and a swap-out that does not fit the out ring beside the held-back ones,
+                                       first wait on the host for the hand-over.  Costs a few
                                        microseconds per swap-out. */
 #define KV_FLAG_NO_STRIDED_COPIES 256u /* one copy per run of adjacent host records, never a 2-D copy over
                                        several equal runs a constant stride apart (for comparison) */

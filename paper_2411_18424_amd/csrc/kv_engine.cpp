@@ -396,6 +396,21 @@ int32_t wait_all_issued(kv_pool* p) {
   return KV_OK;
 }
 
+// Bytes of the out ring that a new swap-out can claim before its claims would have to evict a
+// region whose copies have not been enqueued yet (regions are claimed and retired in ring
+// order, so those are the newest ones).  A piece that does not fit before the end of the ring
+// skips the tail: one piece is held in reserve for that.
+int64_t out_ring_room(kv_pool* p) {
+  const ByteRing& r = p->ring_out;
+  const int64_t piece = r.piece_blocks * p->R;
+  for (const Region& g : r.live) {
+    if (g.recorded) continue;
+    const int64_t ahead = g.off >= r.head ? g.off - r.head : r.cap - r.head + g.off;
+    return std::max<int64_t>(0, ahead - piece);
+  }
+  return r.cap - piece;
+}
+
 void stop_copy_thread(kv_pool* p, std::unique_lock<std::mutex>& lk) {
   (void)wait_all_issued(p);
   if (!p->copy_thread.joinable()) return;

@@ -230,6 +230,7 @@ Op* find_op(std::deque<OpRef>& dq, uint64_t seq);
 int32_t host_wait_op(kv_pool* p, const OpRef& op);
 int32_t wait_issued(kv_pool* p, const OpRef& op);  // lock held; returns once the op's events are all recorded
 int32_t wait_all_issued(kv_pool* p);               // the same for every swap-out handed to the copy thread
+int64_t out_ring_room(kv_pool* p);                 // bytes a swap-out can claim without reaching a held-back one's regions
 void stop_copy_thread(kv_pool* p, std::unique_lock<std::mutex>& lk);
 int32_t new_op(kv_pool* p, bool is_out, OpRef* out);
 void order_for_strided_copies(kv_pool* p, std::vector<Move>& mv);

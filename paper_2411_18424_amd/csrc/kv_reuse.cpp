@@ -138,9 +138,24 @@ bool arena_evict(kv_pool* p, int64_t need, int32_t prio, const std::vector<int64
 
 int32_t do_swap_out(kv_pool* p, std::vector<OutItem>& items, int32_t* out_n_moved, int direct) {
   int32_t rc;
-  // one swap-out at a time may have its copies held back: its ring regions are still open and
-  // the host arena must not be rearranged under copies that have not been enqueued yet
-  if ((rc = wait_all_issued(p))) return rc;
+  // Swap-outs whose copies are still held back keep their regions of the out ring open, and their
+  // completion events do not exist on the device yet.  This call may be enqueued behind them if
+  // it follows none of them on its own requests and fits the ring without reaching their regions;
+  // otherwise it waits, on the host, for their hand-over.
+  if (p->deferred_pending > 0) {
+    int64_t need = 0;
+    bool own = false;
+    for (const OutItem& it : items) {
+      need += std::max<int64_t>(it.n, 0) * p->R;
+      auto f = p->reqs.find(it.req);
+      own |= f != p->reqs.end() && f->second.last && !f->second.last->issued;
+    }
+    if (own || need > out_ring_room(p)) {
+      if ((rc = wait_all_issued(p))) return rc;
+    } else if (p->copy_thread_rc) {
+      return wait_all_issued(p);  // reports the copy thread's error
+    }
+  }
   reap(p);
   // 1. validate tables (ids unique across the whole call) and shapes
   ++p->epoch;

@@ -515,6 +515,49 @@ def test_swap_out_copies_held_back_until_the_gathers_are_done(harness, flags):
     h.pool.swap_out(2, tb)      # and the pool is destroyed (by the fixture) with a swap-out just handed over
 
 
+def test_several_swap_outs_held_back_at_once(harness):
+    """Swap-outs of different requests issued back to back: each is enqueued behind the ones whose
+    copies are still held back as long as the out ring has room for it, and waits for their
+    hand-over when it has not; a small swap-out (copies enqueued inside the call) overtakes them,
+    and so does another request's swap-in."""
+    shape = synth.KVShape("s", 8, 8, 128, 16, 2, 1024, "bf16")  # R = 512 KiB, out ring 128 MiB
+    h = harness(shape, cfg=38, host_bytes=600 * MiB, fill="random")
+    rng = synth.rng_for(38)
+    perm = rng.permutation(1024).astype(np.int32)
+    tabs = [perm[i * 44:(i + 1) * 44] for i in range(8)]           # 22 MiB each: held back
+    spare = [perm[500 + i * 44:500 + (i + 1) * 44] for i in range(8)]
+    small = perm[400:404]                                           # 2 MiB: not held back
+    here, there = perm[900:944], perm[950:994]
+    h.pool.swap_out(100, here)
+    h.oracle.swap_out(100, here)
+    h.pool.kv_wait(100)
+    for rep in range(2):
+        for r in range(8):                     # 176 MiB in all: the later calls wait for ring room
+            h.pool.swap_out(r, tabs[r])
+            h.oracle.swap_out(r, tabs[r])
+            if r == 2:
+                h.pool.swap_out(50, small)
+                h.oracle.swap_out(50, small)
+            if r == 4:
+                h.pool.swap_in(100, there)     # another request's swap-in goes ahead
+                h.oracle.swap_in(100, there)
+        h.pool.kv_wait_all()
+        for r in list(range(8)) + [50, 100]:
+            assert h.pool.kv_query(r)
+            h.assert_image_equal(r)
+        h.assert_pool_equal()
+        for r in range(8):                     # and back, into other blocks
+            h.pool.swap_in(r, spare[r])
+            h.oracle.swap_in(r, spare[r])
+        h.pool.swap_out(100, there)
+        h.oracle.swap_out(100, there)
+        h.pool.kv_wait_all()
+        h.assert_pool_equal()
+        h.assert_image_equal(100)
+        tabs, spare = spare, tabs
+        here, there = there, here
+
+
 def test_a_c_caller_reads_host_images_in_the_contract_layout():
     """tests/host/host_read_check.cpp (built by paper_2411_18424_amd.build): kv_host_read and
     kv_host_view from a C++ program, including an image that continues in a second extent."""
