@@ -533,6 +533,8 @@ def main() -> int:
         "device_state": dev_state,
         "settle": settled,
         "streams": 4 if args.four_streams else 3 if args.scatter_stream else 2,
+        "swap_out_copies": "enqueued inside the call" if args.no_defer_copies
+                           else "held back until their gathers are done (copy thread)",
         "pack_variant": int(os.environ.get("KVSWAP_PACK_VARIANT", "0")),  # development aid; 0 = the default kernels
         "swap_in_path": "mapped host reads" if args.mapped_swap_in else "staged copies + scatter",
         "verified_samples_ok": ok,

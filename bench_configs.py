@@ -335,6 +335,8 @@ def config3(args):
                                     "picked up by step-1 polling or by the synchronous branch of step 4", **via},
             "streams": 4 if args.four_streams else 3 if args.scatter_stream else 2, "mapped_swap_in": bool(args.mapped_swap_in),
             "call_order": "swap-out first" if out_first else "swap-in first", "pack_variant": _variant_note(),
+            "swap_out_copies": "enqueued inside the call" if getattr(args, "no_defer_copies", False)
+                               else "held back until their gathers are done (copy thread)",
             "conflict_waits": st["conflict_waits"], "host_arena_bytes": st["host_arena_bytes"],
             "settle": settled, "small_copy_latency_us": fairness}
 
