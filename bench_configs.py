@@ -224,6 +224,7 @@ def config3(args):
     rng = synth.rng_for(3)
     nblk = synth.blocks_for(rng.integers(512, 4097, size=n_pre), s.block_size)
     host_bytes = int((lag + 2) * (256 + 40)) * s.R
+    two_way_peak = kv.kv_link_probe(GiB, 2, 5)  # 1 GiB each way at once, nothing else running
     gpu, pool = _pool(kv, torch, s, host_bytes, copy_chunk_bytes=args.copy_chunk_mib << 20,
                       flags=_flags(args, kv, kv.KV_FLAG_PROFILE))
     a = torch.randn(8192, 8192, device="cuda:0", dtype=torch.bfloat16)
@@ -319,6 +320,8 @@ def config3(args):
     fairness = _copy_fairness(kv, torch, s, gpu) if not getattr(args, "no_fairness", False) else None
     return {"metric": "KV swap GB/s (out+in) and per-preemption switch latency, 1 MI355X", "unit": "GB/s",
             "value": direct["gbps"],
+            "link": {"measured_peak_two_way_gbps": round(two_way_peak, 2),
+                     "frac_of_measured": round(direct["gbps"] / two_way_peak, 4)},
             "config": {"workload": "config 3: Llama-2-13B-shaped MHA KV (40 layers, 40 KV heads, head_dim 128, fp16), "
                                    "pool %d blocks = %.1f GB, %d preemptions of 512..4096 tokens, one out while one in, "
                                    "compute running on a third stream" % (s.n_blocks, s.n_blocks * s.R / 1e9, n_pre)},
