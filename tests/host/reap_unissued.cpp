@@ -90,6 +90,38 @@ int main() {
   EXPECT(out->packed == nullptr && out->done == nullptr);
   EXPECT(p.alloc.n_draining() == 0 && p.alloc.n_free() == 3);
 
+  // room of the out ring beside swap-outs whose copies have not been enqueued yet: the bytes from
+  // the ring head forward to the oldest such region, less one piece held in reserve for a skipped tail
+  {
+    p.R = 10;
+    kvi::ByteRing& r = p.ring_out;
+    r.cap = 1000;
+    r.piece_blocks = 5;  // pieces of 50 bytes
+    r.head = 0;
+    EXPECT(kvi::out_ring_room(&p) == 950);  // nothing held back
+    auto region = [](int64_t off, int64_t len, bool recorded) {
+      kvi::Region g;
+      g.off = off;
+      g.len = len;
+      g.recorded = recorded;
+      return g;
+    };
+    r.live = {region(100, 200, true), region(300, 100, false), region(400, 100, false)};
+    r.head = 500;
+    EXPECT(kvi::out_ring_room(&p) == 500 + 300 - 50);  // to the end, around, up to offset 300
+    r.live = {region(700, 100, false), region(800, 100, true)};
+    r.head = 900;  // (a recorded region behind an open one cannot arise; the oldest open one decides anyway)
+    EXPECT(kvi::out_ring_room(&p) == 100 + 700 - 50);
+    r.live = {region(600, 300, false)};
+    r.head = 100;  // wrapped: the open region lies ahead of the head
+    EXPECT(kvi::out_ring_room(&p) == 500 - 50);
+    r.live = {region(120, 900 - 120, false)};
+    r.head = 100;  // nearly full
+    EXPECT(kvi::out_ring_room(&p) == 0);
+    r.live.clear();
+    r.head = 0;
+  }
+
   p.event_pool.clear();  // stand-in handles: nothing to destroy
   printf("reap_unissued: %d failures\n", g_fail);
   return g_fail ? 1 : 0;
