@@ -546,6 +546,7 @@ def main() -> int:
         # the other workload configs in short form (after the headline's timed region; each waits for
         # the copy engines to be quiet first); `python bench.py --config N` is the long form of each
         log("running configs 1, 4, 5, 3 in short form ...")
+        args.two_way_peak = link_duplex  # measured above, at the start of the process
         result["other_configs"] = bench_configs.other_configs(args)
     print(json.dumps(result), flush=True)
     return 0 if ok else 1
