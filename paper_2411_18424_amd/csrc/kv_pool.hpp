@@ -177,7 +177,6 @@ struct kv_pool {
   char* static_staging = nullptr;  // this device's address of the library's file-scope staging array
   kvi::ByteRing ring_out, ring_in;
   hipStream_t s_pack = nullptr, s_d2h = nullptr, s_h2d = nullptr, s_scat = nullptr;
-  hipStream_t s_d2h2 = nullptr;  // second device-to-host copy stream (small copies alternate), or null
   hipStream_t compute = nullptr;
   hipEvent_t ev_compute = nullptr;
   int unroll = 0, grid = 0, variant = 0;

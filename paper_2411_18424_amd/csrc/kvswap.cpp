@@ -47,7 +47,7 @@ void destroy_pool(kv_pool* p) {
   }
   if (!p->plan) {
     // wait for the library's own streams only: the caller's streams are none of its business
-    for (hipStream_t s : {p->s_pack, p->s_d2h, p->s_h2d, p->s_scat, p->s_d2h2})
+    for (hipStream_t s : {p->s_pack, p->s_d2h, p->s_h2d, p->s_scat})
       if (s) (void)hipStreamSynchronize(s);
     for (ByteRing* r : {&p->ring_out, &p->ring_in})
       for (Region& g : r->live)
@@ -69,7 +69,7 @@ void destroy_pool(kv_pool* p) {
     if (p->ev_compute) (void)hipEventDestroy(p->ev_compute);
     if (p->s_d2h == p->s_pack) p->s_d2h = nullptr;  // aliases of the other two
     if (p->s_scat == p->s_h2d) p->s_scat = nullptr;
-    for (hipStream_t s : {p->s_pack, p->s_d2h, p->s_h2d, p->s_scat, p->s_d2h2})
+    for (hipStream_t s : {p->s_pack, p->s_d2h, p->s_h2d, p->s_scat})
       if (s) (void)hipStreamDestroy(s);
     if (p->own_staging && p->staging) (void)hipFree(p->staging);
     if (p->host) (void)hipHostFree(p->host);
