@@ -363,7 +363,7 @@ def config4(args):
     arena_blocks = (args.arena_gib << 30) // s.R
     waves, cur, used = [], [], 0
     for c in range(n_conv):  # greedy waves that fit the arena (context + room for two turns)
-        need = int(nb0[c]) + 140
+        need = int(nb0[c]) + 180
         if cur and used + need > arena_blocks:
             waves.append(cur)
             cur, used = [], 0
@@ -378,6 +378,7 @@ def config4(args):
     work = rng.permutation(s.n_blocks)[:1200].astype(np.int32)
     full_ms, delta_ms, in_ms, fracs, delta_bytes, full_bytes = [], [], [], [], 0, 0
     delta_op_gbps, full_recs, probes = [], [], []
+    new_ms, new_fracs, new_bytes = [], [], 0  # third turn: the new turn's blocks only, no scattered ones
 
     def probe():  # is the link itself disturbed right now?  (a 256 MiB device-to-host copy, best of 3)
         probes.append(round(kv.kv_link_probe(256 * MiB, 0, 3), 2))
@@ -389,7 +390,7 @@ def config4(args):
             pool.swap_out(c, rng.permutation(work)[:int(nb0[c])])
             tok[c] = int(ctx[c])
         pool.kv_wait_all()
-        for turn in range(2):
+        for turn in range(3):
             for c in wave:
                 n_old = int(synth.blocks_for(tok[c], B))
                 t = rng.permutation(work)[:n_old]
@@ -399,15 +400,22 @@ def config4(args):
                 in_ms.append((time.perf_counter() - a0) * 1e3)
                 new_tokens = int(rng.integers(64, 513))
                 dirty = synth.turn_dirty_mask(n_old, tok[c], new_tokens, B)
-                target = rng.uniform(0.05, 0.30)
-                dirty[:n_old] |= synth.random_mask(rng, n_old, max(0.0, target - dirty.mean()))
+                if turn < 2:  # top the mask up with scattered blocks of the old context (contaminated copies)
+                    target = rng.uniform(0.05, 0.30)
+                    dirty[:n_old] |= synth.random_mask(rng, n_old, max(0.0, target - dirty.mean()))
                 grown = np.concatenate([t, np.setdiff1d(work, t)[:len(dirty) - n_old]]).astype(np.int32)
                 a0 = time.perf_counter()
                 moved = pool.swap_out_delta(c, grown, dirty)
                 pool.kv_wait(c)
                 ms = (time.perf_counter() - a0) * 1e3
-                delta_ms.append(ms)
                 assert moved == int(dirty.sum()), (moved, int(dirty.sum()))
+                if turn == 2:
+                    new_ms.append(ms)
+                    new_bytes += moved * s.R
+                    new_fracs.append(moved / len(dirty))
+                    tok[c] += new_tokens
+                    continue
+                delta_ms.append(ms)
                 delta_bytes += moved * s.R
                 delta_op_gbps.append(moved * s.R / ms / 1e6)
                 fracs.append(moved / len(dirty))
@@ -430,7 +438,8 @@ def config4(args):
             "value": round(delta_bytes / (sum(delta_ms) * 1e-3) / 1e9, 3),
             "value_is": "payload rate of the delta swap-outs alone (all of them: bytes / summed call-to-done times)",
             "config": {"workload": "config 4: Llama-3-8B shape, %d conversations with 1k..16k tokens on the host, in %d wave(s) "
-                                   "through a %.0f GiB pinned arena, 2 turns of +64..512 tokens, dirty fraction 5..30 %%"
+                                   "through a %.0f GiB pinned arena, 2 turns of +64..512 tokens with the mask topped up by "
+                                   "scattered blocks to a dirty fraction of 5..30 %% (the value), then a turn of new blocks only"
                                    % (n_conv, len(waves), host_bytes / GiB)},
             "dirty_fraction": {"min": round(min(fracs), 3), "median": _pct(fracs, 50), "max": round(max(fracs), 3)},
             "delta_swap_out_ms": {"median": _pct(delta_ms, 50), "p99": _pct(delta_ms, 99)},
@@ -440,6 +449,14 @@ def config4(args):
                                            "p90": _pct(delta_op_gbps, 90)},
             "link_probe_d2h_gbps": {"what": "256 MiB pinned copies between the phases of the run: is the link itself steady",
                                     "min": min(probes), "median": _pct(probes, 50), "max": max(probes)},
+            "new_blocks_only": {"what": "a third turn per conversation whose mask holds the turn's own blocks only (the tail "
+                                        "block it wrote into and the appended ones: adjacent records on the host), "
+                                        "no scattered blocks of the old context",
+                                "gbps": round(new_bytes / (sum(new_ms) * 1e-3) / 1e9, 3),
+                                "ms": {"median": _pct(new_ms, 50), "p99": _pct(new_ms, 99)},
+                                "dirty_fraction": {"min": round(min(new_fracs), 3), "median": _pct(new_fracs, 50),
+                                                   "max": round(max(new_fracs), 3)},
+                                "mean_MiB": round(new_bytes / len(new_ms) / MiB, 1)},
             "full_swap_out_ms": {"median": _pct(full_ms, 50), "p99": _pct(full_ms, 99)},
             "full_swap_out_gbps": round(full_bytes / (sum(full_ms) * 1e-3) / 1e9, 3),
             "swap_in_ms": {"median": _pct(in_ms, 50), "p99": _pct(in_ms, 99)},
