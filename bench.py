@@ -192,6 +192,8 @@ def main() -> int:
                     help="KV_FLAG_NO_DEFER_COPIES: every swap-out's copies are enqueued inside the call and wait for "
                          "their gathers on the device (default: the pool's copy thread enqueues them once the gathers "
                          "have finished)")
+    ap.add_argument("--no-direct-path", action="store_true",
+                    help="config 5: leave out the per-group direct copies (the comparison path with hundreds of thousands of copies)")
     ap.add_argument("--out-first", action="store_true",
                     help="config 3: issue the swap-out of an iteration before its swap-in (default: swap-in first)")
     ap.add_argument("--requests", type=int, default=4, help="config 5: 10 GiB requests per run length")
