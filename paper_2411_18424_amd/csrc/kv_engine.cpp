@@ -501,9 +501,19 @@ int32_t enqueue_in(kv_pool* p, const std::vector<Move>& mv, const std::vector<hi
   int32_t rc;
   for (hipEvent_t e : pre_copy)
     if ((rc = stream_wait(p, p->s_h2d, e))) return rc;
-  if ((rc = order_after_compute(p, p->s_scat))) return rc;
-  for (hipEvent_t e : pre_scat)
-    if ((rc = stream_wait(p, p->s_scat, e))) return rc;
+  // What the scatters have to wait for (the caller's compute, gathers that still read the target
+  // blocks) is put in front of the first scatter, not in front of the copies: with one stream per
+  // direction the first piece's copy into staging then runs while that work finishes.
+  bool scatter_ordered = false;
+  auto order_scatters = [&]() -> int32_t {
+    if (scatter_ordered) return KV_OK;
+    scatter_ordered = true;
+    int32_t rc2;
+    if ((rc2 = order_after_compute(p, p->s_scat))) return rc2;
+    for (hipEvent_t e : pre_scat)
+      if ((rc2 = stream_wait(p, p->s_scat, e))) return rc2;
+    return KV_OK;
+  };
   ByteRing& r = p->ring_in;
   const int64_t m = (int64_t)mv.size();
   auto no_flush = []() -> int32_t { return KV_OK; };  // every region is closed before the next claim
@@ -518,6 +528,7 @@ int32_t enqueue_in(kv_pool* p, const std::vector<Move>& mv, const std::vector<hi
     if (ready) op->aux.push_back(ready);
     if ((rc = record(p, ready, p->s_h2d))) return rc;
     if ((rc = stream_wait(p, p->s_scat, ready))) return rc;
+    if ((rc = order_scatters())) return rc;
     for (int64_t k = 0; k < mp; k += p->launch_blocks) {
       int64_t ml = std::min<int64_t>(p->launch_blocks, mp - k);
       if ((rc = launch_pack(p, true, at(sb, k * p->R), &mv[(size_t)(i + k)], ml))) return rc;
@@ -525,6 +536,7 @@ int32_t enqueue_in(kv_pool* p, const std::vector<Move>& mv, const std::vector<hi
     if ((rc = record(p, g->freed, p->s_scat))) return rc;
     g->recorded = true;
   }
+  if ((rc = order_scatters())) return rc;  // an empty move list still completes in order
   if (m == 0) {
     // nothing moved: completion still follows the image's last writer
     for (hipEvent_t e : pre_copy)
