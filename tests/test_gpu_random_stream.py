@@ -352,6 +352,10 @@ CASES = {
                                                              max_piece_bytes=128 * KiB, defer_min_bytes=1)),
     "deferred_copies_three_streams": (109, ORDER_COMPUTE | SCATTER_STREAM, dict(host_slack_blocks=4, defer_min_bytes=1)),
     "deferred_copies_tight_host_arena": (110, ORDER_COMPUTE, dict(host_slack_blocks=2, defer_min_bytes=1)),
+    "deferred_copies_four_streams_small_rings": (111, ORDER_COMPUTE | FOUR_STREAMS,
+                                                 dict(staging_out_bytes=1 * MiB, staging_in_bytes=512 * KiB,
+                                                      max_piece_bytes=64 * KiB, defer_min_bytes=1)),
+    "deferred_copies_mapped_swap_in": (112, ORDER_COMPUTE | MAPPED_SWAP_IN, dict(host_slack_blocks=8, defer_min_bytes=1)),
 }
 
 
