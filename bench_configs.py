@@ -350,8 +350,9 @@ def config3(args):
 def config4(args):
     """Multi-turn delta swap on the Llama-3-8B shape: conversations with a host copy return,
     append 64..512 tokens and leave; only dirty blocks move out.  The stated 128 conversations
-    need about 110 GiB of pinned memory at once, more than one allocation gets on these machines
-    (64 GiB was granted, 72 GiB refused): they go through an arena of --arena-gib in waves."""
+    need about 110 GiB of pinned memory at once, more than a process gets on these machines
+    (64 GiB was granted, 72 GiB refused, a second 48 GiB beside a first refused too): they go
+    through an arena of --arena-gib in waves."""
     import torch
     from paper_2411_18424_amd import kvswap as kv, synth
     s = synth.LLAMA3_8B
