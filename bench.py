@@ -194,6 +194,8 @@ def main() -> int:
                          "have finished)")
     ap.add_argument("--no-direct-path", action="store_true",
                     help="config 5: leave out the per-group direct copies (the comparison path with hundreds of thousands of copies)")
+    ap.add_argument("--second-lane", action="store_true",
+                    help="KV_FLAG_SECOND_LANE: scattered records of a held-back swap-out as plain copies over both copy streams")
     ap.add_argument("--out-first", action="store_true",
                     help="config 3: issue the swap-out of an iteration before its swap-in (default: swap-in first)")
     ap.add_argument("--requests", type=int, default=4, help="config 5: 10 GiB requests per run length")
@@ -265,6 +267,7 @@ def main() -> int:
                      flags=kv.KV_FLAG_PROFILE | (kv.KV_FLAG_FOUR_STREAMS if args.four_streams else 0)
                      | (kv.KV_FLAG_SCATTER_STREAM if args.scatter_stream else 0)
                      | (kv.KV_FLAG_NO_DEFER_COPIES if args.no_defer_copies else 0)
+                     | (kv.KV_FLAG_SECOND_LANE if args.second_lane else 0)
                      | (kv.KV_FLAG_MAPPED_SWAP_IN if args.mapped_swap_in else 0),
                      pack_variant=int(os.environ.get("KVSWAP_PACK_VARIANT", "0")),
                      copy_chunk_bytes=args.copy_chunk_mib << 20, max_piece_bytes=args.max_piece_mib << 20)

@@ -35,7 +35,8 @@ def _flags(args, kv, base=0):
             | (kv.KV_FLAG_MAPPED_SWAP_IN if args.mapped_swap_in else 0)
             | (kv.KV_FLAG_MAPPED_SWAP_OUT if getattr(args, "mapped_swap_out", False) else 0)
             | (kv.KV_FLAG_NO_STRIDED_COPIES if getattr(args, "no_strided_copies", False) else 0)
-            | (kv.KV_FLAG_NO_DEFER_COPIES if getattr(args, "no_defer_copies", False) else 0))
+            | (kv.KV_FLAG_NO_DEFER_COPIES if getattr(args, "no_defer_copies", False) else 0)
+            | (kv.KV_FLAG_SECOND_LANE if getattr(args, "second_lane", False) else 0))
 
 
 def _variant_note():

@@ -102,6 +102,15 @@ typedef enum {
                                        and a swap-out that does not fit the out ring beside the held-back ones,
                                        first wait on the host for the hand-over.  Costs a few
                                        microseconds per swap-out. */
+#define KV_FLAG_SECOND_LANE   1024u /* a held-back swap-out (see above) of many scattered records of 1 to 8 MiB
+                                       sends them as plain copies, every other one on the host-to-device stream,
+                                       while no swap-in is in flight: that stream's copy engine would otherwise be
+                                       idle, and two engines overlap the pause each makes between two copies
+                                       (Section 3.3's increments with contaminated blocks: 50.8 -> 52-53 GB/s).
+                                       A swap-in issued meanwhile queues behind those copies (at most 256 MiB of
+                                       them).  Off by default: which copy engine a stream uses is the runtime's
+                                       choice; the library arranges its calls so that the two streams got different
+                                       ones in every process measured, and loses 10 % where they do not */
 #define KV_FLAG_NO_STRIDED_COPIES 256u /* one copy per run of adjacent host records, never a 2-D copy over
                                        several equal runs a constant stride apart (for comparison) */
 
@@ -336,6 +345,7 @@ typedef struct {
   int64_t host_evicted_blocks;          /* logical blocks whose host copy was reclaimed (KV_FLAG_HOST_EVICT) */
   int64_t host_arena_used, host_arena_bytes;
   int64_t strided_copies;               /* of d2h_copies + h2d_copies: 2-D copies that carry several runs */
+  int64_t second_lane_copies;           /* of d2h_copies: issued on the host-to-device stream (KV_FLAG_SECOND_LANE) */
 } kv_stats_t;
 int32_t kv_stats(kv_pool_t* pool, kv_stats_t* out);
 

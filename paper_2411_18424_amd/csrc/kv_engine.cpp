@@ -220,7 +220,67 @@ void plan_copies(const Move* mv, int64_t m, int64_t R, int64_t copy_chunk, bool 
   }
 }
 
-int32_t issue_copies(kv_pool* p, bool to_host, char* slot, const Move* mv, int64_t m) {
+// One copy of a plan, on stream s.
+static int32_t issue_one(kv_pool* p, bool to_host, char* slot, const CopyDesc& c, hipStream_t s) {
+  char* h = p->host + c.host_off;
+  char* d = slot + c.slot_off;
+  if (c.rows > 1) {
+    if (to_host)
+      HIP_TRY(hipMemcpy2DAsync(h, (size_t)c.pitch, d, (size_t)c.width, (size_t)c.width, (size_t)c.rows,
+                               hipMemcpyDeviceToHost, s));
+    else
+      HIP_TRY(hipMemcpy2DAsync(d, (size_t)c.width, h, (size_t)c.pitch, (size_t)c.width, (size_t)c.rows,
+                               hipMemcpyHostToDevice, s));
+  } else if (to_host) {
+    HIP_TRY(hipMemcpyAsync(h, d, (size_t)c.width, hipMemcpyDeviceToHost, s));
+  } else {
+    HIP_TRY(hipMemcpyAsync(d, h, (size_t)c.width, hipMemcpyHostToDevice, s));
+  }
+  return KV_OK;
+}
+
+// KV_FLAG_SECOND_LANE: the scattered records of a held-back swap-out as plain copies, every other one
+// on `lane2`, the host-to-device stream, whose copy engine has nothing to do while no swap-in is in
+// flight.  A copy engine spends about 9 us between two copies; two engines spend them in turn.
+// Measured (2 MiB records, a fifth of a 400-block image dirty): 45.6 GB/s as plain copies on one
+// stream, 50.8 as 2-D copies on one stream (the default), 52-53 this way.  2-D copies themselves do
+// not run side by side on two streams (45.5 GB/s on one or on two), and a second stream of the same
+// direction shares the first one's engine, so it has to be this stream and plain copies.
+// What makes the second stream use another engine is the runtime's to decide; what was seen is that a
+// stream with nothing outstanding takes an engine that is free at that moment and then stays on it.
+// So the second lane is synchronised first (its earlier copies are long done) and gets its first
+// copy only when the own lane's first copy has finished and its second one is running.  Without
+// that the second lane ended up on the own lane's engine in whole processes (46 GB/s).
+// The own stream is made to wait for the second lane's last copy, so what is recorded on it
+// afterwards covers both; the events used go to *aux.  Called by the copy thread only: the copies
+// depend on nothing that still runs, and the caller has seen that no swap-in is in flight.
+static int32_t issue_two_lanes(kv_pool* p, char* slot, const std::vector<CopyDesc>& plan, hipStream_t lane2,
+                               std::vector<hipEvent_t>* aux) {
+  int32_t rc;
+  hipEvent_t first_done, hop;
+  if ((rc = get_event(p, &first_done))) return rc;
+  aux->push_back(first_done);
+  if ((rc = get_event(p, &hop))) return rc;
+  aux->push_back(hop);
+  const hipStream_t own = p->s_d2h;
+  if ((rc = issue_one(p, true, slot, plan[0], own))) return rc;
+  HIP_TRY(hipEventRecord(first_done, own));
+  if ((rc = issue_one(p, true, slot, plan[2], own))) return rc;
+  HIP_TRY(hipStreamSynchronize(lane2));
+  HIP_TRY(hipEventSynchronize(first_done));
+  for (size_t k = 1; k < plan.size(); ++k) {
+    if (k == 2) continue;
+    if ((rc = issue_one(p, true, slot, plan[k], (k & 1) ? lane2 : own))) return rc;
+  }
+  HIP_TRY(hipEventRecord(hop, lane2));
+  HIP_TRY(hipStreamWaitEvent(own, hop, 0));
+  p->st.d2h_copies += (int64_t)plan.size();
+  p->st.second_lane_copies += (int64_t)plan.size() / 2;
+  return KV_OK;
+}
+
+int32_t issue_copies(kv_pool* p, bool to_host, char* slot, const Move* mv, int64_t m, hipStream_t lane2 = nullptr,
+                     std::vector<hipEvent_t>* aux = nullptr) {
   hipStream_t s = to_host ? p->s_d2h : p->s_h2d;
   hipEvent_t e0 = nullptr, e1 = nullptr;
   if (p->profile && !p->plan) {
@@ -232,25 +292,26 @@ int32_t issue_copies(kv_pool* p, bool to_host, char* slot, const Move* mv, int64
     HIP_TRY(hipEventRecord(e0, s));
   }
   std::vector<CopyDesc> plan;
+  if (lane2 && to_host && !p->plan && m * p->R <= KV_SECOND_LANE_MAX_PIECE_BYTES) {
+    // worth two lanes: several plain copies of a few MiB each (the sizes measured)
+    plan_copies(mv, m, p->R, p->copy_chunk, false, &plan);
+    const int64_t n = (int64_t)plan.size();
+    if (n >= KV_SECOND_LANE_MIN_COPIES && m * p->R >= n * KV_SECOND_LANE_MIN_AVG_BYTES &&
+        m * p->R <= n * KV_SECOND_LANE_MAX_AVG_BYTES) {
+      int32_t rc = issue_two_lanes(p, slot, plan, lane2, aux);
+      if (rc) return rc;
+      if (e1) HIP_TRY(hipEventRecord(e1, s));
+      return KV_OK;
+    }
+    plan.clear();
+  }
   plan_copies(mv, m, p->R, p->copy_chunk, p->strided_copies, &plan);
   for (const CopyDesc& c : plan) {
     (to_host ? p->st.d2h_copies : p->st.h2d_copies)++;
     if (c.rows > 1) p->st.strided_copies++;
     if (p->plan) continue;
-    char* h = p->host + c.host_off;
-    char* d = slot + c.slot_off;
-    if (c.rows > 1) {
-      if (to_host)
-        HIP_TRY(hipMemcpy2DAsync(h, (size_t)c.pitch, d, (size_t)c.width, (size_t)c.width, (size_t)c.rows,
-                                 hipMemcpyDeviceToHost, s));
-      else
-        HIP_TRY(hipMemcpy2DAsync(d, (size_t)c.width, h, (size_t)c.pitch, (size_t)c.width, (size_t)c.rows,
-                                 hipMemcpyHostToDevice, s));
-    } else if (to_host) {
-      HIP_TRY(hipMemcpyAsync(h, d, (size_t)c.width, hipMemcpyDeviceToHost, s));
-    } else {
-      HIP_TRY(hipMemcpyAsync(d, h, (size_t)c.width, hipMemcpyHostToDevice, s));
-    }
+    int32_t rc = issue_one(p, to_host, slot, c, s);
+    if (rc) return rc;
   }
   if (e1) HIP_TRY(hipEventRecord(e1, s));
   return KV_OK;
@@ -327,9 +388,10 @@ int32_t ring_claim(kv_pool* p, ByteRing* r, int64_t len, uint64_t op_seq, hipStr
 // Copies of one gathered piece (moves [first, first + count) at ring offset off) to the host, and
 // the event that gives its ring region back.
 static int32_t drain_piece(kv_pool* p, ByteRing& r, uint64_t op_seq, const Move* mv, int64_t first,
-                           int64_t count, int64_t off) {
+                           int64_t count, int64_t off, hipStream_t lane2 = nullptr,
+                           std::vector<hipEvent_t>* aux = nullptr) {
   int32_t rc;
-  if ((rc = issue_copies(p, true, at(r.base, off), mv + first, count))) return rc;
+  if ((rc = issue_copies(p, true, at(r.base, off), mv + first, count, lane2, aux))) return rc;
   for (Region& g : r.live)
     if (g.off == off && g.op_seq == op_seq && !g.recorded) {
       if ((rc = record(p, g.freed, p->s_d2h))) return rc;
@@ -365,7 +427,14 @@ static void copy_thread_main(kv_pool* p) {
       lk.lock();
       if (e != hipSuccess) note(fail(KV_EHIP, "copy thread: hipEventSynchronize: %s", hipGetErrorString(e)));
       note(stream_wait(p, p->s_d2h, q.ready));  // already complete: costs nothing, and keeps the order on the device explicit
-      note(drain_piece(p, p->ring_out, job.op->seq, job.mv.data(), q.first, q.count, q.off));
+      // KV_FLAG_SECOND_LANE: while no swap-in is in flight the host-to-device stream may carry every
+      // other copy of a piece of scattered records (issue_two_lanes)
+      hipStream_t lane2 = nullptr;
+      if (p->second_lane) {
+        reap(p);
+        if (p->ops_in.empty()) lane2 = p->s_h2d;
+      }
+      note(drain_piece(p, p->ring_out, job.op->seq, job.mv.data(), q.first, q.count, q.off, lane2, &job.op->aux));
     }
     note(record(p, job.op->done, p->s_d2h));
     job.op->issued = true;

@@ -112,6 +112,11 @@ struct Move {
 struct CopyDesc {
   int64_t host_off, slot_off, width, rows, pitch;
 };
+// KV_FLAG_SECOND_LANE: which pieces of a held-back swap-out travel as plain copies on two streams
+constexpr int64_t KV_SECOND_LANE_MIN_COPIES = 8;
+constexpr int64_t KV_SECOND_LANE_MIN_AVG_BYTES = 1ll << 20;     // average copy of 1 MiB ... 8 MiB: the sizes measured
+constexpr int64_t KV_SECOND_LANE_MAX_AVG_BYTES = 8ll << 20;
+constexpr int64_t KV_SECOND_LANE_MAX_PIECE_BYTES = 512ll << 20;  // bounds what a swap-in that arrives meanwhile queues behind
 constexpr int64_t KV_MAX_COPY_PITCH = 1ll << 30;      // largest host pitch of a 2-D copy (measured up to here)
 constexpr int64_t KV_MAX_STRIDED_WIDTH = 16ll << 20;  // widest row of a 2-D copy (measured up to here)
 
@@ -184,6 +189,7 @@ struct kv_pool {
   int64_t copy_chunk = 0;
   bool defer_copies = true;   // off with KV_FLAG_NO_DEFER_COPIES
   int64_t defer_min = 0;      // smallest swap-out (bytes) whose copies are held back
+  bool second_lane = false;   // KV_FLAG_SECOND_LANE
   int device = 0;             // the device that was current when the pool was created
   bool strided_copies = true;  // equal runs a constant stride apart go out as rows of one 2-D copy
   int64_t slack = 32;

@@ -23,6 +23,7 @@ KV_FLAG_PLAN_ONLY, KV_FLAG_PROFILE, KV_FLAG_ORDER_COMPUTE, KV_FLAG_FOUR_STREAMS 
 KV_FLAG_MAPPED_SWAP_IN, KV_FLAG_HOST_EVICT, KV_FLAG_MAPPED_SWAP_OUT, KV_FLAG_SCATTER_STREAM = 16, 32, 64, 128
 KV_FLAG_NO_STRIDED_COPIES = 256
 KV_FLAG_NO_DEFER_COPIES = 512
+KV_FLAG_SECOND_LANE = 1024
 KV_TASK_SWAP_OUT, KV_TASK_SWAP_IN, KV_TASK_SWAP_OUT_DELTA, KV_TASK_SWAP_IN_DELTA = 0, 1, 2, 3
 KV_WHERE_RUNNING, KV_WHERE_SWAPPED, KV_WHERE_ONGOING_SWAP_IN = 0, 1, 2
 KV_IT_FREE_OUT_BLOCKS = 1
@@ -57,7 +58,7 @@ class kv_stats_t(C.Structure):
         "bytes_out", "bytes_in", "blocks_out", "blocks_in", "gather_launches",
         "scatter_launches", "d2h_copies", "h2d_copies", "conflict_waits",
         "host_new_extents", "host_evicted_blocks", "host_arena_used", "host_arena_bytes",
-        "strided_copies")]
+        "strided_copies", "second_lane_copies")]
 
 
 class kv_bg_stats_t(C.Structure):

@@ -270,6 +270,45 @@ def test_scattered_dirty_blocks_and_scattered_swap_in(harness, flags):
     assert st["bytes_out"] == h.oracle.bytes_out and st["bytes_in"] == h.oracle.bytes_in
 
 
+@pytest.mark.parametrize("flags", [1024, 1024 | 8], ids=["two_streams", "four_streams"])
+def test_scattered_records_over_both_copy_streams(harness, flags):
+    """KV_FLAG_SECOND_LANE: the scattered 1 MiB records of a delta swap-out travel as plain copies,
+    every other one on the host-to-device stream, unless a swap-in is in flight; images and pool
+    must match the oracle byte for byte, also when a swap-in follows at once on that stream."""
+    shape = synth.KVShape("s", 16, 8, 128, 16, 2, 512, "bf16")  # R = 1 MiB
+    h = harness(shape, cfg=39, host_bytes=400 * MiB, fill="random", flags=flags, host_slack_blocks=8)
+    rng = synth.rng_for(39)
+    perm = rng.permutation(512).astype(np.int32)
+    t, other, spare = perm[:200], perm[200:260], perm[260:320]
+    h.pool.swap_out(0, t)
+    h.oracle.swap_out(0, t)
+    h.pool.swap_out(1, other)
+    h.oracle.swap_out(1, other)
+    h.pool.kv_wait_all()
+    for turn in range(4):
+        dirty = synth.random_mask(rng, t.size, 0.25)
+        touched = np.flatnonzero(dirty)
+        h.overwrite_blocks(t[touched], synth.fresh_tokens(rng, shape, touched.size))
+        if turn == 2:      # a swap-in is in flight: the host-to-device stream is not idle
+            h.pool.swap_in(1, spare)
+            h.oracle.swap_in(1, spare)
+        moved = h.pool.swap_out_delta(0, t, dirty)
+        assert moved == len(h.oracle.swap_out_delta(0, t, dirty))
+        if turn == 1:      # a swap-in right behind the swap-out, on the stream that carries half of its copies
+            h.pool.swap_in(1, spare)
+            h.oracle.swap_in(1, spare)
+        h.pool.kv_wait_all()
+        h.assert_image_equal(0)
+        h.assert_pool_equal()
+        if turn in (1, 2):
+            h.pool.swap_out(1, spare)
+            h.oracle.swap_out(1, spare)
+            h.pool.kv_wait(1)
+            other, spare = spare, other
+    st = h.pool.kv_stats()
+    assert st["second_lane_copies"] > 0 and st["bytes_out"] == h.oracle.bytes_out
+
+
 def test_partial_swap_in_moves_only_non_resident_blocks(harness):
     h = harness(synth.TINY, cfg=8)
     rng = synth.rng_for(8)

@@ -19,6 +19,7 @@ BIG = synth.KVShape("stream_big", 8, 8, 128, 16, 2, 4096, "bf16")
 
 ORDER_COMPUTE, FOUR_STREAMS, MAPPED_SWAP_IN, MAPPED_SWAP_OUT, SCATTER_STREAM = 4, 8, 16, 64, 128
 NO_DEFER_COPIES = 512
+SECOND_LANE = 1024
 
 
 class Loop:
@@ -391,6 +392,7 @@ BIG_CASES = {
     "three_streams": (204, ORDER_COMPUTE | SCATTER_STREAM, dict(staging_out_bytes=128 * MiB, staging_in_bytes=32 * MiB,
                                                              max_piece_bytes=8 * MiB)),
     "mapped_both_ways": (203, ORDER_COMPUTE | MAPPED_SWAP_IN | MAPPED_SWAP_OUT, dict(mapped_out_max_blocks=64)),
+    "second_lane": (207, ORDER_COMPUTE | SECOND_LANE, dict(staging_out_bytes=256 * MiB, staging_in_bytes=64 * MiB)),
     # the cases above hold back the copies of swap-outs of 16 MiB or more (the default); these hold back all, or none
     "all_copies_held_back_small_rings": (205, ORDER_COMPUTE, dict(staging_out_bytes=48 * MiB, staging_in_bytes=24 * MiB,
                                                                  max_piece_bytes=8 * MiB, defer_min_bytes=1)),
