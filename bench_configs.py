@@ -466,6 +466,7 @@ def config4(args):
             "all_kernels_and_copies": _rates(pool_recs),
             "bytes_moved_equals_dirty_blocks": True, "mapped_swap_in": bool(args.mapped_swap_in),
             "strided_copies": not getattr(args, "no_strided_copies", False), "pack_variant": _variant_note(),
+            "second_lane": bool(getattr(args, "second_lane", False)), "second_lane_copies": st["second_lane_copies"],
             "host_new_extents": st["host_new_extents"], "d2h_copies": st["d2h_copies"],
             "d2h_copies_strided": st["strided_copies"], "settle": settled}
 
@@ -567,11 +568,15 @@ def other_configs(args):
     a.requests, a.no_group_sweep = 2, True
     a.mapped_swap_in = a.mapped_swap_out = a.four_streams = a.scatter_stream = a.no_strided_copies = False
     a.copy_chunk_mib = 0
+    a.second_lane = False
+    lane = copy.copy(a)
+    lane.second_lane = True  # config 4 once more with KV_FLAG_SECOND_LANE
     out = {}
-    for name, fn in (("config_1", config1), ("config_4", config4), ("config_5", config5), ("config_3", config3)):
+    for name, fn, arg in (("config_1", config1, a), ("config_4", config4, a), ("config_4_second_lane", config4, lane),
+                          ("config_5", config5, a), ("config_3", config3, a)):
         t0 = time.perf_counter()
         try:
-            r = fn(a)
+            r = fn(arg)
             r.pop("metric", None)
         except Exception as e:  # e.g. not enough free device or pinned memory for this config's pool: say so, go on
             r = {"error": "%s: %s" % (type(e).__name__, str(e)[:300])}
