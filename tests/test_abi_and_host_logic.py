@@ -353,6 +353,32 @@ def test_mapped_swap_out_takes_small_moved_sets_only(kv):
     assert ei.value.status == kv.KV_EINVAL
 
 
+def test_copy_scheduling_options_do_not_change_what_moves(kv):
+    """Holding copies back, never holding them back, the second copy lane: options of how copies
+    are enqueued.  The plan (what moves, how many launches and copies, where the records land)
+    is the same under each of them; a plan-only pool starts no thread."""
+    shape = synth.TINY
+    rng = synth.rng_for(77)
+    t = rng.permutation(shape.n_blocks)[:40].astype(np.int32)
+    dirty = synth.random_mask(rng, 40, 0.3)
+    seen = []
+    for flags, kw in ((0, {}), (kv.KV_FLAG_NO_DEFER_COPIES, {}), (kv.KV_FLAG_SECOND_LANE, dict(defer_min_bytes=1)),
+                      (0, dict(defer_min_bytes=1))):
+        p = plan_pool(kv, shape, host_blocks=256, flags_extra=flags, **kw)
+        p.swap_out(3, t)
+        assert p.kv_query(3)
+        moved = p.swap_out_delta(3, t, dirty)
+        p.swap_in(3, t[::-1].copy())
+        p.kv_wait_all()
+        st = p.kv_stats()
+        rec = p.kv_host_blocks(3)[1]
+        seen.append((moved, st["gather_launches"], st["d2h_copies"], st["h2d_copies"], st["strided_copies"],
+                     st["second_lane_copies"], st["bytes_out"], st["bytes_in"], tuple(int(r) for r in rec)))
+        p.kv_pool_destroy()
+    assert all(s == seen[0] for s in seen), seen
+    assert seen[0][0] == int(dirty.sum()) and seen[0][5] == 0
+
+
 def test_host_images_grow_by_extents_and_give_everything_back(kv):
     """Section 3.3: room behind a new image is reserved for the next turn; when it is used up
     the image continues in a further extent (it is never moved)."""
