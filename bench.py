@@ -196,6 +196,10 @@ def main() -> int:
                     help="config 5: leave out the per-group direct copies (the comparison path with hundreds of thousands of copies)")
     ap.add_argument("--second-lane", action="store_true",
                     help="KV_FLAG_SECOND_LANE: scattered records of a held-back swap-out as plain copies over both copy streams")
+    ap.add_argument("--no-profile", action="store_true",
+                    help="config 3: a pool without KV_FLAG_PROFILE, as an application would create it (no per-launch rates)")
+    ap.add_argument("--no-launch-events", action="store_true",
+                    help="KV_FLAG_NO_LAUNCH_EVENTS: plain pack launches also for large swaps (with --no-profile)")
     ap.add_argument("--out-first", action="store_true",
                     help="config 3: issue the swap-out of an iteration before its swap-in (default: swap-in first)")
     ap.add_argument("--requests", type=int, default=4, help="config 5: 10 GiB requests per run length")

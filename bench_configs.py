@@ -36,7 +36,8 @@ def _flags(args, kv, base=0):
             | (kv.KV_FLAG_MAPPED_SWAP_OUT if getattr(args, "mapped_swap_out", False) else 0)
             | (kv.KV_FLAG_NO_STRIDED_COPIES if getattr(args, "no_strided_copies", False) else 0)
             | (kv.KV_FLAG_NO_DEFER_COPIES if getattr(args, "no_defer_copies", False) else 0)
-            | (kv.KV_FLAG_SECOND_LANE if getattr(args, "second_lane", False) else 0))
+            | (kv.KV_FLAG_SECOND_LANE if getattr(args, "second_lane", False) else 0)
+            | (kv.KV_FLAG_NO_LAUNCH_EVENTS if getattr(args, "no_launch_events", False) else 0))
 
 
 def _variant_note():
@@ -229,8 +230,9 @@ def config3(args):
     # stream on the copy engine it used last, and in a process that has already run other pools the probe's two
     # fresh streams can come up on one engine (it then reads 60 GB/s, less than the swaps below reach)
     two_way_peak = getattr(args, "two_way_peak", 0) or kv.kv_link_probe(GiB, 2, 5)
+    profiled = not getattr(args, "no_profile", False)  # timing events on every launch and copy, for the rates below
     gpu, pool = _pool(kv, torch, s, host_bytes, copy_chunk_bytes=args.copy_chunk_mib << 20,
-                      flags=_flags(args, kv, kv.KV_FLAG_PROFILE))
+                      flags=_flags(args, kv, kv.KV_FLAG_PROFILE if profiled else 0))
     a = torch.randn(8192, 8192, device="cuda:0", dtype=torch.bfloat16)
     comp = torch.cuda.Stream()
     settled = settle(torch)
@@ -257,7 +259,8 @@ def config3(args):
         """The 200-preemption stream; tables from the library's block-group allocator (groups of >= 8
         where the pool allows).  mgr None: direct calls; else through kv_manager_iterate."""
         lat, evs, in_tables, moved = [], [], {}, 0
-        pool.kv_profile_reset()
+        if profiled:
+            pool.kv_profile_reset()
         t_start = time.perf_counter()
         for i in range(n_pre + lag):
             evs.append(compute(per_iter))  # keeps the compute stream busy for about one iteration
@@ -304,7 +307,7 @@ def config3(args):
         busy_ms = sum(x.elapsed_time(y) for x, y in evs) / (per_iter * len(evs))
         return {"gbps": round(moved / total_s / 1e9, 3),
                 "switch_latency_ms": {"median": _pct(lat, 50), "p99": _pct(lat, 99), "max": _pct(lat, 100)},
-                "kernels_and_copies": _rates(pool.kv_profile_read()),
+                "kernels_and_copies": _rates(pool.kv_profile_read()) if profiled else None,
                 "compute_slowdown": round(busy_ms / alone_ms, 4), "compute_ms_beside_swaps": round(busy_ms, 4)}
 
     out_first = bool(getattr(args, "out_first", False))
@@ -333,7 +336,7 @@ def config3(args):
                                   **direct["switch_latency_ms"]},
             "request_MiB": {"median": round(float(np.median(nblk)) * s.R / MiB, 1),
                             "max": round(float(nblk.max()) * s.R / MiB, 1)},
-            "kernels_and_copies": direct["kernels_and_copies"],
+            "kernels_and_copies": direct["kernels_and_copies"], "pool_has_timing_events": profiled,
             "compute_matmul_ms": {"what": "8192^3 bf16 matmul on the compute stream, %d per iteration" % per_iter,
                                   "alone": round(alone_ms, 4), "beside_swaps": direct["compute_ms_beside_swaps"],
                                   "slowdown": direct["compute_slowdown"]},

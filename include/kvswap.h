@@ -111,6 +111,13 @@ typedef enum {
                                        them).  Off by default: which copy engine a stream uses is the runtime's
                                        choice; the library arranges its calls so that the two streams got different
                                        ones in every process measured, and loses 10 % where they do not */
+#define KV_FLAG_NO_LAUNCH_EVENTS 2048u /* the gather and scatter launches of a swap of defer_min_bytes or more are
+                                        plain launches.  Default (flag off): they carry begin and end events of
+                                        their own, as under KV_FLAG_PROFILE, although nobody reads them: with
+                                        plain launches a swap-out and a swap-in that run at the same time shared
+                                        the link badly in some call patterns (one after the other instead of side
+                                        by side; a swap-out issued before the step's swap-in cost it 7 ms at the
+                                        median and 30 ms at the 99th percentile).  For comparison */
 #define KV_FLAG_NO_STRIDED_COPIES 256u /* one copy per run of adjacent host records, never a 2-D copy over
                                        several equal runs a constant stride apart (for comparison) */
 

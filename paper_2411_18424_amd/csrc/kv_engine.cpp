@@ -83,6 +83,8 @@ void reap(kv_pool* p) {
     o.packed = o.done = nullptr;
     for (hipEvent_t e : o.aux) put_event(p, e);
     o.aux.clear();
+    for (hipEvent_t e : o.timed) p->timing_pool.push_back(e);
+    o.timed.clear();
     p->ops_out.pop_front();
   }
   while (!p->ops_in.empty()) {
@@ -96,6 +98,8 @@ void reap(kv_pool* p) {
     o.aux.clear();
     for (hipEvent_t e : o.layer_ev) put_event(p, e);
     o.layer_ev.clear();
+    for (hipEvent_t e : o.timed) p->timing_pool.push_back(e);
+    o.timed.clear();
     p->ops_in.pop_front();
   }
   for (ByteRing* r : {&p->ring_out, &p->ring_in}) {
@@ -144,8 +148,19 @@ int32_t record(kv_pool* p, hipEvent_t ev, hipStream_t s) {
 
 // One pack launch over m blocks and the planes [p0, p0 + np) (np = 0: all planes); staging
 // holds [m][np][C].
+// op (may be null) and op_bytes: the swap this launch belongs to and the bytes it moves in all.
+// The pack launches of a swap of defer_min_bytes or more carry begin and end events of their own
+// also when nobody reads them.  Measured on config 3 (a swap-out and a swap-in per step beside
+// GEMMs), pools without KV_FLAG_PROFILE: with plain launches 90.8 GB/s, median 38.4 / p99 65 ms when
+// the step's swap-in is issued first, but 79.3 GB/s and 44.5 / 97.8 ms when the swap-out is, and in a
+// plain loop of one swap-in and one swap-out at a time the two directions took turns on the link
+// (56.6 GB/s in all, until a hipStreamSynchronize of the pool's streams).  With the events on the
+// launches 91.9 GB/s and 37 / 69 ms in either order, and 95.6 GB/s in the plain loop.  Events around
+// the copies instead change nothing.  A launch that has events gets a completion signal of its own,
+// which is presumably what the copy that follows it then waits for; what the runtime does without
+// one is not visible from here.  Small swaps keep the plain launch: the events cost them 5-10 us.
 int32_t launch_pack(kv_pool* p, bool scatter, char* staging, const Move* mv, int64_t m,
-                    int32_t p0 = 0, int32_t np = 0) {
+                    int32_t p0 = 0, int32_t np = 0, Op* op = nullptr, int64_t op_bytes = 0) {
   hipStream_t s = scatter ? p->s_scat : p->s_pack;
   (scatter ? p->st.scatter_launches : p->st.gather_launches)++;
   if (p->plan) return KV_OK;
@@ -166,6 +181,13 @@ int32_t launch_pack(kv_pool* p, bool scatter, char* staging, const Move* mv, int
     rc = get_timing_event(p, &e1);
     if (rc) return rc;
     p->prof.push_back({scatter ? 1 : 0, m * np * p->C, e0, e1});
+  } else if (op && p->launch_events && op_bytes >= p->defer_min) {
+    int32_t rc = get_timing_event(p, &e0);
+    if (rc) return rc;
+    op->timed.push_back(e0);
+    rc = get_timing_event(p, &e1);
+    if (rc) return rc;
+    op->timed.push_back(e1);
   }
   HIP_TRY(kv_launch_pack(scatter, a, p->unroll, p->variant, p->grid, s, e0, e1));
   return KV_OK;
@@ -526,7 +548,8 @@ int32_t enqueue_out(kv_pool* p, const std::vector<Move>& mv, const std::vector<h
     const int64_t off = g->off;
     for (int64_t k = 0; k < mp; k += p->launch_blocks) {
       int64_t ml = std::min<int64_t>(p->launch_blocks, mp - k);
-      if ((rc = launch_pack(p, false, at(r.base, off + k * p->R), &mv[(size_t)(i + k)], ml))) return rc;
+      if ((rc = launch_pack(p, false, at(r.base, off + k * p->R), &mv[(size_t)(i + k)], ml, 0, 0, op.get(), m * p->R)))
+        return rc;
     }
     hipEvent_t piece_ready = nullptr;
     if (defer) {
@@ -600,7 +623,7 @@ int32_t enqueue_in(kv_pool* p, const std::vector<Move>& mv, const std::vector<hi
     if ((rc = order_scatters())) return rc;
     for (int64_t k = 0; k < mp; k += p->launch_blocks) {
       int64_t ml = std::min<int64_t>(p->launch_blocks, mp - k);
-      if ((rc = launch_pack(p, true, at(sb, k * p->R), &mv[(size_t)(i + k)], ml))) return rc;
+      if ((rc = launch_pack(p, true, at(sb, k * p->R), &mv[(size_t)(i + k)], ml, 0, 0, op.get(), m * p->R))) return rc;
     }
     if ((rc = record(p, g->freed, p->s_scat))) return rc;
     g->recorded = true;

@@ -47,6 +47,7 @@ struct Op {
                                 // has its gathers enqueued and this set long before `issued`)
   bool deferred = false;        // the copy thread finishes the enqueue and sets `issued`
   std::vector<hipEvent_t> aux;  // hand-off events of this op, recycled when it is done
+  std::vector<hipEvent_t> timed;  // begin / end events attached to the pack launches of a large op (see launch_pack)
   std::vector<hipEvent_t> layer_ev;  // layer-wise swap-in: one per step of layer_step layers (null
                                      // entries in a plan-only pool); recycled when the op is done
   int32_t layer_step = 0;
@@ -190,6 +191,7 @@ struct kv_pool {
   bool defer_copies = true;   // off with KV_FLAG_NO_DEFER_COPIES
   int64_t defer_min = 0;      // smallest swap-out (bytes) whose copies are held back
   bool second_lane = false;   // KV_FLAG_SECOND_LANE
+  bool launch_events = true;  // off with KV_FLAG_NO_LAUNCH_EVENTS
   int device = 0;             // the device that was current when the pool was created
   bool strided_copies = true;  // equal runs a constant stride apart go out as rows of one 2-D copy
   int64_t slack = 32;

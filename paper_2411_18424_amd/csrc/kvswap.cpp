@@ -57,6 +57,7 @@ void destroy_pool(kv_pool* p) {
         if (o->packed) (void)hipEventDestroy(o->packed);
         if (o->done) (void)hipEventDestroy(o->done);
         for (hipEvent_t e : o->aux) (void)hipEventDestroy(e);
+        for (hipEvent_t e : o->timed) (void)hipEventDestroy(e);
         for (hipEvent_t e : o->layer_ev)
           if (e) (void)hipEventDestroy(e);
       }
@@ -128,6 +129,7 @@ int32_t kv_pool_create(const kv_pool_config_t* cfg, kv_pool_t** out) {
   p->defer_copies = (cfg->flags & KV_FLAG_NO_DEFER_COPIES) == 0;
   p->defer_min = cfg->defer_min_bytes > 0 ? cfg->defer_min_bytes : (16ll << 20);
   p->second_lane = (cfg->flags & KV_FLAG_SECOND_LANE) != 0;
+  p->launch_events = (cfg->flags & KV_FLAG_NO_LAUNCH_EVENTS) == 0;
   if (cfg->mapped_in_grid > 0) p->mapped_grid = cfg->mapped_in_grid;
   p->launch_blocks = kv_max_launch_blocks((uint32_t)C, (uint32_t)p->P, p->unroll, p->variant);
   // staging rings: defaults scale with the pool, capped at 4 GiB (out) and 1 GiB (in)

@@ -24,6 +24,7 @@ KV_FLAG_MAPPED_SWAP_IN, KV_FLAG_HOST_EVICT, KV_FLAG_MAPPED_SWAP_OUT, KV_FLAG_SCA
 KV_FLAG_NO_STRIDED_COPIES = 256
 KV_FLAG_NO_DEFER_COPIES = 512
 KV_FLAG_SECOND_LANE = 1024
+KV_FLAG_NO_LAUNCH_EVENTS = 2048
 KV_TASK_SWAP_OUT, KV_TASK_SWAP_IN, KV_TASK_SWAP_OUT_DELTA, KV_TASK_SWAP_IN_DELTA = 0, 1, 2, 3
 KV_WHERE_RUNNING, KV_WHERE_SWAPPED, KV_WHERE_ONGOING_SWAP_IN = 0, 1, 2
 KV_IT_FREE_OUT_BLOCKS = 1
