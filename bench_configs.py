@@ -572,6 +572,7 @@ def other_configs(args):
     a.mapped_swap_in = a.mapped_swap_out = a.four_streams = a.scatter_stream = a.no_strided_copies = False
     a.copy_chunk_mib = 0
     a.second_lane = False
+    a.no_profile = True  # config 3 in a pool as an application creates it: no timing events beyond the launches' own
     lane = copy.copy(a)
     lane.second_lane = True  # config 4 once more with KV_FLAG_SECOND_LANE
     out = {}
