@@ -158,7 +158,8 @@ int32_t record(kv_pool* p, hipEvent_t ev, hipStream_t s) {
 // launches 91.9 GB/s and 37 / 69 ms in either order, and 95.6 GB/s in the plain loop.  Events around
 // the copies instead change nothing.  A launch that has events gets a completion signal of its own,
 // which is presumably what the copy that follows it then waits for; what the runtime does without
-// one is not visible from here.  Small swaps keep the plain launch: the events cost them 5-10 us.
+// one is not visible from here.  Small swaps keep the plain launch: the events cost a swap-out on its
+// own 17-20 us and a swap-in 8 us, and pay for a pair issued together from about 8 MiB each.
 int32_t launch_pack(kv_pool* p, bool scatter, char* staging, const Move* mv, int64_t m,
                     int32_t p0 = 0, int32_t np = 0, Op* op = nullptr, int64_t op_bytes = 0) {
   hipStream_t s = scatter ? p->s_scat : p->s_pack;
