@@ -253,7 +253,11 @@ def main() -> int:
     log("workload: %s, pool %d blocks (%.1f GiB), %d requests, %d victims = %d blocks = %.2f GiB each way"
         % (s.name, s.n_blocks, s.n_blocks * s.R / GiB, len(work.tables), len(victims), nb, payload / GiB))
 
-    # ---- measured ceilings (before anything else is resident)
+    # ---- measured ceilings (before anything else is resident; not while the driver still clears the device memory
+    #      of a process that has just ended: the two-way probe then reads 60 GB/s instead of 97)
+    import bench_configs
+    settled_first = bench_configs.settle(torch)
+    log("settle (before the probes):", settled_first)
     link_d2h = kv.kv_link_probe(GiB, 0, 10)
     link_h2d = kv.kv_link_probe(GiB, 1, 10)
     link_duplex = kv.kv_link_probe(GiB, 2, 5)
@@ -277,7 +281,6 @@ def main() -> int:
                      copy_chunk_bytes=args.copy_chunk_mib << 20, max_piece_bytes=args.max_piece_mib << 20)
     cur = [work.tables[v] for v in victims]
     nxt = list(work.resume_tables)
-    import bench_configs
     settled = bench_configs.settle(torch)  # not while the driver still clears a previous process's device memory
     log("settle:", settled)
 
@@ -540,7 +543,7 @@ def main() -> int:
                                        if mgr_stats else None),
         },
         "device_state": dev_state,
-        "settle": settled,
+        "settle": settled, "settle_before_probes": {k: settled_first[k] for k in ("waited_s", "slow_probes", "probes")},
         "streams": 4 if args.four_streams else 3 if args.scatter_stream else 2,
         "swap_out_copies": "enqueued inside the call" if args.no_defer_copies
                            else "held back until their gathers are done (copy thread)",

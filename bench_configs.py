@@ -226,10 +226,12 @@ def config3(args):
     rng = synth.rng_for(3)
     nblk = synth.blocks_for(rng.integers(512, 4097, size=n_pre), s.block_size)
     host_bytes = int((lag + 2) * (256 + 40)) * s.R
-    # 1 GiB each way at once, nothing else running.  Measured at the start of the process: the runtime keeps a
-    # stream on the copy engine it used last, and in a process that has already run other pools the probe's two
-    # fresh streams can come up on one engine (it then reads 60 GB/s, less than the swaps below reach)
-    two_way_peak = getattr(args, "two_way_peak", 0) or kv.kv_link_probe(GiB, 2, 5)
+    # 1 GiB each way at once, nothing else running - and not while the driver still clears the device memory of a
+    # process that has just ended (the probe then reads 60 GB/s, less than the swaps below reach): wait first
+    two_way_peak = getattr(args, "two_way_peak", 0)
+    if not two_way_peak:
+        settle(torch)
+        two_way_peak = kv.kv_link_probe(GiB, 2, 5)
     profiled = not getattr(args, "no_profile", False)  # timing events on every launch and copy, for the rates below
     gpu, pool = _pool(kv, torch, s, host_bytes, copy_chunk_bytes=args.copy_chunk_mib << 20,
                       flags=_flags(args, kv, kv.KV_FLAG_PROFILE if profiled else 0))
